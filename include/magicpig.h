@@ -1,0 +1,135 @@
+/*
+ * magicpig.h - C ABI of the MI355X (gfx950) library for LSH-sampled decode attention,
+ * the method of "MagicPIG: LSH Sampling for Efficient LLM Generation" (arXiv 2410.16179).
+ *
+ * The calls follow the paper's problem statement (Algorithm 1 "MagicPIG Decoding"):
+ * inputs K, V in R^{n x d}, q in R^{1 x d}, random projectors W in R^{d x (K*L)}, a hash
+ * structure over the cached keys, and a static set T of sink + local tokens.  Here the
+ * hash structure is the array of packed SimHash codes of all keys, kept in HBM and
+ * scanned on every decode step; the sample S is the same set a hash-table lookup gives.
+ *
+ * Conventions for every call
+ *  - `params` is HOST memory, read during the call only.  Every other pointer is a
+ *    DEVICE pointer owned by the caller (the library allocates and frees nothing and
+ *    keeps no state between calls).  `workspace` is caller-owned device scratch of at
+ *    least magicpig_workspace_bytes(params) bytes, 256-byte aligned; its contents need
+ *    not be preserved or initialised between calls, and two calls that share it must be
+ *    ordered on one stream.
+ *  - `hip_stream` is a hipStream_t (NULL = default stream).  Calls enqueue work and
+ *    return without synchronising.
+ *  - Return value: MAGICPIG_OK or a negative status.  Arguments are validated before any
+ *    GPU call, so INVALID_ARG / UNSUPPORTED / WORKSPACE_TOO_SMALL can be observed on a
+ *    host without a GPU.  No C++ exception crosses this boundary.
+ *  - Tensors: q [batch, n_q_heads, 128]; K/V cache [batch, n_kv_heads, n, 128] addressed
+ *    through element strides (innermost dimension contiguous); W [128, K*L] row-major,
+ *    column t*K + b being hyperplane b of table t; mu [batch, n_kv_heads, 128] float32.
+ *    q, K, V, W share the element type `dtype` (bf16 or float32).
+ *  - Grouped-query attention: query head h uses KV head h / (n_q_heads / n_kv_heads).
+ */
+#ifndef MAGICPIG_H
+#define MAGICPIG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { MAGICPIG_BF16 = 0, MAGICPIG_FP32 = 1 };
+
+enum {
+  MAGICPIG_OK = 0,
+  MAGICPIG_INVALID_ARG = -1,         /* null pointer, negative size, heads not divisible ... */
+  MAGICPIG_UNSUPPORTED = -2,         /* head_dim != 128, K or L out of range, unknown dtype  */
+  MAGICPIG_WORKSPACE_TOO_SMALL = -3,
+  MAGICPIG_LAUNCH_FAILED = -4        /* a HIP call failed; see magicpig_last_hip_error()      */
+};
+
+typedef struct magicpig_params {
+  int32_t batch, n_q_heads, n_kv_heads;
+  int32_t head_dim;   /* must be 128 */
+  int32_t K;          /* sign bits per table, 1..16 */
+  int32_t L;          /* tables, 1..512 */
+  int32_t min_hits;   /* a key is sampled iff it collides in >= min_hits tables; the paper
+                         uses 2 (Sec. 4.3).  0: every eligible key is sampled with u = 1,
+                         which makes the result exact attention. */
+  int32_t n_sink;     /* first n_sink and last n_local keys form the static set T, attended */
+  int32_t n_local;    /* exactly and excluded from sampling (Sec. 4.4 "On-device cache")    */
+  int32_t dtype;      /* MAGICPIG_BF16 | MAGICPIG_FP32: element type of q, K, V, W */
+  int64_t n_ctx;      /* keys per sequence seen by the decode step (all sequences alike)    */
+  int64_t n_cap;      /* key capacity of the code buffer per (batch, KV head), >= n_ctx     */
+  int64_t k_stride_b, k_stride_h, k_stride_n;   /* element strides of the K cache */
+  int64_t v_stride_b, v_stride_h, v_stride_n;   /* element strides of the V cache */
+} magicpig_params;
+
+/* ---- packed code layout (part of the contract: the caller stores codes between calls) ----
+ * A key's code is NW = K * ceil(L/32) 32-bit words.  Word x = w*K + b holds, in bit beta,
+ * the sign bit b (SimHash, Sec. 2.2: 1 iff the projection is >= 0) of table t = 32*w + beta;
+ * bits of tables t >= L are 0 in key codes and 1 in query codes, so they never collide.
+ * Key codes are stored in blocks of 64 consecutive keys of one (batch, KV head):
+ * word x of key i lives at u32 index
+ *     ((b*n_kv_heads + g)*ceil(n_cap/64) + i/64) * 64*NW + slot(x, i%64),
+ *     slot(x, r) = (x/4)*256 + r*4 + x%4              for x <  4*(NW/4),
+ *                = (NW/4)*256 + r*(NW%4) + x%4        otherwise,
+ * i.e. each lane of a 64-wide wavefront reads its key's words as 16-byte vectors and a
+ * wavefront reads a contiguous 256*NW-byte block.  magicpig_key_code_index() evaluates
+ * this formula.  Query codes are [batch, n_q_heads, NW] row-major.
+ */
+size_t magicpig_code_words_per_key(const magicpig_params* params);
+size_t magicpig_key_code_bytes(const magicpig_params* params);    /* whole key-code buffer  */
+size_t magicpig_query_code_bytes(const magicpig_params* params);
+/* u32 index of word x of key i of (b, g) in the key-code buffer; (size_t)-1 if out of range */
+size_t magicpig_key_code_index(const magicpig_params* params, int32_t b, int32_t g,
+                               int64_t key, int32_t word);
+/* Scratch needed by any of the calls below for these params (0 on invalid params). */
+size_t magicpig_workspace_bytes(const magicpig_params* params);
+
+/* Key centering vector (Sec. 4.3 "Data pre-processing"): mu[b,g,:] = (1/n_ctx) sum_i k_i over
+ * keys [0, n_ctx) of each (batch, KV head), accumulated in float32 per row group and float64
+ * across groups, rounded to float32.  mu_out [batch, n_kv_heads, 128] float32. */
+int magicpig_key_mean(const magicpig_params* params, const void* K_cache, float* mu_out,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* SimHash codes of cached keys (Sec. 4.3 "Hash function selection"; Algorithm 1 input HT):
+ * for keys first_key <= i < first_key + n_keys of every (batch, KV head),
+ *   bit(i, t, b) = [ sum_d (k_{i,d} - mu_d) * W_{d, t*K+b} >= 0 ],
+ * the sign being that of the exact real sum over the stored values (independent of
+ * summation order).  mu may be NULL (no centering).  Requires first_key + n_keys <= n_cap;
+ * n_ctx is not consulted, so keys can be appended with a frozen mu.  Writes only the words
+ * of those keys. */
+int magicpig_hash_keys(const magicpig_params* params, const void* K_cache, const float* mu,
+                       const void* W, int64_t first_key, int64_t n_keys, uint32_t* key_codes,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* SimHash codes of the decode queries (Algorithm 1 "Encode(q, W)"); queries are not centered. */
+int magicpig_hash_query(const magicpig_params* params, const void* q, const void* W,
+                        uint32_t* q_codes, void* workspace, size_t workspace_bytes,
+                        void* hip_stream);
+
+/* One decode step of sampled attention (Algorithm 1; Eq. "lsh sampling probability" and Eq.
+ * "close form"): for every query head h with KV head g,
+ *   count(h,i) = #{ t : code_q(h,t) == code_k(g,i,t) },
+ *   T = [0,n_sink) U [n_ctx-n_local, n_ctx)   (all keys if n_ctx <= n_sink + n_local),
+ *   S_h = { i not in T : count(h,i) >= min_hits },
+ *   p_i = 1 - arccos(cos(q, k_i - mu))/pi,  u_i = P[Binomial(L, p_i^K) >= min_hits],
+ *   out_h = softmax_{i in S_h U T}( q.k_i/sqrt(128) - [i in S_h] log u_i ) V.
+ * out [batch, n_q_heads, 128] float32 (zero vector when S_h U T is empty).  mu may be NULL.
+ * Optional debug outputs (NULL in production): dbg_counts [batch, n_q_heads, n_ctx] uint16;
+ * dbg_cand [batch, n_q_heads, dbg_cand_cap] int32 receives S_h in unspecified order and
+ * dbg_ncand [batch, n_q_heads] int32 its size (entries beyond the capacity are counted but
+ * not stored; dbg_ncand must be zeroed by the caller). */
+int magicpig_sampled_attention(const magicpig_params* params, const void* q, const void* K_cache,
+                               const void* V_cache, const float* mu, const uint32_t* key_codes,
+                               const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
+                               int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+const char* magicpig_status_string(int status);
+/* Text of the HIP error behind the most recent MAGICPIG_LAUNCH_FAILED on this thread. */
+const char* magicpig_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MAGICPIG_H */

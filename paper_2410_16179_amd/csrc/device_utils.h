@@ -1,0 +1,73 @@
+// Small device helpers shared by the gfx950 kernels: row fragment loads and
+// wavefront / 16-lane reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mp {
+
+// Eight consecutive elements of a 128-element row, as stored (bf16: 16 bytes, float32: 32).
+struct Frag {
+  uint4 a, b;
+};
+
+template <bool FP32>
+__device__ inline void frag_load(const void* base, int64_t elem, Frag& f) {
+  if constexpr (FP32) {
+    const uint4* p = reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(base) + elem);
+    f.a = p[0];
+    f.b = p[1];
+  } else {
+    f.a = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(base) + elem);
+  }
+}
+
+template <bool FP32>
+__device__ inline void frag_zero(Frag& f) {
+  f.a = make_uint4(0, 0, 0, 0);
+  if constexpr (FP32) f.b = make_uint4(0, 0, 0, 0);
+}
+
+template <bool FP32>
+__device__ inline void frag_to_float(const Frag& f, float (&v)[8]) {
+  if constexpr (FP32) {
+    v[0] = __uint_as_float(f.a.x); v[1] = __uint_as_float(f.a.y);
+    v[2] = __uint_as_float(f.a.z); v[3] = __uint_as_float(f.a.w);
+    v[4] = __uint_as_float(f.b.x); v[5] = __uint_as_float(f.b.y);
+    v[6] = __uint_as_float(f.b.z); v[7] = __uint_as_float(f.b.w);
+  } else {
+    const uint32_t u[4] = {f.a.x, f.a.y, f.a.z, f.a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(u[i] << 16);
+      v[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+    }
+  }
+}
+
+// Sum over the 16 lanes of a DPP row (rotate-and-add); every lane of the row gets the total.
+template <int N>
+__device__ inline float dpp_row_ror(float v) {
+  const int r = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xf, 0xf, false);
+  return __builtin_bit_cast(float, r);
+}
+__device__ inline float row_sum16(float v) {
+  v += dpp_row_ror<8>(v);
+  v += dpp_row_ror<4>(v);
+  v += dpp_row_ror<2>(v);
+  v += dpp_row_ror<1>(v);
+  return v;
+}
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+}  // namespace mp

@@ -1,0 +1,102 @@
+// Direct SimHash coding in float64 with an exact fallback (Sec. 2.2; Algorithm 1 "Encode").
+//
+// Used for the decode queries (a few thousand projections), for float32 inputs, and as the
+// reference-accurate path for bf16 keys when the matrix-core kernel cannot be used.  Every
+// projection is accumulated in float64 from exact products; results inside the float64
+// error bound are re-summed exactly (exact_dot.h), so the bits do not depend on
+// summation order.
+#include "mp_common.h"
+#include "exact_dot.h"
+#include <hip/hip_bf16.h>
+
+namespace mp {
+
+__device__ inline double load_elem(const void* p, int64_t idx, int is_fp32) {
+  if (is_fp32) return (double)reinterpret_cast<const float*>(p)[idx];
+  const uint32_t b = reinterpret_cast<const uint16_t*>(p)[idx];
+  return (double)__uint_as_float(b << 16);
+}
+
+// One wavefront codes two vectors at a time: lanes 0..31 take tables 32w..32w+31 of the
+// first, lanes 32..63 of the second; a ballot turns the 64 sign tests into two code words.
+__global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
+  __shared__ long long limbs[4][kLimbs];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (lane < kLimbs) limbs[wave][lane] = 0;
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+
+  const int64_t row0 = ((int64_t)blockIdx.x * 4 + wave) * 2;
+  if (row0 >= a.total_rows) return;
+  const int half = lane >> 5, beta = lane & 31;
+  const int64_t row = row0 + half;
+  const bool row_ok = row < a.total_rows;
+  const int64_t rr = row_ok ? row : row0;
+  const int64_t unit = rr / a.n_keys;
+  const int64_t key = a.first_key + rr % a.n_keys;
+  const int64_t xbase = (unit / a.n_kv_heads) * a.stride_b + (unit % a.n_kv_heads) * a.stride_h +
+                        key * a.stride_n;
+  const float* mu = a.mu ? a.mu + unit * kHeadDim : nullptr;
+  const int ncol = a.K * a.L;
+  const int Wd = table_words(a.L);
+
+  for (int x = 0; x < a.NW; ++x) {
+    const int w = x / a.K, b = x % a.K;
+    const int t = 32 * w + beta;
+    const bool col_ok = t < a.L;
+    const int j = col_ok ? t * a.K + b : 0;
+    double s = 0.0, mag = 0.0;
+    for (int d = 0; d < kHeadDim; ++d) {
+      const double wv = load_elem(a.W, (int64_t)d * ncol + j, a.is_fp32);
+      const double xv = load_elem(a.X, xbase + d, a.is_fp32);
+      const double p = xv * wv;
+      s += p;
+      mag += fabs(p);
+      if (mu) {
+        const double pm = (double)mu[d] * wv;
+        s -= pm;
+        mag += fabs(pm);
+      }
+    }
+    bool bit = s >= 0.0;
+    bool unsure = col_ok && row_ok && mag > 0.0 && fabs(s) <= kF64Slack * mag;
+    uint64_t pending = __ballot(unsure);
+    while (pending) {
+      const int src = __ffsll((unsigned long long)pending) - 1;
+      const int64_t sx = __shfl((int)(xbase >> 32), src);   // 64-bit broadcast in two halves
+      const int64_t sxl = (uint32_t)__shfl((int)(xbase & 0xffffffff), src);
+      const int64_t xb = (sx << 32) | sxl;
+      const int sj = __shfl(j, src);
+      const int64_t su = ((int64_t)__shfl((int)(unit >> 32), src) << 32) |
+                         (uint32_t)__shfl((int)(unit & 0xffffffff), src);
+      const float* smu = a.mu ? a.mu + su * kHeadDim : nullptr;
+      const bool r = exact_sign_nonneg_wave(
+          limbs[wave],
+          [&](int d) { return load_elem(a.X, xb + d, a.is_fp32); },
+          [&](int d) { return load_elem(a.W, (int64_t)d * ncol + sj, a.is_fp32); },
+          [&](int d) { return smu ? (double)smu[d] : 0.0; }, smu != nullptr);
+      if (lane == src) bit = r;
+      pending &= pending - 1;
+    }
+    const uint64_t m = __ballot(bit && col_ok);
+    uint32_t word = half ? (uint32_t)(m >> 32) : (uint32_t)m;
+    if (a.query_layout && (w == Wd - 1) && (a.L & 31)) word |= ~0u << (a.L & 31);
+    if (beta == 0 && row_ok) {
+      if (a.query_layout) {
+        a.codes[row * a.NW + x] = word;
+      } else {
+        const int64_t blk = unit * a.blocks_cap + key / kBlockKeys;
+        a.codes[blk * (kBlockKeys * (int64_t)a.NW) + slot_in_block(a.NW, x, (int)(key % kBlockKeys))] = word;
+      }
+    }
+  }
+}
+
+hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s) {
+  if (a.total_rows <= 0) return hipSuccess;
+  const int64_t groups = (a.total_rows + 7) / 8;
+  hipLaunchKernelGGL(hash_direct_kernel, dim3((unsigned)groups), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace mp

@@ -1,0 +1,71 @@
+// Key centering vector mu = (1/n) sum_i k_i per (batch, KV head) (Sec. 4.3 "Data
+// pre-processing").  HBM-bound streaming read of the K cache: each thread sums up to
+// rows_per_chunk/16 rows of one 8-element column group in float32, the workgroup and the
+// chunks are combined in float64 in a fixed order, so the result is reproducible.
+#include "mp_common.h"
+
+namespace mp {
+
+template <bool FP32>
+__device__ inline void load8(const void* base, int64_t elem, float (&v)[8]) {
+  if constexpr (FP32) {
+    const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + elem);
+    const float4 a = p[0], b = p[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  } else {
+    const uint4 r = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(base) + elem);
+    const uint32_t u[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(u[i] << 16);
+      v[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+    }
+  }
+}
+
+template <bool FP32>
+__global__ __launch_bounds__(256) void key_mean_partial_kernel(MeanArgs a) {
+  __shared__ double red[16][kHeadDim];
+  const int unit = blockIdx.y, chunk = blockIdx.x;
+  const int cg = threadIdx.x & 15, rl = threadIdx.x >> 4;
+  const int64_t base = (int64_t)(unit / a.n_kv_heads) * a.stride_b + (int64_t)(unit % a.n_kv_heads) * a.stride_h;
+  const int64_t r0 = (int64_t)chunk * a.rows_per_chunk;
+  const int64_t r1 = r0 + a.rows_per_chunk < a.n ? r0 + a.rows_per_chunk : a.n;
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int64_t i = r0 + rl; i < r1; i += 16) {
+    float v[8];
+    load8<FP32>(a.Kc, base + i * a.stride_n + cg * 8, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += v[e];
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[rl][cg * 8 + e] = (double)acc[e];
+  __syncthreads();
+  if (threadIdx.x < kHeadDim) {
+    double s = 0.0;
+    for (int r = 0; r < 16; ++r) s += red[r][threadIdx.x];
+    a.partial[((int64_t)unit * a.nchunk + chunk) * kHeadDim + threadIdx.x] = s;
+  }
+}
+
+__global__ __launch_bounds__(kHeadDim) void key_mean_final_kernel(MeanArgs a) {
+  const int unit = blockIdx.x;
+  double s = 0.0;
+  for (int c = 0; c < a.nchunk; ++c) s += a.partial[((int64_t)unit * a.nchunk + c) * kHeadDim + threadIdx.x];
+  a.mu[(int64_t)unit * kHeadDim + threadIdx.x] = a.n > 0 ? (float)(s / (double)a.n) : 0.f;
+}
+
+hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s) {
+  if (a.units <= 0) return hipSuccess;
+  if (a.nchunk > 0) {
+    dim3 grid((unsigned)a.nchunk, (unsigned)a.units);
+    if (a.is_fp32) hipLaunchKernelGGL(key_mean_partial_kernel<true>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(key_mean_partial_kernel<false>, grid, dim3(256), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(key_mean_final_kernel, dim3((unsigned)a.units), dim3(kHeadDim), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace mp

@@ -1,0 +1,206 @@
+// C ABI of the library: argument validation, workspace carving and kernel launches.
+// Validation touches no HIP call so that it can be exercised on a host without a GPU.
+#include "mp_common.h"
+
+#include <string>
+
+namespace {
+
+thread_local std::string g_last_hip_error;
+
+int fail_hip(hipError_t e) {
+  g_last_hip_error = hipGetErrorString(e);
+  return MAGICPIG_LAUNCH_FAILED;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+int check_params(const magicpig_params* p) {
+  if (!p) return MAGICPIG_INVALID_ARG;
+  if (p->batch < 0 || p->n_q_heads <= 0 || p->n_kv_heads <= 0) return MAGICPIG_INVALID_ARG;
+  if (p->n_q_heads % p->n_kv_heads != 0) return MAGICPIG_INVALID_ARG;
+  if (p->n_ctx < 0 || p->n_cap < p->n_ctx) return MAGICPIG_INVALID_ARG;
+  if (p->n_sink < 0 || p->n_local < 0 || p->min_hits < 0) return MAGICPIG_INVALID_ARG;
+  if (p->head_dim != mp::kHeadDim) return MAGICPIG_UNSUPPORTED;
+  if (p->K < 1 || p->K > 16 || p->L < 1 || p->L > 512) return MAGICPIG_UNSUPPORTED;
+  if (p->dtype != MAGICPIG_BF16 && p->dtype != MAGICPIG_FP32) return MAGICPIG_UNSUPPORTED;
+  const int G = p->n_q_heads / p->n_kv_heads;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return MAGICPIG_UNSUPPORTED;
+  if (p->n_cap > (int64_t)1 << 31) return MAGICPIG_UNSUPPORTED;
+  return MAGICPIG_OK;
+}
+
+// strides must keep every 8-element row fragment 16-byte aligned and rows in bounds
+int check_strides(int64_t sb, int64_t sh, int64_t sn) {
+  if (sb < 0 || sh < 0 || sn < mp::kHeadDim) return MAGICPIG_INVALID_ARG;
+  if ((sb | sh | sn) & 7) return MAGICPIG_UNSUPPORTED;
+  return MAGICPIG_OK;
+}
+
+constexpr int64_t kMeanRowsPerChunk = 1024;
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+size_t ws_mean(const magicpig_params* p) {
+  const int64_t units = (int64_t)p->batch * p->n_kv_heads;
+  const int64_t nchunk = (p->n_ctx + kMeanRowsPerChunk - 1) / kMeanRowsPerChunk;
+  return align256((size_t)(units * nchunk * mp::kHeadDim) * sizeof(double));
+}
+
+size_t ws_attention(const magicpig_params* p) {
+  int cb, nc;
+  mp::attention_chunking(p->batch * p->n_kv_heads, p->n_ctx, &cb, &nc);
+  return align256((size_t)p->batch * p->n_q_heads * nc * mp::kPartialStride * sizeof(float));
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t magicpig_code_words_per_key(const magicpig_params* p) {
+  if (check_params(p) != MAGICPIG_OK) return 0;
+  return (size_t)mp::code_words(p->K, p->L);
+}
+
+size_t magicpig_key_code_bytes(const magicpig_params* p) {
+  if (check_params(p) != MAGICPIG_OK) return 0;
+  return (size_t)p->batch * p->n_kv_heads * (size_t)mp::key_blocks(p->n_cap) * mp::kBlockKeys *
+         mp::code_words(p->K, p->L) * sizeof(uint32_t);
+}
+
+size_t magicpig_query_code_bytes(const magicpig_params* p) {
+  if (check_params(p) != MAGICPIG_OK) return 0;
+  return (size_t)p->batch * p->n_q_heads * mp::code_words(p->K, p->L) * sizeof(uint32_t);
+}
+
+size_t magicpig_key_code_index(const magicpig_params* p, int32_t b, int32_t g, int64_t key, int32_t word) {
+  if (check_params(p) != MAGICPIG_OK) return (size_t)-1;
+  const int NW = mp::code_words(p->K, p->L);
+  if (b < 0 || b >= p->batch || g < 0 || g >= p->n_kv_heads || key < 0 || key >= p->n_cap ||
+      word < 0 || word >= NW)
+    return (size_t)-1;
+  const int64_t blk = ((int64_t)b * p->n_kv_heads + g) * mp::key_blocks(p->n_cap) + key / mp::kBlockKeys;
+  return (size_t)(blk * mp::kBlockKeys * NW + mp::slot_in_block(NW, word, (int)(key % mp::kBlockKeys)));
+}
+
+size_t magicpig_workspace_bytes(const magicpig_params* p) {
+  if (check_params(p) != MAGICPIG_OK) return 0;
+  size_t a = ws_mean(p), b = ws_attention(p);
+  size_t m = a > b ? a : b;
+  return m < 256 ? 256 : m;
+}
+
+int magicpig_key_mean(const magicpig_params* p, const void* K_cache, float* mu_out, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  int st = check_params(p);
+  if (st != MAGICPIG_OK) return st;
+  if ((st = check_strides(p->k_stride_b, p->k_stride_h, p->k_stride_n)) != MAGICPIG_OK) return st;
+  if (!mu_out || !workspace || (!K_cache && p->n_ctx > 0 && p->batch > 0)) return MAGICPIG_INVALID_ARG;
+  if (!aligned16(K_cache) || !aligned16(workspace)) return MAGICPIG_INVALID_ARG;
+  if (workspace_bytes < ws_mean(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
+  mp::MeanArgs a{};
+  a.Kc = K_cache; a.mu = mu_out; a.partial = reinterpret_cast<double*>(workspace);
+  a.is_fp32 = p->dtype == MAGICPIG_FP32;
+  a.n_kv_heads = p->n_kv_heads; a.units = p->batch * p->n_kv_heads; a.n = p->n_ctx;
+  a.rows_per_chunk = kMeanRowsPerChunk;
+  a.nchunk = (int)((p->n_ctx + kMeanRowsPerChunk - 1) / kMeanRowsPerChunk);
+  a.stride_b = p->k_stride_b; a.stride_h = p->k_stride_h; a.stride_n = p->k_stride_n;
+  const hipError_t e = mp::launch_key_mean(a, reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
+}
+
+int magicpig_hash_keys(const magicpig_params* p, const void* K_cache, const float* mu, const void* W,
+                       int64_t first_key, int64_t n_keys, uint32_t* key_codes, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
+  int st = check_params(p);
+  if (st != MAGICPIG_OK) return st;
+  if ((st = check_strides(p->k_stride_b, p->k_stride_h, p->k_stride_n)) != MAGICPIG_OK) return st;
+  if (first_key < 0 || n_keys < 0 || first_key + n_keys > p->n_cap) return MAGICPIG_INVALID_ARG;
+  if (!W || !key_codes || !workspace || (!K_cache && n_keys > 0 && p->batch > 0)) return MAGICPIG_INVALID_ARG;
+  if (!aligned16(K_cache) || !aligned16(W) || !aligned16(key_codes) || !aligned16(workspace) ||
+      (mu && !aligned16(mu)))
+    return MAGICPIG_INVALID_ARG;
+  if (workspace_bytes < magicpig_workspace_bytes(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
+  mp::HashDirectArgs a{};
+  a.X = K_cache; a.W = W; a.mu = mu; a.codes = key_codes;
+  a.is_fp32 = p->dtype == MAGICPIG_FP32;
+  a.K = p->K; a.L = p->L; a.NW = mp::code_words(p->K, p->L);
+  a.query_layout = 0;
+  a.n_keys = n_keys > 0 ? n_keys : 1; a.first_key = first_key;
+  a.n_kv_heads = p->n_kv_heads;
+  a.stride_b = p->k_stride_b; a.stride_h = p->k_stride_h; a.stride_n = p->k_stride_n;
+  a.blocks_cap = mp::key_blocks(p->n_cap);
+  a.total_rows = (int64_t)p->batch * p->n_kv_heads * n_keys;
+  const hipError_t e = mp::launch_hash_direct(a, reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
+}
+
+int magicpig_hash_query(const magicpig_params* p, const void* q, const void* W, uint32_t* q_codes,
+                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int st = check_params(p);
+  if (st != MAGICPIG_OK) return st;
+  if (!W || !q_codes || !workspace || (!q && p->batch > 0)) return MAGICPIG_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(W) || !aligned16(q_codes) || !aligned16(workspace)) return MAGICPIG_INVALID_ARG;
+  if (workspace_bytes < magicpig_workspace_bytes(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
+  mp::HashDirectArgs a{};
+  a.X = q; a.W = W; a.mu = nullptr; a.codes = q_codes;
+  a.is_fp32 = p->dtype == MAGICPIG_FP32;
+  a.K = p->K; a.L = p->L; a.NW = mp::code_words(p->K, p->L);
+  a.query_layout = 1;
+  a.total_rows = (int64_t)p->batch * p->n_q_heads;
+  a.n_keys = a.total_rows > 0 ? a.total_rows : 1; a.first_key = 0;   // one unit holding every query row
+  a.n_kv_heads = 1;
+  a.stride_b = 0; a.stride_h = 0; a.stride_n = mp::kHeadDim;
+  a.blocks_cap = 0;
+  const hipError_t e = mp::launch_hash_direct(a, reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
+}
+
+int magicpig_sampled_attention(const magicpig_params* p, const void* q, const void* K_cache,
+                               const void* V_cache, const float* mu, const uint32_t* key_codes,
+                               const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
+                               int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int st = check_params(p);
+  if (st != MAGICPIG_OK) return st;
+  if ((st = check_strides(p->k_stride_b, p->k_stride_h, p->k_stride_n)) != MAGICPIG_OK) return st;
+  if ((st = check_strides(p->v_stride_b, p->v_stride_h, p->v_stride_n)) != MAGICPIG_OK) return st;
+  const bool has_keys = p->n_ctx > 0 && p->batch > 0;
+  if (!out || !workspace || (!q && p->batch > 0)) return MAGICPIG_INVALID_ARG;
+  if (has_keys && (!K_cache || !V_cache || !key_codes || !q_codes)) return MAGICPIG_INVALID_ARG;
+  if ((dbg_cand != nullptr) != (dbg_ncand != nullptr) || dbg_cand_cap < 0) return MAGICPIG_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(K_cache) || !aligned16(V_cache) || !aligned16(key_codes) ||
+      !aligned16(q_codes) || !aligned16(out) || !aligned16(workspace) || (mu && !aligned16(mu)))
+    return MAGICPIG_INVALID_ARG;
+  if (workspace_bytes < ws_attention(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
+  mp::AttnArgs a{};
+  a.q = q; a.Kc = K_cache; a.Vc = V_cache; a.mu = mu; a.kcodes = key_codes; a.qcodes = q_codes;
+  a.partial = reinterpret_cast<float*>(workspace); a.out = out;
+  a.dbg_counts = dbg_counts; a.dbg_cand = dbg_cand; a.dbg_ncand = dbg_ncand; a.dbg_cand_cap = dbg_cand_cap;
+  a.is_fp32 = p->dtype == MAGICPIG_FP32;
+  a.B = p->batch; a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.K = p->K; a.L = p->L;
+  a.Wd = mp::table_words(p->L); a.NW = mp::code_words(p->K, p->L);
+  a.tau = p->min_hits; a.n_sink = p->n_sink; a.n_local = p->n_local;
+  a.n = p->n_ctx; a.blocks_cap = mp::key_blocks(p->n_cap);
+  a.ks_b = p->k_stride_b; a.ks_h = p->k_stride_h; a.ks_n = p->k_stride_n;
+  a.vs_b = p->v_stride_b; a.vs_h = p->v_stride_h; a.vs_n = p->v_stride_n;
+  mp::attention_chunking(p->batch * p->n_kv_heads, p->n_ctx, &a.chunk_blocks, &a.nchunk);
+  a.scale = 0.08838834764831845f;   // 1/sqrt(128)
+  const hipError_t e = mp::launch_sampled_attention(a, reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
+}
+
+const char* magicpig_status_string(int status) {
+  switch (status) {
+    case MAGICPIG_OK: return "ok";
+    case MAGICPIG_INVALID_ARG: return "invalid argument";
+    case MAGICPIG_UNSUPPORTED: return "unsupported configuration";
+    case MAGICPIG_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case MAGICPIG_LAUNCH_FAILED: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+const char* magicpig_last_hip_error(void) { return g_last_hip_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+// Shared declarations of the gfx950 library for LSH-sampled decode attention.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "magicpig.h"
+
+namespace mp {
+
+constexpr int kHeadDim = 128;
+constexpr int kBlockKeys = 64;   // keys per code block = lanes per wavefront
+constexpr int kNumCU = 256;      // MI355X
+
+// ---- packed code layout (documented in magicpig.h) ----
+__host__ __device__ inline int table_words(int L) { return (L + 31) >> 5; }
+__host__ __device__ inline int code_words(int K, int L) { return K * table_words(L); }
+__host__ __device__ inline int64_t key_blocks(int64_t n) { return (n + kBlockKeys - 1) / kBlockKeys; }
+__host__ __device__ inline int slot_in_block(int NW, int x, int r) {
+  const int full = NW >> 2, rem = NW & 3;
+  const int gq = x >> 2;
+  return gq < full ? gq * 256 + r * 4 + (x & 3) : full * 256 + r * rem + (x & 3);
+}
+
+// Launch description of the direct (float64 + exact fallback) SimHash kernel.
+struct HashDirectArgs {
+  const void* X;        // vectors to hash
+  const void* W;        // [128, K*L] row-major
+  const float* mu;      // per (b,g) [128] or nullptr
+  uint32_t* codes;
+  int is_fp32;          // element type of X and W
+  int K, L, NW;
+  int query_layout;     // 1: codes[row][NW], pad bits 1;  0: blocked key layout, pad bits 0
+  // key addressing: row r in [0, units*n_keys): unit = r / n_keys, i = first_key + r % n_keys
+  int64_t n_keys, first_key;
+  int n_kv_heads;       // unit = b*n_kv_heads + g
+  int64_t stride_b, stride_h, stride_n;   // element strides (query layout: stride_n = 128, others 0)
+  int64_t blocks_cap;   // code blocks per unit
+  int64_t total_rows;
+};
+
+struct MeanArgs {
+  const void* Kc; float* mu; double* partial;
+  int is_fp32; int n_kv_heads; int units; int64_t n; int nchunk; int64_t rows_per_chunk;
+  int64_t stride_b, stride_h, stride_n;
+};
+
+struct AttnArgs {
+  const void* q; const void* Kc; const void* Vc; const float* mu;
+  const uint32_t* kcodes; const uint32_t* qcodes;
+  float* partial; float* out;
+  uint16_t* dbg_counts; int32_t* dbg_cand; int32_t* dbg_ncand; int64_t dbg_cand_cap;
+  int is_fp32;
+  int B, Hq, Hkv, K, L, Wd, NW, tau, n_sink, n_local;
+  int64_t n, blocks_cap;
+  int64_t ks_b, ks_h, ks_n, vs_b, vs_h, vs_n;
+  int chunk_blocks, nchunk;
+  float scale;
+};
+
+constexpr int kPartialStride = 132;   // 128 output elements, running max, running sum, pad
+constexpr int kAttnWaves = 4;
+constexpr int kMaxChunkBlocks = 32;
+
+// host-side launchers (defined next to their kernels)
+hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s);
+hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s);
+hipError_t launch_sampled_attention(const AttnArgs& a, hipStream_t s);
+
+// chunking of the context for the decode kernel (host)
+inline void attention_chunking(int units, int64_t n, int* chunk_blocks, int* nchunk) {
+  const int64_t nb = key_blocks(n);
+  int64_t cb = (nb * units + (int64_t)kNumCU * 6 - 1) / ((int64_t)kNumCU * 6);
+  cb = (cb + kAttnWaves - 1) / kAttnWaves * kAttnWaves;
+  if (cb < kAttnWaves) cb = kAttnWaves;
+  if (cb > kMaxChunkBlocks) cb = kMaxChunkBlocks;
+  *chunk_blocks = (int)cb;
+  *nchunk = (int)((nb + cb - 1) / cb);
+}
+
+}  // namespace mp

@@ -67,7 +67,7 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
     return rounded.view(np.float32)
 
 
-def _store(x: np.ndarray, dtype: str) -> np.ndarray:
+def store(x: np.ndarray, dtype: str) -> np.ndarray:
     x = np.ascontiguousarray(x, dtype=np.float32)
     return round_to_bf16(x) if dtype == "bf16" else x
 
@@ -81,7 +81,7 @@ def _rng(seed: int, wl: Workload, tag: str, *idx: int) -> np.random.Generator:
 def projector(wl: Workload, seed: int = 0) -> np.ndarray:
     """W [head_dim, K*L]; column t*K + b is hyperplane b of table t."""
     g = _rng(seed, wl, "W")
-    return _store(g.standard_normal((wl.head_dim, wl.K * wl.L), dtype=np.float32), wl.dtype)
+    return store(g.standard_normal((wl.head_dim, wl.K * wl.L), dtype=np.float32), wl.dtype)
 
 
 def keys_values(wl: Workload, b: int, g: int, seed: int = 0):
@@ -91,7 +91,7 @@ def keys_values(wl: Workload, b: int, g: int, seed: int = 0):
     K = r.standard_normal((wl.n_ctx, wl.head_dim), dtype=np.float32)
     K += m
     V = r.standard_normal((wl.n_ctx, wl.head_dim), dtype=np.float32)
-    return _store(K, wl.dtype), _store(V, wl.dtype)
+    return store(K, wl.dtype), store(V, wl.dtype)
 
 
 def query(wl: Workload, b: int, h: int, K_g: np.ndarray, seed: int = 0,
@@ -115,7 +115,7 @@ def query(wl: Workload, b: int, h: int, K_g: np.ndarray, seed: int = 0,
     nrm = np.linalg.norm(s)
     direction = s / nrm if nrm > 0 else s
     noise = 0.5 * r.standard_normal(wl.head_dim, dtype=np.float32)
-    return _store(alpha * direction + noise, wl.dtype)
+    return store(alpha * direction + noise, wl.dtype)
 
 
 def generate(wl: Workload, seed: int = 0, alpha: float = 0.8):

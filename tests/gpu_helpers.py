@@ -1,0 +1,122 @@
+"""Shared plumbing of the GPU parity tests: upload inputs, run the HIP path through the
+binding, bring results back in the oracle's canonical forms."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2410_16179_amd import binding as mp
+
+TOL = 2e-3   # max relative error of attention outputs (fp32 accumulate, bf16 K/V)
+
+
+def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+    if dtype == "bf16":
+        t16 = t.to(torch.bfloat16)
+        assert torch.equal(t16.to(torch.float32), t), "inputs must be bf16-representable"
+        t = t16
+    return t.cuda()
+
+
+def pack_table_codes(codes: np.ndarray, K: int, L: int, pad_bit: int) -> np.ndarray:
+    """[..., L] canonical integers -> [..., NW] packed words (inverse of table_codes_from_words)."""
+    Wd = (L + 31) // 32
+    codes = np.asarray(codes).astype(np.uint32)
+    full = np.zeros(codes.shape[:-1] + (Wd * 32,), np.uint32)
+    full[..., :L] = codes
+    if pad_bit:
+        full[..., L:] = (1 << K) - 1
+    full = full.reshape(codes.shape[:-1] + (Wd, 32))
+    words = np.zeros(codes.shape[:-1] + (Wd, K), np.uint32)
+    for b in range(K):
+        bits = (full >> np.uint32(b)) & np.uint32(1)
+        words[..., b] = (bits << np.arange(32, dtype=np.uint32)).sum(axis=-1, dtype=np.uint64).astype(np.uint32)
+    return words.reshape(codes.shape[:-1] + (Wd * K,))
+
+
+class Session:
+    """Device buffers of one problem instance."""
+
+    def __init__(self, *, K, L, dtype, Kc, Vc, q, W, n_ctx=None, min_hits=2, n_sink=4, n_local=64):
+        B, Hkv, n_cap, d = Kc.shape
+        self.B, self.Hq, self.Hkv, self.K, self.L = B, q.shape[1], Hkv, K, L
+        self.n_cap = n_cap
+        self.n = n_cap if n_ctx is None else n_ctx
+        self.dtype = dtype
+        self.params = mp.make_params(batch=B, n_q_heads=self.Hq, n_kv_heads=Hkv, K=K, L=L,
+                                     n_ctx=self.n, n_cap=n_cap, dtype=dtype, min_hits=min_hits,
+                                     n_sink=n_sink, n_local=n_local)
+        self.Kc, self.Vc, self.q, self.W = (to_dev(x, dtype) for x in (Kc, Vc, q, W))
+        self.key_codes = mp.alloc_key_codes(self.params)
+        self.q_codes = mp.alloc_query_codes(self.params)
+        self.ws = mp.alloc_workspace(self.params)
+        self.mu = None
+        self.NW = mp.magicpig_code_words_per_key(self.params)
+
+    def set_mu(self, mu: np.ndarray | None):
+        self.mu = None if mu is None else torch.from_numpy(np.ascontiguousarray(mu, np.float32)).cuda()
+
+    def key_mean(self) -> np.ndarray:
+        out = torch.empty(self.B, self.Hkv, 128, dtype=torch.float32, device="cuda")
+        mp.magicpig_key_mean(self.params, self.Kc, out, self.ws)
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+
+    def hash_keys(self, first=0, count=None):
+        count = self.n_cap - first if count is None else count
+        mp.magicpig_hash_keys(self.params, self.Kc, self.mu, self.W, first, count, self.key_codes, self.ws)
+
+    def hash_query(self):
+        mp.magicpig_hash_query(self.params, self.q, self.W, self.q_codes, self.ws)
+
+    def key_table_codes(self) -> np.ndarray:
+        """[B, Hkv, n_cap, L] canonical codes read back from the packed buffer."""
+        torch.cuda.synchronize()
+        raw = self.key_codes.cpu().numpy().view(np.uint32)
+        words = raw[mp.key_code_gather_index(self.params)]
+        return mp.table_codes_from_words(words, self.K, self.L)
+
+    def query_table_codes(self) -> np.ndarray:
+        torch.cuda.synchronize()
+        raw = self.q_codes.cpu().numpy().view(np.uint32)[: self.B * self.Hq * self.NW]
+        return mp.table_codes_from_words(raw.reshape(self.B, self.Hq, self.NW), self.K, self.L)
+
+    def upload_codes(self, key_codes: np.ndarray, q_codes: np.ndarray):
+        """Install oracle codes ([B,Hkv,n_cap,L], [B,Hq,L]) in the packed device layout."""
+        idx = mp.key_code_gather_index(self.params)
+        raw = np.zeros(self.key_codes.numel(), np.uint32)
+        raw[idx.ravel()] = pack_table_codes(key_codes, self.K, self.L, 0).ravel()
+        self.key_codes.copy_(torch.from_numpy(raw.view(np.int32)))
+        qw = pack_table_codes(q_codes, self.K, self.L, 1).ravel()
+        self.q_codes[: qw.size].copy_(torch.from_numpy(qw.view(np.int32)))
+
+    def attend(self, debug=True, cand_cap=None):
+        B, Hq, n = self.B, self.Hq, self.n
+        out = torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device="cuda")
+        if debug:
+            cap = max(n, 1) if cand_cap is None else cand_cap
+            counts = torch.full((B, Hq, max(n, 1)), -1, dtype=torch.int16, device="cuda")
+            cand = torch.full((B, Hq, cap), -1, dtype=torch.int32, device="cuda")
+            ncand = torch.zeros((B, Hq), dtype=torch.int32, device="cuda")
+        else:
+            counts = cand = ncand = None
+        mp.magicpig_sampled_attention(self.params, self.q, self.Kc, self.Vc, self.mu, self.key_codes,
+                                      self.q_codes, out, counts, cand, ncand, self.ws)
+        torch.cuda.synchronize()
+        res = {"out": out.cpu().numpy()}
+        if debug:
+            res["counts"] = counts.cpu().numpy()[:, :, :n].astype(np.int32)
+            nc = ncand.cpu().numpy()
+            cd = cand.cpu().numpy()
+            res["ncand"] = nc
+            res["S"] = [[np.sort(cd[b, h, : min(nc[b, h], cd.shape[-1])]) for h in range(Hq)] for b in range(B)]
+        return res
+
+
+def rel_err(out: np.ndarray, ref: np.ndarray) -> float:
+    """Per head: max_j |o_j - ref_j| / max_j |ref_j|; returns the worst head."""
+    out = np.asarray(out, np.float64).reshape(-1, out.shape[-1])
+    ref = np.asarray(ref, np.float64).reshape(-1, ref.shape[-1])
+    scale = np.maximum(np.abs(ref).max(axis=1), 1e-30)
+    return float((np.abs(out - ref).max(axis=1) / scale).max())

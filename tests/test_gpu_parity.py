@@ -1,0 +1,226 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Hash codes, collision counts and candidate sets must match bit for bit;
+attention outputs within 2e-3 max relative error per head."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2410_16179_amd import binding as mp
+from paper_2410_16179_amd import workloads as wl
+from tests.gpu_helpers import Session, TOL, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    mp.lib()
+
+
+def oracle_mu(oracle, Kc, n):
+    B, Hkv = Kc.shape[:2]
+    return np.stack([[oracle.key_mean(Kc[b, g, :n]) for g in range(Hkv)] for b in range(B)]).astype(np.float32)
+
+
+def run_case(oracle, w: wl.Workload, seed=0, alpha=0.8, use_mu=True, n_cap=None, check_codes=True,
+             oracle_codes_too=True, heads=None, centered_query=False, say=""):
+    print(f"[case] {say or w.name} B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} n={w.n_ctx} "
+          f"K={w.K} L={w.L} tau={w.min_hits} dtype={w.dtype} seed={seed}", flush=True)
+    data = wl.generate(w, seed, alpha)
+    Kc, Vc, q, W = data["K"], data["V"], data["q"], data["W"]
+    n = w.n_ctx
+    mu = oracle_mu(oracle, Kc, n) if use_mu else None
+    if centered_query:
+        for b in range(w.batch):
+            for h in range(w.n_q_heads):
+                q[b, h] = wl.query(w, b, h, Kc[b, h // w.group], seed, alpha, center=mu[b, h // w.group])
+    if n_cap is not None and n_cap > n:          # cache with spare capacity behind the context
+        pad = wl.store(np.random.default_rng(5).standard_normal((w.batch, w.n_kv_heads, n_cap - n, 128)), w.dtype)
+        Kc = np.concatenate([Kc, pad], axis=2)
+        Vc = np.concatenate([Vc, pad], axis=2)
+    ref = oracle.decode_step(q, Kc[:, :, :n], Vc[:, :, :n], W, w.K, w.L,
+                             mu=mu if use_mu else np.zeros((w.batch, w.n_kv_heads, 128), np.float32),
+                             min_hits=w.min_hits, n_sink=w.n_sink, n_local=w.n_local, heads=heads)
+    s = Session(K=w.K, L=w.L, dtype=w.dtype, Kc=Kc, Vc=Vc, q=q, W=W, n_ctx=n,
+                min_hits=w.min_hits, n_sink=w.n_sink, n_local=w.n_local)
+    s.set_mu(mu)
+    s.hash_keys(0, n)
+    s.hash_query()
+    pairs = heads if heads is not None else [(b, h) for b in range(w.batch) for h in range(w.n_q_heads)]
+    if check_codes:
+        np.testing.assert_array_equal(s.query_table_codes(), ref["q_codes"])
+        got = s.key_table_codes()[:, :, :n]
+        for b, g in sorted({(b, h // w.group) for b, h in pairs}):
+            np.testing.assert_array_equal(got[b, g], ref["key_codes"][b, g])
+    res = s.attend()
+    worst = 0.0
+    for b, h in pairs:
+        np.testing.assert_array_equal(res["counts"][b, h], ref["counts"][b, h])
+        assert res["ncand"][b, h] == ref["S"][b][h].size
+        np.testing.assert_array_equal(res["S"][b][h], ref["S"][b][h])
+        worst = max(worst, rel_err(res["out"][b, h][None], ref["out"][b, h][None]))
+    assert worst <= TOL, worst
+    # production call (no debug outputs) gives the same result
+    res2 = s.attend(debug=False)
+    for b, h in pairs:
+        np.testing.assert_array_equal(res2["out"][b, h], res["out"][b, h])
+    if oracle_codes_too and heads is None:       # scan fed with the oracle's own codes
+        s.upload_codes(np.concatenate([ref["key_codes"], np.zeros((w.batch, w.n_kv_heads, Kc.shape[2] - n, w.L), np.int32)], axis=2),
+                       ref["q_codes"])
+        res3 = s.attend()
+        np.testing.assert_array_equal(res3["counts"], ref["counts"])
+    return ref, res, worst
+
+
+def test_c1_full(oracle):
+    ref, res, worst = run_case(oracle, wl.CONFIGS["C1"])
+    frac = ref["S"][0][0].size / 4096
+    assert 0.01 < frac < 0.15        # (8,75) samples a few per cent of the keys
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_c1_other_seeds(oracle, seed):
+    run_case(oracle, wl.CONFIGS["C1"], seed=seed)
+
+
+def test_c2_shape_ragged_context(oracle):
+    # Llama-3.1-8B shapes, (10,150), context not a multiple of the 64-key block or the chunk
+    run_case(oracle, wl.scaled(wl.CONFIGS["C2"], n_ctx=5003))
+
+
+def test_c4_shape_peaked_and_flat_heads(oracle):
+    run_case(oracle, wl.scaled(wl.CONFIGS["C4"], batch=2, n_ctx=3000))
+
+
+def test_c5_shape_group_of_eight(oracle):
+    run_case(oracle, wl.scaled(wl.CONFIGS["C5"], batch=2, n_ctx=2500))
+
+
+@pytest.mark.parametrize("K,L,Hq,Hkv,dtype", [(7, 65, 4, 2, "bf16"), (3, 33, 2, 2, "fp32"),
+                                              (16, 40, 8, 1, "bf16"), (1, 1, 1, 1, "fp32"),
+                                              (5, 512, 2, 1, "bf16")])
+def test_generic_table_shapes(oracle, K, L, Hq, Hkv, dtype):
+    w = wl.Workload("gen", 1, Hq, Hkv, 1500, K, L, dtype, (8,))
+    run_case(oracle, w)
+
+
+@pytest.mark.parametrize("tau", [0, 1, 3])
+def test_other_hit_thresholds(oracle, tau):
+    w = wl.scaled(wl.CONFIGS["C2"], n_ctx=2000, n_q_heads=8, n_kv_heads=2, min_hits=tau)
+    ref, res, _ = run_case(oracle, w)
+    if tau == 0:        # every key sampled with u = 1: exact attention
+        data = wl.generate(w, 0)
+        for h in range(8):
+            ex = oracle.exact_attention(data["q"][0, h], data["K"][0, h // 4], data["V"][0, h // 4])
+            assert rel_err(res["out"][0, h][None], ex[None]) <= TOL
+
+
+@pytest.mark.parametrize("n", [0, 1, 5, 64, 68, 69, 130, 257])
+def test_short_contexts(oracle, n):
+    w = wl.scaled(wl.CONFIGS["C2"], n_ctx=max(n, 1), n_q_heads=4, n_kv_heads=1)
+    if n == 0:
+        s = Session(K=w.K, L=w.L, dtype=w.dtype, Kc=np.zeros((1, 1, 64, 128), np.float32),
+                    Vc=np.zeros((1, 1, 64, 128), np.float32), q=np.ones((1, 4, 128), np.float32),
+                    W=wl.projector(w), n_ctx=0)
+        s.hash_query()
+        res = s.attend(debug=False)
+        assert np.all(res["out"] == 0)
+        return
+    run_case(oracle, w)
+
+
+def test_no_static_tokens_and_no_centering(oracle):
+    w = wl.scaled(wl.CONFIGS["C2"], n_ctx=3000, n_q_heads=8, n_kv_heads=2, n_sink=0, n_local=0)
+    run_case(oracle, w, use_mu=False)
+    run_case(oracle, w, use_mu=True)
+
+
+def test_spare_capacity_behind_the_context(oracle):
+    w = wl.scaled(wl.CONFIGS["C2"], n_ctx=1000, n_q_heads=8, n_kv_heads=2)
+    run_case(oracle, w, n_cap=1500, oracle_codes_too=False)
+
+
+@pytest.mark.parametrize("alpha", [8.0, 24.0])
+def test_queries_with_large_inclusion_probabilities(oracle, alpha):
+    # queries aligned with (centered) planted keys: u_i spans (0, 1], exercising both
+    # branches of the inclusion-probability evaluation
+    w = wl.scaled(wl.CONFIGS["C2"], n_ctx=4000, n_q_heads=8, n_kv_heads=2, planted=(4,))
+    ref, _, _ = run_case(oracle, w, alpha=alpha, centered_query=True)
+
+
+def test_append_keys_with_frozen_mean(oracle):
+    w = wl.scaled(wl.CONFIGS["C2"], n_ctx=700, n_q_heads=4, n_kv_heads=1)
+    data = wl.generate(w)
+    mu = oracle_mu(oracle, data["K"], 500)                    # frozen after 500 prefill keys
+    s = Session(K=w.K, L=w.L, dtype=w.dtype, Kc=data["K"], Vc=data["V"], q=data["q"], W=data["W"])
+    s.set_mu(mu)
+    s.hash_keys(0, 500)
+    s.hash_keys(500, 37)
+    s.hash_keys(537, 163)
+    ref = oracle.hash_keys(data["K"][0, 0], data["W"], mu[0, 0], w.K, w.L)
+    np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
+
+
+def test_hash_bits_follow_the_exact_sum(oracle):
+    # projections that cancel to (almost) nothing: the bit is the sign of the exact sum
+    K, L = 2, 3
+    big, tiny = 2.0 ** 40, 2.0 ** -40
+    W = np.zeros((128, K * L), np.float32)
+    W[:4, :] = 1.0
+    W[4, 1] = 1.0
+    rows = np.zeros((1, 1, 64, 128), np.float32)
+    rows[0, 0, 0, :3] = [-tiny, big, -big]
+    rows[0, 0, 1, :3] = [tiny, big, -big]
+    rows[0, 0, 2, :3] = [big, -big, 0]
+    rows[0, 0, 3, :5] = [big, -big, 0, 0, -tiny]
+    rows[0, 0, 4, :3] = [1.5, -1.5, 0]
+    for dtype in ("fp32", "bf16"):
+        for mu in (None, np.zeros((1, 1, 128), np.float32), None):
+            s = Session(K=K, L=L, dtype=dtype, Kc=rows, Vc=rows, q=rows[:, :, 0], W=W, n_ctx=64)
+            s.set_mu(mu)
+            s.hash_keys()
+            ref = oracle.hash_keys(rows[0, 0], W, None if mu is None else mu[0, 0], K, L)
+            np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
+    # centering that matters only in exact arithmetic
+    mu = np.zeros((1, 1, 128), np.float32)
+    mu[0, 0, 0] = big
+    mu[0, 0, 1] = tiny
+    rows2 = np.zeros((1, 1, 64, 128), np.float32)
+    rows2[0, 0, :, 0] = big
+    s = Session(K=K, L=L, dtype="fp32", Kc=rows2, Vc=rows2, q=rows2[:, :, 0], W=W, n_ctx=64)
+    s.set_mu(mu)
+    s.hash_keys()
+    ref = oracle.hash_keys(rows2[0, 0], W, mu[0, 0], K, L)
+    np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
+    assert ref[0, 0] == 0          # x - mu = -2^-40 < 0 in both planes of table 0
+
+
+def test_key_mean(oracle):
+    w = wl.scaled(wl.CONFIGS["C2"], n_ctx=5003, n_q_heads=8, n_kv_heads=2, batch=2)
+    data = wl.generate(w)
+    s = Session(K=w.K, L=w.L, dtype=w.dtype, Kc=data["K"], Vc=data["V"], q=data["q"], W=data["W"])
+    got = s.key_mean()
+    ref = np.stack([[oracle.key_mean(data["K"][b, g]) for g in range(2)] for b in range(2)])
+    # float32 partial sums over at most 64 rows, float64 beyond: error far below 1e-5 of |k|
+    assert np.abs(got - ref).max() <= 1e-5 * np.abs(data["K"]).max()
+    w1 = wl.CONFIGS["C1"]
+    d1 = wl.generate(w1)
+    s1 = Session(K=w1.K, L=w1.L, dtype="fp32", Kc=d1["K"], Vc=d1["V"], q=d1["q"], W=d1["W"])
+    assert np.abs(s1.key_mean()[0, 0] - oracle.key_mean(d1["K"][0, 0])).max() <= 1e-5 * np.abs(d1["K"]).max()
+
+
+def test_repeatable(oracle):
+    w = wl.scaled(wl.CONFIGS["C2"], n_ctx=6000)
+    data = wl.generate(w)
+    s = Session(K=w.K, L=w.L, dtype=w.dtype, Kc=data["K"], Vc=data["V"], q=data["q"], W=data["W"])
+    s.set_mu(oracle_mu(oracle, data["K"], w.n_ctx))
+    s.hash_keys(); s.hash_query()
+    a = s.attend(debug=False)["out"]
+    codes = s.key_codes.clone()
+    s.hash_keys()
+    assert torch.equal(codes, s.key_codes)
+    b = s.attend(debug=False)["out"]
+    np.testing.assert_array_equal(a, b)

@@ -1,0 +1,125 @@
+"""Host-side checks that need no GPU: the library loads and exports what the header
+declares, argument validation, sizes and the packed-code layout."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2410_16179_amd import binding as mp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def params(**kw):
+    base = dict(batch=1, n_q_heads=32, n_kv_heads=8, K=10, L=150, n_ctx=1000, dtype="bf16")
+    base.update(kw)
+    return mp.make_params(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "magicpig.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(magicpig_[a-z_]+)\s*\(", header))
+    assert declared == set(mp.EXPORTS)
+    lib = mp.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(mp.magicpig_params) == 10 * 4 + 8 * 8
+
+
+def test_sizes_and_paper_projector_size():
+    p = params()
+    assert mp.magicpig_code_words_per_key(p) == 10 * 5
+    assert mp.magicpig_query_code_bytes(p) == 32 * 50 * 4
+    assert mp.magicpig_key_code_bytes(p) == 8 * 1024 * 50 * 4     # capacity rounded to 64 keys
+    assert mp.magicpig_workspace_bytes(p) >= 256
+    # Table "overhead of LSH": the (10,150) projector for d = 128 in bf16 is 384 KB
+    assert 128 * p.K * p.L * 2 == 384000
+
+
+@pytest.mark.parametrize("K,L,n_cap", [(10, 150, 200), (9, 120, 64), (8, 75, 130), (3, 33, 65), (1, 1, 1), (7, 65, 100)])
+def test_code_layout_is_a_bijection_inside_the_buffer(K, L, n_cap):
+    p = params(batch=2, n_q_heads=4, n_kv_heads=2, K=K, L=L, n_ctx=n_cap, n_cap=n_cap)
+    idx = mp.key_code_gather_index(p)
+    NW = mp.magicpig_code_words_per_key(p)
+    assert idx.shape == (2, 2, n_cap, NW)
+    flat = idx.ravel()
+    assert len(np.unique(flat)) == flat.size
+    assert flat.min() >= 0 and flat.max() < mp.magicpig_key_code_bytes(p) // 4
+    rng = np.random.default_rng(0)
+    for _ in range(50):      # the vectorised index agrees with the C function everywhere
+        b, g, k, x = rng.integers(2), rng.integers(2), rng.integers(n_cap), rng.integers(NW)
+        assert idx[b, g, k, x] == mp.magicpig_key_code_index(p, int(b), int(g), int(k), int(x))
+    assert mp.magicpig_key_code_index(p, 0, 0, n_cap, 0) == ctypes.c_size_t(-1).value
+    assert mp.magicpig_key_code_index(p, 0, 0, 0, NW) == ctypes.c_size_t(-1).value
+
+
+def test_table_codes_from_words_roundtrip():
+    rng = np.random.default_rng(1)
+    K, L = 5, 70
+    Wd = 3
+    bits = rng.integers(0, 2, size=(4, L, K))
+    words = np.zeros((4, Wd * K), np.uint32)
+    for t in range(L):
+        for b in range(K):
+            words[:, (t // 32) * K + b] |= (bits[:, t, b].astype(np.uint32) << np.uint32(t % 32))
+    codes = mp.table_codes_from_words(words, K, L)
+    expect = (bits * (1 << np.arange(K))).sum(axis=2)
+    np.testing.assert_array_equal(codes, expect)
+
+
+def _status(fn, *args):
+    return fn(*args)
+
+
+def test_argument_validation_without_a_gpu():
+    lib = mp.lib()
+    ws = (ctypes.c_char * 4096)()
+    wsp = ctypes.addressof(ws)
+    wsp += (-wsp) % 16
+    fake = ctypes.c_void_p(wsp)
+    big = 1 << 40
+
+    def hash_query(p, q=fake, W=fake, codes=fake, wbytes=big):
+        return lib.magicpig_hash_query(ctypes.byref(p), q, W, codes, fake, wbytes, None)
+
+    assert hash_query(params(head_dim=64)) == -2
+    assert hash_query(params(K=0)) == -2
+    assert hash_query(params(K=17)) == -2
+    assert hash_query(params(L=513)) == -2
+    assert hash_query(params(dtype=7)) == -2
+    assert hash_query(params(n_q_heads=6, n_kv_heads=4)) == -1
+    assert hash_query(params(n_q_heads=24, n_kv_heads=8)) == -2      # group size 3
+    assert hash_query(params(n_ctx=100, n_cap=50)) == -1
+    assert hash_query(params(), W=None) == -1
+    assert hash_query(params(), q=ctypes.c_void_p(wsp + 2)) == -1     # misaligned
+    assert hash_query(params(), wbytes=8) == -3
+    p = params()
+    assert lib.magicpig_hash_keys(ctypes.byref(p), fake, None, fake, 900, 200, fake, fake, big, None) == -1
+    assert lib.magicpig_hash_keys(ctypes.byref(p), fake, None, fake, -1, 2, fake, fake, big, None) == -1
+    bad = params(k_strides=(8 * 1000 * 128, 1000 * 128, 100))
+    assert lib.magicpig_hash_keys(ctypes.byref(bad), fake, None, fake, 0, 1, fake, fake, big, None) == -1
+    bad = params(k_strides=(8 * 1000 * 132, 1000 * 132, 132))
+    assert lib.magicpig_hash_keys(ctypes.byref(bad), fake, None, fake, 0, 1, fake, fake, big, None) == -2
+    assert lib.magicpig_sampled_attention(ctypes.byref(p), fake, fake, fake, None, fake, fake, None,
+                                          None, None, None, 0, fake, big, None) == -1
+    assert lib.magicpig_sampled_attention(ctypes.byref(p), fake, fake, fake, None, fake, fake, fake,
+                                          None, fake, None, 4, fake, big, None) == -1
+    assert lib.magicpig_sampled_attention(ctypes.byref(p), fake, fake, fake, None, fake, fake, fake,
+                                          None, None, None, 0, fake, 16, None) == -3
+    assert lib.magicpig_key_mean(ctypes.byref(p), fake, None, fake, big, None) == -1
+    assert mp.magicpig_workspace_bytes(params(K=0)) == 0
+    assert lib.magicpig_status_string(-3) == b"workspace too small"
+    assert lib.magicpig_status_string(0) == b"ok"
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(mp, "_lib", None)
+    monkeypatch.setattr(mp, "LIB_PATH", "/nonexistent/libmagicpig.so")
+    with pytest.raises(mp.MagicpigError):
+        mp.lib()
