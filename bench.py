@@ -1,0 +1,207 @@
+"""Benchmark of the LSH-sampled decode attention hot path on one MI355X.
+
+One step = one decode step of one layer at the C3 workload (Llama-3.1-8B shapes, batch 1,
+32 query / 8 KV heads, head_dim 128, context 98304, bf16, SimHash K=10 L=150, >= 2 hits,
+4 sink + 64 local): magicpig_hash_query + magicpig_sampled_attention (query coding,
+collision scan, compaction, gather, importance-weighted softmax.V).  Inputs, key codes and
+the centering vector are resident in HBM before the timed region.  The one-time prefill
+work (magicpig_key_mean + magicpig_hash_keys over all 786432 keys) is timed separately and
+reported under "prefill_hash".  Steps rotate over several independent copies of (codes, K,
+V) so that no step finds its data in the last-level cache, as in a real model where each
+layer has its own cache.
+
+Prints ONE JSON line.  `python bench.py --gpus 1 --steps K --warmup W`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+import torch  # noqa: E402
+
+from paper_2410_16179_amd import binding as mp  # noqa: E402
+from paper_2410_16179_amd import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+METRIC = "LSH-sampled decode attn: query-heads/s at 96k ctx"
+
+
+def build_workload(name: str, copies: int, seed: int):
+    w = wl.CONFIGS[name]
+    t0 = time.time()
+    data = wl.generate(w, seed)
+    gen_s = time.time() - t0
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    Kd = torch.from_numpy(data["K"]).to(tdt).cuda()
+    Vd = torch.from_numpy(data["V"]).to(tdt).cuda()
+    qd = torch.from_numpy(data["q"]).to(tdt).cuda()
+    Wd = torch.from_numpy(data["W"]).to(tdt).cuda()
+    params = mp.make_params(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, K=w.K,
+                            L=w.L, n_ctx=w.n_ctx, dtype=w.dtype, min_hits=w.min_hits,
+                            n_sink=w.n_sink, n_local=w.n_local)
+    sets = []
+    for c in range(copies):
+        sets.append({
+            "K": Kd if c == 0 else Kd.clone(), "V": Vd if c == 0 else Vd.clone(),
+            "codes": mp.alloc_key_codes(params),
+            "mu": torch.empty(w.batch, w.n_kv_heads, 128, dtype=torch.float32, device="cuda"),
+        })
+    return w, data, params, qd, Wd, sets, gen_s
+
+
+def time_prefill(params, w, Wd, sets, ws):
+    """key mean + key hashing of every copy; returns average ms per copy."""
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for s in sets:
+        mp.magicpig_key_mean(params, s["K"], s["mu"], ws)
+        mp.magicpig_hash_keys(params, s["K"], s["mu"], Wd, 0, w.n_ctx, s["codes"], ws)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / len(sets)
+
+
+def cpu_baseline(w, data, seed):
+    """The CPU oracle, as it stands, on a bounded sample: the decode step (query coding,
+    collision counts, sample, estimator) of the query heads of the first KV heads, at the
+    full context.  Key codes for those KV heads are computed by the oracle beforehand
+    (untimed here, like the GPU's prefill hashing)."""
+    from oracle import magicpig_oracle as oracle
+    from threadpoolctl import threadpool_limits
+    n_groups = 2
+    G = w.group
+    heads = [(0, h) for h in range(n_groups * G)]
+    with threadpool_limits(limits=1):
+        mu = np.stack([[oracle.key_mean(data["K"][0, g]) for g in range(w.n_kv_heads)]]).astype(np.float32)
+        t0 = time.time()
+        codes = np.zeros((1, w.n_kv_heads, w.n_ctx, w.L), np.int32)
+        for g in range(n_groups):
+            codes[0, g] = oracle.hash_keys(data["K"][0, g], data["W"], mu[0, g], w.K, w.L)
+        hash_s = time.time() - t0
+        t0 = time.time()
+        ref = oracle.decode_step(data["q"], data["K"], data["V"], data["W"], w.K, w.L, mu=mu,
+                                 min_hits=w.min_hits, n_sink=w.n_sink, n_local=w.n_local,
+                                 key_codes=codes, heads=heads)
+        dec_s = time.time() - t0
+    return {
+        "value": len(heads) / dec_s, "unit": "query-heads/s", "cores": 1, "kind": "oracle",
+        "sample": f"decode step of {len(heads)} of {w.n_q_heads} query heads (KV heads 0..{n_groups - 1}) "
+                  f"at the full {w.n_ctx}-key context, {dec_s:.2f} s; oracle key hashing of those "
+                  f"{n_groups * w.n_ctx} keys took {hash_s:.1f} s (not in value)",
+    }, ref, heads
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--copies", type=int, default=8)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path "
+              "(the path shards by KV head without communication; see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    mp.lib()
+
+    w, data, params, qd, Wd, sets, gen_s = build_workload(args.workload, args.copies, args.seed)
+    ws = mp.alloc_workspace(params)
+    qcodes = mp.alloc_query_codes(params)
+    out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+
+    prefill_ms = time_prefill(params, w, Wd, sets, ws)          # also produces codes and mu
+    prefill_ms = time_prefill(params, w, Wd, sets, ws)          # second pass: warm
+
+    def step(i):
+        s = sets[i % len(sets)]
+        mp.magicpig_hash_query(params, qd, Wd, qcodes, ws)
+        mp.magicpig_sampled_attention(params, qd, s["K"], s["V"], s["mu"], s["codes"], qcodes, out,
+                                      workspace=ws)
+
+    # sample sizes for the algorithmic byte count (debug outputs, outside the timed region)
+    ncand = torch.zeros(w.batch, w.n_q_heads, dtype=torch.int32, device="cuda")
+    cand = torch.zeros(w.batch, w.n_q_heads, 1, dtype=torch.int32, device="cuda")
+    mp.magicpig_hash_query(params, qd, Wd, qcodes, ws)
+    mp.magicpig_sampled_attention(params, qd, sets[0]["K"], sets[0]["V"], sets[0]["mu"], sets[0]["codes"],
+                                  qcodes, out, None, cand, ncand, ws)
+    torch.cuda.synchronize()
+    n_sampled = ncand.cpu().numpy().astype(np.int64)
+    out0 = out.cpu().numpy().copy()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        s = sets[i % len(sets)]
+        mp.magicpig_hash_query(params, qd, Wd, qcodes, ws)
+        ev[i][0].record()
+        mp.magicpig_sampled_attention(params, qd, s["K"], s["V"], s["mu"], s["codes"], qcodes, out,
+                                      workspace=ws)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    heads = w.batch * w.n_q_heads
+    value = heads / (ms_per_step * 1e-3)
+
+    n_static = min(w.n_ctx, w.n_sink + w.n_local)
+    scan_bytes = w.batch * w.n_kv_heads * max(w.n_ctx - n_static, 0) * w.K * w.L / 8.0
+    gather_bytes = float((n_sampled + n_static).sum()) * 2 * 128 * (2 if w.dtype == "bf16" else 4)
+    out_bytes = heads * 128 * 4
+    alg_bytes = scan_bytes + gather_bytes + out_bytes
+    achieved = alg_bytes / (attn_ms * 1e-3) / 1e9
+
+    hash_flops = 2.0 * w.batch * w.n_kv_heads * w.n_ctx * 128 * w.K * w.L
+    result = {
+        "metric": METRIC, "value": value, "unit": "query-heads/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads} query / {w.n_kv_heads} KV heads, "
+                               f"head_dim 128, context {w.n_ctx}, K={w.K} L={w.L}, min_hits {w.min_hits}, "
+                               f"{w.n_sink} sink + {w.n_local} local, {args.copies} rotating cache copies",
+                   "step": "magicpig_hash_query + magicpig_sampled_attention"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "magicpig_sampled_attention (scan+compaction+gather+softmax, incl. merge)",
+                     "avg_launch_ms": attn_ms, "algorithmic_bytes": alg_bytes,
+                     "scan_bytes": scan_bytes, "gather_bytes": gather_bytes,
+                     "mean_sampled_per_head": float(n_sampled.mean())},
+        "prefill_hash": {"ms": prefill_ms, "keys": w.batch * w.n_kv_heads * w.n_ctx,
+                         "tflops": hash_flops / (prefill_ms * 1e-3) / 1e12,
+                         "frac_of_bf16_mfma_peak": hash_flops / (prefill_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                         "what": "magicpig_key_mean + magicpig_hash_keys over the whole cache (one-time)"},
+        "input_generation_s": gen_s,
+    }
+    if not args.no_cpu_baseline:
+        cb, ref, ref_heads = cpu_baseline(w, data, args.seed)
+        result["cpu_baseline"] = cb
+        err = max(float(np.abs(out0[b, h] - ref["out"][b, h]).max() / np.abs(ref["out"][b, h]).max())
+                  for b, h in ref_heads)
+        result["parity_vs_oracle_max_rel_err"] = err
+        same_sets = all(int(n_sampled[b, h]) == ref["S"][b][h].size for b, h in ref_heads)
+        result["parity_sample_sizes_equal"] = bool(same_sets)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -40,12 +40,15 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
   const int ncol = a.K * a.L;
   const int Wd = table_words(a.L);
 
-  for (int x = 0; x < a.NW; ++x) {
+  // blockIdx.y walks the code words: all words of a vector are coded by different
+  // workgroups, which keeps the few query vectors of a decode step spread over the chip.
+  for (int x = blockIdx.y; x < a.NW; x += gridDim.y) {
     const int w = x / a.K, b = x % a.K;
     const int t = 32 * w + beta;
     const bool col_ok = t < a.L;
     const int j = col_ok ? t * a.K + b : 0;
     double s = 0.0, mag = 0.0;
+#pragma unroll 8
     for (int d = 0; d < kHeadDim; ++d) {
       const double wv = load_elem(a.W, (int64_t)d * ncol + j, a.is_fp32);
       const double xv = load_elem(a.X, xbase + d, a.is_fp32);
@@ -95,7 +98,9 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
 hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s) {
   if (a.total_rows <= 0) return hipSuccess;
   const int64_t groups = (a.total_rows + 7) / 8;
-  hipLaunchKernelGGL(hash_direct_kernel, dim3((unsigned)groups), dim3(256), 0, s, a);
+  // few vectors (queries): one workgroup per (8 vectors, word); many (keys): words looped
+  const unsigned ny = groups >= 4096 ? 1u : (unsigned)a.NW;
+  hipLaunchKernelGGL(hash_direct_kernel, dim3((unsigned)groups, ny), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

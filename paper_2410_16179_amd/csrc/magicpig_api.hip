@@ -48,9 +48,10 @@ size_t ws_mean(const magicpig_params* p) {
 }
 
 size_t ws_attention(const magicpig_params* p) {
-  int cb, nc;
-  mp::attention_chunking(p->batch * p->n_kv_heads, p->n_ctx, &cb, &nc);
-  return align256((size_t)p->batch * p->n_q_heads * nc * mp::kPartialStride * sizeof(float));
+  int64_t bpp;
+  int np;
+  mp::attention_partition(p->batch * p->n_kv_heads, p->n_q_heads / p->n_kv_heads, p->n_ctx, &bpp, &np);
+  return align256((size_t)p->batch * p->n_q_heads * np * mp::kPartialStride * sizeof(float));
 }
 
 }  // namespace
@@ -184,7 +185,7 @@ int magicpig_sampled_attention(const magicpig_params* p, const void* q, const vo
   a.n = p->n_ctx; a.blocks_cap = mp::key_blocks(p->n_cap);
   a.ks_b = p->k_stride_b; a.ks_h = p->k_stride_h; a.ks_n = p->k_stride_n;
   a.vs_b = p->v_stride_b; a.vs_h = p->v_stride_h; a.vs_n = p->v_stride_n;
-  mp::attention_chunking(p->batch * p->n_kv_heads, p->n_ctx, &a.chunk_blocks, &a.nchunk);
+  mp::attention_partition(p->batch * p->n_kv_heads, a.Hq / a.Hkv, p->n_ctx, &a.blocks_per_part, &a.nparts);
   a.scale = 0.08838834764831845f;   // 1/sqrt(128)
   const hipError_t e = mp::launch_sampled_attention(a, reinterpret_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);

@@ -53,28 +53,32 @@ struct AttnArgs {
   int B, Hq, Hkv, K, L, Wd, NW, tau, n_sink, n_local;
   int64_t n, blocks_cap;
   int64_t ks_b, ks_h, ks_n, vs_b, vs_h, vs_n;
-  int chunk_blocks, nchunk;
+  int64_t blocks_per_part;   // key blocks owned by one workgroup
+  int nparts;                // workgroups (= partial results) per (batch, KV head)
   float scale;
 };
 
 constexpr int kPartialStride = 132;   // 128 output elements, running max, running sum, pad
-constexpr int kAttnWaves = 4;
-constexpr int kMaxChunkBlocks = 32;
+constexpr int kAttnWgPerCU = 2;       // resident workgroups per CU the decode kernel is sized for
 
 // host-side launchers (defined next to their kernels)
 hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s);
 hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s);
 hipError_t launch_sampled_attention(const AttnArgs& a, hipStream_t s);
 
-// chunking of the context for the decode kernel (host)
-inline void attention_chunking(int units, int64_t n, int* chunk_blocks, int* nchunk) {
+// Split of the context over workgroups of the decode kernel (host): every (batch, KV head)
+// is cut into `nparts` contiguous runs of `blocks_per_part` 64-key blocks, sized so that the
+// whole grid is resident at once (kAttnWgPerCU workgroups per CU).
+inline void attention_partition(int units, int G, int64_t n, int64_t* blocks_per_part, int* nparts) {
+  const int nwaves = G > 4 ? 8 : 4;
   const int64_t nb = key_blocks(n);
-  int64_t cb = (nb * units + (int64_t)kNumCU * 6 - 1) / ((int64_t)kNumCU * 6);
-  cb = (cb + kAttnWaves - 1) / kAttnWaves * kAttnWaves;
-  if (cb < kAttnWaves) cb = kAttnWaves;
-  if (cb > kMaxChunkBlocks) cb = kMaxChunkBlocks;
-  *chunk_blocks = (int)cb;
-  *nchunk = (int)((nb + cb - 1) / cb);
+  int64_t want = units > 0 ? ((int64_t)kNumCU * kAttnWgPerCU + units - 1) / units : 1;
+  if (want < 1) want = 1;
+  int64_t bpp = (nb + want - 1) / want;
+  bpp = (bpp + nwaves - 1) / nwaves * nwaves;
+  if (bpp < nwaves) bpp = nwaves;
+  *blocks_per_part = bpp;
+  *nparts = (int)((nb + bpp - 1) / bpp);
 }
 
 }  // namespace mp
