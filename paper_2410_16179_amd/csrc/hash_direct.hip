@@ -11,14 +11,16 @@
 
 namespace mp {
 
-__device__ inline double load_elem(const void* p, int64_t idx, int is_fp32) {
-  if (is_fp32) return (double)reinterpret_cast<const float*>(p)[idx];
+template <bool FP32>
+__device__ inline double load_elem(const void* p, int64_t idx) {
+  if constexpr (FP32) return (double)reinterpret_cast<const float*>(p)[idx];
   const uint32_t b = reinterpret_cast<const uint16_t*>(p)[idx];
   return (double)__uint_as_float(b << 16);
 }
 
 // One wavefront codes two vectors at a time: lanes 0..31 take tables 32w..32w+31 of the
 // first, lanes 32..63 of the second; a ballot turns the 64 sign tests into two code words.
+template <bool FP32>
 __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
   __shared__ long long limbs[4][kLimbs];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -48,17 +50,25 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
     const bool col_ok = t < a.L;
     const int j = col_ok ? t * a.K + b : 0;
     double s = 0.0, mag = 0.0;
-#pragma unroll 8
-    for (int d = 0; d < kHeadDim; ++d) {
-      const double wv = load_elem(a.W, (int64_t)d * ncol + j, a.is_fp32);
-      const double xv = load_elem(a.X, xbase + d, a.is_fp32);
-      const double p = xv * wv;
-      s += p;
-      mag += fabs(p);
-      if (mu) {
-        const double pm = (double)mu[d] * wv;
-        s -= pm;
-        mag += fabs(pm);
+    // 64 projector and 64 vector elements are requested before any is used, so the 128-long
+    // dot product costs two memory round trips instead of one per element
+    for (int d0 = 0; d0 < kHeadDim; d0 += 64) {
+      double wv[64], xv[64];
+#pragma unroll
+      for (int i = 0; i < 64; ++i) {
+        wv[i] = load_elem<FP32>(a.W, (int64_t)(d0 + i) * ncol + j);
+        xv[i] = load_elem<FP32>(a.X, xbase + d0 + i);
+      }
+#pragma unroll
+      for (int i = 0; i < 64; ++i) {
+        const double p = xv[i] * wv[i];
+        s += p;
+        mag += fabs(p);
+        if (mu) {
+          const double pm = (double)mu[d0 + i] * wv[i];
+          s -= pm;
+          mag += fabs(pm);
+        }
       }
     }
     bool bit = s >= 0.0;
@@ -75,8 +85,8 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
       const float* smu = a.mu ? a.mu + su * kHeadDim : nullptr;
       const bool r = exact_sign_nonneg_wave(
           limbs[wave],
-          [&](int d) { return load_elem(a.X, xb + d, a.is_fp32); },
-          [&](int d) { return load_elem(a.W, (int64_t)d * ncol + sj, a.is_fp32); },
+          [&](int d) { return load_elem<FP32>(a.X, xb + d); },
+          [&](int d) { return load_elem<FP32>(a.W, (int64_t)d * ncol + sj); },
           [&](int d) { return smu ? (double)smu[d] : 0.0; }, smu != nullptr);
       if (lane == src) bit = r;
       pending &= pending - 1;
@@ -100,7 +110,8 @@ hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s) {
   const int64_t groups = (a.total_rows + 7) / 8;
   // few vectors (queries): one workgroup per (8 vectors, word); many (keys): words looped
   const unsigned ny = groups >= 4096 ? 1u : (unsigned)a.NW;
-  hipLaunchKernelGGL(hash_direct_kernel, dim3((unsigned)groups, ny), dim3(256), 0, s, a);
+  if (a.is_fp32) hipLaunchKernelGGL(hash_direct_kernel<true>, dim3((unsigned)groups, ny), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(hash_direct_kernel<false>, dim3((unsigned)groups, ny), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -47,12 +47,19 @@ size_t ws_mean(const magicpig_params* p) {
   return align256((size_t)(units * nchunk * mp::kHeadDim) * sizeof(double));
 }
 
-size_t ws_attention(const magicpig_params* p) {
-  int64_t bpp;
-  int np;
-  mp::attention_partition(p->batch * p->n_kv_heads, p->n_q_heads / p->n_kv_heads, p->n_ctx, &bpp, &np);
-  return align256((size_t)p->batch * p->n_q_heads * np * mp::kPartialStride * sizeof(float));
+// decode workspace: [partials | ballots]
+struct AttnWs { size_t partial_off, masks_off, total; int nranges; };
+AttnWs ws_attention_layout(const magicpig_params* p) {
+  AttnWs w{};
+  const int64_t nblk = mp::key_blocks(p->n_ctx);
+  const size_t heads = (size_t)p->batch * p->n_q_heads;
+  w.nranges = (int)((nblk + mp::kRangeBlocks - 1) / mp::kRangeBlocks);
+  w.partial_off = 0;
+  w.masks_off = align256(heads * w.nranges * mp::kPartialStride * sizeof(float));
+  w.total = w.masks_off + align256(heads * (size_t)nblk * sizeof(uint64_t));
+  return w;
 }
+size_t ws_attention(const magicpig_params* p) { return ws_attention_layout(p).total; }
 
 }  // namespace
 
@@ -176,7 +183,11 @@ int magicpig_sampled_attention(const magicpig_params* p, const void* q, const vo
   if (workspace_bytes < ws_attention(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
   mp::AttnArgs a{};
   a.q = q; a.Kc = K_cache; a.Vc = V_cache; a.mu = mu; a.kcodes = key_codes; a.qcodes = q_codes;
-  a.partial = reinterpret_cast<float*>(workspace); a.out = out;
+  const AttnWs wl = ws_attention_layout(p);
+  char* wsb = reinterpret_cast<char*>(workspace);
+  a.partial = reinterpret_cast<float*>(wsb + wl.partial_off); a.out = out;
+  a.masks = reinterpret_cast<uint64_t*>(wsb + wl.masks_off);
+  a.nranges = wl.nranges;
   a.dbg_counts = dbg_counts; a.dbg_cand = dbg_cand; a.dbg_ncand = dbg_ncand; a.dbg_cand_cap = dbg_cand_cap;
   a.is_fp32 = p->dtype == MAGICPIG_FP32;
   a.B = p->batch; a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.K = p->K; a.L = p->L;
@@ -185,7 +196,6 @@ int magicpig_sampled_attention(const magicpig_params* p, const void* q, const vo
   a.n = p->n_ctx; a.blocks_cap = mp::key_blocks(p->n_cap);
   a.ks_b = p->k_stride_b; a.ks_h = p->k_stride_h; a.ks_n = p->k_stride_n;
   a.vs_b = p->v_stride_b; a.vs_h = p->v_stride_h; a.vs_n = p->v_stride_n;
-  mp::attention_partition(p->batch * p->n_kv_heads, a.Hq / a.Hkv, p->n_ctx, &a.blocks_per_part, &a.nparts);
   a.scale = 0.08838834764831845f;   // 1/sqrt(128)
   const hipError_t e = mp::launch_sampled_attention(a, reinterpret_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);

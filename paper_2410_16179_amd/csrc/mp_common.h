@@ -48,37 +48,22 @@ struct AttnArgs {
   const void* q; const void* Kc; const void* Vc; const float* mu;
   const uint32_t* kcodes; const uint32_t* qcodes;
   float* partial; float* out;
+  uint64_t* masks;        // [B*Hq][key blocks] ballots of sampled + static keys
   uint16_t* dbg_counts; int32_t* dbg_cand; int32_t* dbg_ncand; int64_t dbg_cand_cap;
   int is_fp32;
   int B, Hq, Hkv, K, L, Wd, NW, tau, n_sink, n_local;
   int64_t n, blocks_cap;
   int64_t ks_b, ks_h, ks_n, vs_b, vs_h, vs_n;
-  int64_t blocks_per_part;   // key blocks owned by one workgroup
-  int nparts;                // workgroups (= partial results) per (batch, KV head)
+  int nranges;               // runs of kRangeBlocks key blocks (= partials) per head
   float scale;
 };
 
 constexpr int kPartialStride = 132;   // 128 output elements, running max, running sum, pad
-constexpr int kAttnWgPerCU = 2;       // resident workgroups per CU the decode kernel is sized for
+constexpr int kRangeBlocks = 16;      // key blocks per gather wavefront (1024 keys)
 
 // host-side launchers (defined next to their kernels)
 hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s);
 hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s);
 hipError_t launch_sampled_attention(const AttnArgs& a, hipStream_t s);
-
-// Split of the context over workgroups of the decode kernel (host): every (batch, KV head)
-// is cut into `nparts` contiguous runs of `blocks_per_part` 64-key blocks, sized so that the
-// whole grid is resident at once (kAttnWgPerCU workgroups per CU).
-inline void attention_partition(int units, int G, int64_t n, int64_t* blocks_per_part, int* nparts) {
-  const int nwaves = G > 4 ? 8 : 4;
-  const int64_t nb = key_blocks(n);
-  int64_t want = units > 0 ? ((int64_t)kNumCU * kAttnWgPerCU + units - 1) / units : 1;
-  if (want < 1) want = 1;
-  int64_t bpp = (nb + want - 1) / want;
-  bpp = (bpp + nwaves - 1) / nwaves * nwaves;
-  if (bpp < nwaves) bpp = nwaves;
-  *blocks_per_part = bpp;
-  *nparts = (int)((nb + bpp - 1) / bpp);
-}
 
 }  // namespace mp
