@@ -15,6 +15,7 @@ Prints ONE JSON line.  `python bench.py --gpus 1 --steps K --warmup W`.
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -147,28 +148,88 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+
+    # ---- timed region: exactly `steps` decode steps, replayed from one HIP graph so that the
+    # host's launch cost (python + ctypes, several microseconds per call) is not what is
+    # measured.  If capture is unavailable the same steps are timed as eager launches.
+    launch_mode = "hipgraph"
+    graph = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(args.steps):
+                    step(i)
+        torch.cuda.current_stream().wait_stream(side)
+        graph.replay()                      # untimed: first replay uploads the graph
+        torch.cuda.synchronize()
+    except Exception as exc:  # noqa: BLE001
+        print(f"graph capture failed ({exc}); timing eager launches", file=sys.stderr)
+        graph, launch_mode = None, "eager"
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        s = sets[i % len(sets)]
-        mp.magicpig_hash_query(params, qd, Wd, qcodes, ws)
-        ev[i][0].record()
-        mp.magicpig_sampled_attention(params, qd, s["K"], s["V"], s["mu"], s["codes"], qcodes, out,
-                                      workspace=ws)
-        ev[i][1].record()
+    e0.record()
+    if graph is not None:
+        graph.replay()
+    else:
+        for i in range(args.steps):
+            step(i)
+    e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
-    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    gpu_ms_per_step = e0.elapsed_time(e1) / args.steps
     heads = w.batch * w.n_q_heads
     value = heads / (ms_per_step * 1e-3)
+
+    # ---- per-kernel durations, live, with HIP events recorded between the kernels on the
+    # stream they run on (same steps, eager launches)
+    hip = ctypes.CDLL("libamdhip64.so")
+    n_ev = min(args.steps, 100)
+    evs = []
+    for _ in range(n_ev):
+        quad = []
+        for _ in range(5):
+            e = ctypes.c_void_p()
+            assert hip.hipEventCreate(ctypes.byref(e)) == 0
+            quad.append(e)
+        evs.append(quad)
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    for i in range(n_ev):
+        s = sets[i % len(sets)]
+        hip.hipEventRecord(evs[i][4], stream)
+        mp.magicpig_hash_query(params, qd, Wd, qcodes, ws)
+        mp.magicpig_profile_stage_events([e.value for e in evs[i][:4]])
+        mp.magicpig_sampled_attention(params, qd, s["K"], s["V"], s["mu"], s["codes"], qcodes, out,
+                                      workspace=ws)
+    mp.magicpig_profile_stage_events(None)
+    torch.cuda.synchronize()
+
+    def span(a, b):
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+        return ms.value
+    stage_ms = {
+        "hash_query": float(np.mean([span(q[4], q[0]) for q in evs])),
+        "collision_scan": float(np.mean([span(q[0], q[1]) for q in evs])),
+        "gather_estimate": float(np.mean([span(q[1], q[2]) for q in evs])),
+        "merge": float(np.mean([span(q[2], q[3]) for q in evs])),
+    }
+    for quad in evs:
+        for e in quad:
+            hip.hipEventDestroy(e)
+    scan_ms = stage_ms["collision_scan"]
 
     n_static = min(w.n_ctx, w.n_sink + w.n_local)
     scan_bytes = w.batch * w.n_kv_heads * max(w.n_ctx - n_static, 0) * w.K * w.L / 8.0
     gather_bytes = float((n_sampled + n_static).sum()) * 2 * 128 * (2 if w.dtype == "bf16" else 4)
     out_bytes = heads * 128 * 4
     alg_bytes = scan_bytes + gather_bytes + out_bytes
-    achieved = alg_bytes / (attn_ms * 1e-3) / 1e9
+    achieved = scan_bytes / (scan_ms * 1e-3) / 1e9
+    path_gbs = alg_bytes / ((scan_ms + stage_ms['gather_estimate'] + stage_ms['merge']) * 1e-3) / 1e9
 
     hash_flops = 2.0 * w.batch * w.n_kv_heads * w.n_ctx * 128 * w.K * w.L
     result = {
@@ -182,10 +243,13 @@ def main():
                    "step": "magicpig_hash_query + magicpig_sampled_attention"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "magicpig_sampled_attention (scan+compaction+gather+softmax, incl. merge)",
-                     "avg_launch_ms": attn_ms, "algorithmic_bytes": alg_bytes,
-                     "scan_bytes": scan_bytes, "gather_bytes": gather_bytes,
+                     "kernel": "collision_scan_kernel (dominant kernel of magicpig_sampled_attention)",
+                     "avg_launch_ms": scan_ms, "algorithmic_bytes": scan_bytes,
+                     "scan_plus_gather": {"algorithmic_bytes": alg_bytes, "gather_bytes": gather_bytes,
+                                          "achieved": path_gbs, "frac": path_gbs / HBM_PEAK_GBS,
+                                          "what": "scan + gather + merge kernels, bytes / summed durations"},
                      "mean_sampled_per_head": float(n_sampled.mean())},
+        "stage_ms": stage_ms, "launch": launch_mode, "gpu_ms_per_step": gpu_ms_per_step,
         "prefill_hash": {"ms": prefill_ms, "keys": w.batch * w.n_kv_heads * w.n_ctx,
                          "tflops": hash_flops / (prefill_ms * 1e-3) / 1e12,
                          "frac_of_bf16_mfma_peak": hash_flops / (prefill_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,

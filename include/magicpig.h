@@ -125,6 +125,12 @@ int magicpig_sampled_attention(const magicpig_params* params, const void* q, con
                                int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Profiling aid (the only per-thread setting the library keeps): when `events` is non-NULL it
+ * points to four hipEvent_t handles which later magicpig_sampled_attention calls on this host
+ * thread record on their stream - before the collision scan, after it, after the gather /
+ * estimator kernel, after the merge.  NULL switches the recording off again. */
+void magicpig_profile_stage_events(void* const* events);
+
 const char* magicpig_status_string(int status);
 /* Text of the HIP error behind the most recent MAGICPIG_LAUNCH_FAILED on this thread. */
 const char* magicpig_last_hip_error(void);

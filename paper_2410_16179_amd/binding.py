@@ -39,7 +39,7 @@ EXPORTS = (
     "magicpig_code_words_per_key", "magicpig_key_code_bytes", "magicpig_query_code_bytes",
     "magicpig_key_code_index", "magicpig_workspace_bytes", "magicpig_key_mean",
     "magicpig_hash_keys", "magicpig_hash_query", "magicpig_sampled_attention",
-    "magicpig_status_string", "magicpig_last_hip_error",
+    "magicpig_status_string", "magicpig_last_hip_error", "magicpig_profile_stage_events",
 )
 
 _lib = None
@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
     L.magicpig_sampled_attention.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
     L.magicpig_status_string.restype, L.magicpig_status_string.argtypes = ctypes.c_char_p, [ctypes.c_int]
     L.magicpig_last_hip_error.restype, L.magicpig_last_hip_error.argtypes = ctypes.c_char_p, []
+    L.magicpig_profile_stage_events.restype = None
+    L.magicpig_profile_stage_events.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
     _lib = L
     return L
 
@@ -147,6 +149,15 @@ def magicpig_sampled_attention(params, q, K_cache, V_cache, mu, key_codes, q_cod
         ctypes.byref(params), _ptr(q), _ptr(K_cache), _ptr(V_cache), _ptr(mu), _ptr(key_codes),
         _ptr(q_codes), _ptr(out), _ptr(dbg_counts), _ptr(dbg_cand), _ptr(dbg_ncand), cap,
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def magicpig_profile_stage_events(events) -> None:
+    """events: None, or four hipEvent_t handles (ints) recorded around the decode kernels."""
+    if events is None:
+        lib().magicpig_profile_stage_events(None)
+    else:
+        arr = (ctypes.c_void_p * 4)(*events)
+        lib().magicpig_profile_stage_events(arr)
 
 
 # ---- buffer helpers (allocation and layout only) ---------------------------------------------

@@ -7,6 +7,7 @@
 // summation order.
 #include "mp_common.h"
 #include "exact_dot.h"
+#include "device_utils.h"
 #include <hip/hip_bf16.h>
 
 namespace mp {
@@ -50,22 +51,34 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
     const bool col_ok = t < a.L;
     const int j = col_ok ? t * a.K + b : 0;
     double s = 0.0, mag = 0.0;
-    // 64 projector and 64 vector elements are requested before any is used, so the 128-long
-    // dot product costs two memory round trips instead of one per element
-    for (int d0 = 0; d0 < kHeadDim; d0 += 64) {
-      double wv[64], xv[64];
+    // All 128 projector elements of the column and the whole vector are requested before any
+    // is used (their addresses do not depend on data), so the dot product costs one memory
+    // round trip; the vector is read as 16-byte pieces shared by the 32 lanes of its half.
+    {
+      float wf[kHeadDim], xf[kHeadDim];
 #pragma unroll
-      for (int i = 0; i < 64; ++i) {
-        wv[i] = load_elem<FP32>(a.W, (int64_t)(d0 + i) * ncol + j);
-        xv[i] = load_elem<FP32>(a.X, xbase + d0 + i);
+      for (int i = 0; i < kHeadDim; ++i) {
+        if constexpr (FP32) {
+          wf[i] = reinterpret_cast<const float*>(a.W)[(int64_t)i * ncol + j];
+        } else {
+          wf[i] = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(a.W)[(int64_t)i * ncol + j] << 16);
+        }
       }
 #pragma unroll
-      for (int i = 0; i < 64; ++i) {
-        const double p = xv[i] * wv[i];
+      for (int i = 0; i < kHeadDim; i += 8) {
+        float v[8];
+        load8<FP32>(a.X, xbase + i, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) xf[i + e] = v[e];
+      }
+#pragma unroll
+      for (int i = 0; i < kHeadDim; ++i) {
+        const double wv = (double)wf[i];
+        const double p = (double)xf[i] * wv;
         s += p;
         mag += fabs(p);
         if (mu) {
-          const double pm = (double)mu[d0 + i] * wv[i];
+          const double pm = (double)mu[i] * wv;
           s -= pm;
           mag += fabs(pm);
         }

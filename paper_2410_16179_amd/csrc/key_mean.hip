@@ -3,25 +3,9 @@
 // rows_per_chunk/16 rows of one 8-element column group in float32, the workgroup and the
 // chunks are combined in float64 in a fixed order, so the result is reproducible.
 #include "mp_common.h"
+#include "device_utils.h"
 
 namespace mp {
-
-template <bool FP32>
-__device__ inline void load8(const void* base, int64_t elem, float (&v)[8]) {
-  if constexpr (FP32) {
-    const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + elem);
-    const float4 a = p[0], b = p[1];
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-  } else {
-    const uint4 r = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(base) + elem);
-    const uint32_t u[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      v[2 * i] = __uint_as_float(u[i] << 16);
-      v[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
-    }
-  }
-}
 
 template <bool FP32>
 __global__ __launch_bounds__(256) void key_mean_partial_kernel(MeanArgs a) {

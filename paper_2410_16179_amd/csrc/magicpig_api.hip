@@ -7,6 +7,8 @@
 namespace {
 
 thread_local std::string g_last_hip_error;
+thread_local hipEvent_t g_stage_events[4];
+thread_local bool g_have_stage_events = false;
 
 int fail_hip(hipError_t e) {
   g_last_hip_error = hipGetErrorString(e);
@@ -197,8 +199,15 @@ int magicpig_sampled_attention(const magicpig_params* p, const void* q, const vo
   a.ks_b = p->k_stride_b; a.ks_h = p->k_stride_h; a.ks_n = p->k_stride_n;
   a.vs_b = p->v_stride_b; a.vs_h = p->v_stride_h; a.vs_n = p->v_stride_n;
   a.scale = 0.08838834764831845f;   // 1/sqrt(128)
-  const hipError_t e = mp::launch_sampled_attention(a, reinterpret_cast<hipStream_t>(hip_stream));
+  const hipError_t e = mp::launch_sampled_attention(a, reinterpret_cast<hipStream_t>(hip_stream),
+                                                    g_have_stage_events ? g_stage_events : nullptr);
   return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
+}
+
+void magicpig_profile_stage_events(void* const* events) {
+  g_have_stage_events = events != nullptr;
+  if (events)
+    for (int i = 0; i < 4; ++i) g_stage_events[i] = reinterpret_cast<hipEvent_t>(events[i]);
 }
 
 const char* magicpig_status_string(int status) {

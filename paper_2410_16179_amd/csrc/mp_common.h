@@ -64,6 +64,6 @@ constexpr int kRangeBlocks = 16;      // key blocks per gather wavefront (1024 k
 // host-side launchers (defined next to their kernels)
 hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s);
 hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s);
-hipError_t launch_sampled_attention(const AttnArgs& a, hipStream_t s);
+hipError_t launch_sampled_attention(const AttnArgs& a, hipStream_t s, hipEvent_t const* stage_events);
 
 }  // namespace mp

@@ -346,7 +346,7 @@ static hipError_t launch_scan(const AttnArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_sampled_attention(const AttnArgs& a, hipStream_t s) {
+hipError_t launch_sampled_attention(const AttnArgs& a, hipStream_t s, hipEvent_t const* ev) {
   const int64_t heads = (int64_t)a.B * a.Hq;
   if (heads <= 0) return hipSuccess;
   if (a.nranges <= 0) {      // no keys: the output is defined as the zero vector
@@ -354,15 +354,19 @@ hipError_t launch_sampled_attention(const AttnArgs& a, hipStream_t s) {
                        a.out, heads * kHeadDim);
     return hipGetLastError();
   }
-  hipError_t e = launch_scan(a, s);
-  if (e != hipSuccess) return e;
+  hipError_t e;
+  if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return e;
+  if ((e = launch_scan(a, s)) != hipSuccess) return e;
+  if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return e;
   const dim3 grid((unsigned)a.nranges, (unsigned)(a.B * a.Hkv)), block(64 * (a.Hq / a.Hkv));
   if (a.is_fp32) hipLaunchKernelGGL(gather_estimate_kernel<true>, grid, block, 0, s, a);
   else hipLaunchKernelGGL(gather_estimate_kernel<false>, grid, block, 0, s, a);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
   hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)heads), dim3(256), 0, s, a);
-  return hipGetLastError();
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (ev && (e = hipEventRecord(ev[3], s)) != hipSuccess) return e;
+  return hipSuccess;
 }
 
 }  // namespace mp
