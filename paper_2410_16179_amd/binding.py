@@ -40,6 +40,7 @@ EXPORTS = (
     "magicpig_key_code_index", "magicpig_workspace_bytes", "magicpig_key_mean",
     "magicpig_hash_keys", "magicpig_hash_query", "magicpig_sampled_attention",
     "magicpig_status_string", "magicpig_last_hip_error", "magicpig_profile_stage_events",
+    "magicpig_hash_keys_stats_offset",
 )
 
 _lib = None
@@ -56,7 +57,8 @@ def lib() -> ctypes.CDLL:
     P = ctypes.POINTER(magicpig_params)
     vp, sz, i32, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int64
     for name in ("magicpig_code_words_per_key", "magicpig_key_code_bytes",
-                 "magicpig_query_code_bytes", "magicpig_workspace_bytes"):
+                 "magicpig_query_code_bytes", "magicpig_workspace_bytes",
+                 "magicpig_hash_keys_stats_offset"):
         getattr(L, name).restype, getattr(L, name).argtypes = sz, [P]
     L.magicpig_key_code_index.restype = sz
     L.magicpig_key_code_index.argtypes = [P, i32, i32, i64, i32]
@@ -119,6 +121,18 @@ def magicpig_query_code_bytes(params) -> int:
 
 def magicpig_workspace_bytes(params) -> int:
     return lib().magicpig_workspace_bytes(ctypes.byref(params))
+
+
+def magicpig_hash_keys_stats_offset(params) -> int:
+    return lib().magicpig_hash_keys_stats_offset(ctypes.byref(params))
+
+
+def hash_keys_stats(params, workspace) -> dict:
+    """Reads the statistics a bf16 magicpig_hash_keys call left in its workspace (synchronises)."""
+    off = magicpig_hash_keys_stats_offset(params)
+    raw = workspace[off:off + 12].cpu().numpy().view(np.uint32)
+    return {"w_max_norm": float(raw[:1].view(np.float32)[0]), "rechecked": int(raw[1]),
+            "overflowed": bool(raw[2])}
 
 
 def magicpig_key_code_index(params, b, g, key, word) -> int:

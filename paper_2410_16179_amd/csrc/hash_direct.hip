@@ -24,6 +24,7 @@ __device__ inline double load_elem(const void* p, int64_t idx) {
 template <bool FP32>
 __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
   __shared__ long long limbs[4][kLimbs];
+  if (a.run_flag && *a.run_flag == 0) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   if (lane < kLimbs) limbs[wave][lane] = 0;
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");

@@ -1,0 +1,376 @@
+// SimHash coding of cached bf16 keys on the matrix cores (Sec. 4.3 "Hash function
+// selection"; Sec. 4.4 (3): the K*L random projections are the compute-bound step).
+//
+// The projection is a [keys x 128] x [128 x K*L] contraction.  It runs as bf16 MFMA
+// (v_mfma_f32_32x32x16_bf16) with the projector as the A operand and 32 keys as the B
+// operand, so an accumulator register of a lane holds one (projection, key) pair with
+// lane%32 = key: the 32 sign bits of a code word are assembled inside one lane with one
+// funnel shift per element and no cross-lane traffic.  Rows of the A operand are
+// arranged (prep_projector_kernel) so that the two lane halves of two consecutive MFMA
+// tiles produce two complete code words; one half-swap then gives every lane the four
+// words of "its" key and a wavefront stores a contiguous kilobyte of the code layout.
+//
+// Bit-exactness.  The hash bit is the sign of the exact sum  k.W_j - mu.W_j.  The MFMA
+// result acc ~ k.W_j - fl(mu.W_j) (the threshold enters as the initial accumulator) differs
+// from it by at most  bound_i = kGamma * (|k_i| + |mu|) * max_j |W_j|:  every bf16 product is
+// exact in float32, each of the 129 additions on any summation order rounds (or truncates)
+// with relative error <= 2^-23, and sum|terms| <= (|k_i| + |mu|) |W_j| by Cauchy-Schwarz.
+// Elements with |acc| <= bound_i (a few in ten thousand) are listed and re-evaluated by
+// recheck_kernel in float64 with the exact fallback of exact_dot.h, which patches the bit.
+// If the list overflows, a flag makes the direct float64 kernel redo the whole call.
+#include "mp_common.h"
+#include "exact_dot.h"
+#include "device_utils.h"
+
+namespace mp {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+// 129 roundings of relative size 2^-23 in the worst (sequential, truncating) order:
+// (1 + 2^-23)^129 - 1 < 2^-15.98; 2^-15.9 leaves a few per cent on top.
+constexpr float kGamma = 1.6355e-5f;
+constexpr int kListCapLocal = 1536;       // flagged elements a workgroup can hold in LDS
+
+// Projection handled by row rho (0..31) of MFMA tile T: tile pair T/2 makes code words
+// x = 2*(T/2) + eta, eta = (rho/4)%2 being the lane half that receives the row; the row is
+// accumulator register r = 4*(rho/8) + rho%4 of that half, inserted as element 16*(T%2) + r
+// of the word, most significant bit first.
+__host__ __device__ inline void tile_row_to_bit(int T, int rho, int* x, int* beta) {
+  const int eta = (rho >> 2) & 1;
+  const int r = 4 * (rho >> 3) + (rho & 3);
+  *x = 2 * (T >> 1) + eta;
+  *beta = 31 - (16 * (T & 1) + r);
+}
+
+__global__ void prep_zero_kernel(HashMfmaArgs a) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    *a.wmax_bits = 0u;
+    *a.list_count = 0u;
+    *a.overflow = 0;
+  }
+}
+
+// A-operand fragments, transposed bf16 copy of W for the recheck, max column norm.
+// One thread per (tile row, 8-element piece of d).
+__global__ __launch_bounds__(256) void prep_projector_kernel(HashMfmaArgs a) {
+  const int gid = blockIdx.x * 256 + threadIdx.x;
+  const int row = gid >> 4, piece = gid & 15;        // row = T*32 + rho
+  if (row >= a.ntiles * 32) return;
+  const int T = row >> 5, rho = row & 31;
+  int x, beta;
+  tile_row_to_bit(T, rho, &x, &beta);
+  const int t = 32 * (x / a.K) + beta;
+  const bool real = x < a.NW && t < a.L;
+  const int j = real ? t * a.K + x % a.K : 0;
+  const int ncol = a.K * a.L;
+  const uint16_t* W = reinterpret_cast<const uint16_t*>(a.W);
+  uint16_t v[8];
+  float ss = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    v[e] = real ? W[(int64_t)(piece * 8 + e) * ncol + j] : (uint16_t)0;
+    const float f = __uint_as_float((uint32_t)v[e] << 16);
+    ss += f * f;
+  }
+  // fragment order: k-step s = piece/2, lane = (piece%2)*32 + rho, eight bf16 per lane
+  const int s = piece >> 1, lane = (piece & 1) * 32 + rho;
+  uint4 pk;
+  pk.x = v[0] | ((uint32_t)v[1] << 16); pk.y = v[2] | ((uint32_t)v[3] << 16);
+  pk.z = v[4] | ((uint32_t)v[5] << 16); pk.w = v[6] | ((uint32_t)v[7] << 16);
+  reinterpret_cast<uint4*>(a.afrag)[((int64_t)T * 8 + s) * 64 + lane] = pk;
+  if (real) {
+    reinterpret_cast<uint4*>(a.wt)[(int64_t)j * 16 + piece] = pk;
+    ss = row_sum16(ss);                                // the 16 pieces of a row sit in one DPP row
+    if (piece == 0) atomicMax(a.wmax_bits, __float_as_uint(sqrtf(ss) * 1.000001f));
+  }
+}
+
+// Per (batch, KV head): initial accumulators -fl(mu.W_j) in fragment order, and |mu|.
+__global__ __launch_bounds__(256) void prep_threshold_kernel(HashMfmaArgs a) {
+  const int unit = blockIdx.y;
+  const int row = blockIdx.x * 256 + threadIdx.x;
+  const float* mu = a.mu ? a.mu + (int64_t)unit * kHeadDim : nullptr;
+  if (row == 0) {
+    double ss = 0.0;
+    if (mu) for (int d = 0; d < kHeadDim; ++d) ss += (double)mu[d] * (double)mu[d];
+    a.munorm[unit] = (float)sqrt(ss) * 1.000001f;
+  }
+  if (row >= a.ntiles * 32) return;
+  const int T = row >> 5, rho = row & 31;
+  int x, beta;
+  tile_row_to_bit(T, rho, &x, &beta);
+  const int t = 32 * (x / a.K) + beta;
+  const bool real = x < a.NW && t < a.L;
+  float c = -INFINITY;                                 // pad rows: never >= 0, never flagged
+  if (real) {
+    const int j = t * a.K + x % a.K;
+    double th = 0.0;
+    if (mu) {
+      const uint16_t* wt = reinterpret_cast<const uint16_t*>(a.wt) + (int64_t)j * kHeadDim;
+      for (int d = 0; d < kHeadDim; ++d) th += (double)mu[d] * (double)__uint_as_float((uint32_t)wt[d] << 16);
+    }
+    c = 0.0f - (float)th;                              // +0 when the threshold is zero
+  }
+  const int eta = (rho >> 2) & 1, r = 4 * (rho >> 3) + (rho & 3);
+  a.thr[(((int64_t)unit * a.ntiles + T) * 2 + eta) * 16 + r] = c;
+}
+
+__global__ __launch_bounds__(256) void hash_keys_mfma_kernel(HashMfmaArgs a) {
+  __shared__ uint4 sA[2][4 * 8 * 64];                  // two stages of one word quad: 4 tiles x 8 k-steps
+  __shared__ float sThr[2][4 * 2 * 16];
+  __shared__ unsigned long long sList[kListCapLocal];
+  __shared__ unsigned sCount, sBase;
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int unit = blockIdx.y;
+  const int kap = lane & 31, hh = lane >> 5;
+  const int64_t first = a.first_key, last = a.first_key + a.n_keys;   // [first, last)
+  const int64_t cb = first / kBlockKeys + (int64_t)blockIdx.x * 4 + wave;   // my code block
+  const bool wave_on = cb * kBlockKeys < last;
+  if (tid == 0) sCount = 0;
+
+  // ---- B operand: my 64 keys, resident in registers for the whole kernel ----
+  const uint16_t* Kc = reinterpret_cast<const uint16_t*>(a.Kc);
+  const int64_t ubase = (int64_t)(unit / a.n_kv_heads) * a.stride_b + (int64_t)(unit % a.n_kv_heads) * a.stride_h;
+  bf16x8 B[2][8];
+  float bnd[2];
+  int64_t key[2];
+  const float wmax = __uint_as_float(*a.wmax_bits);
+  const float munorm = a.munorm[unit];
+#pragma unroll
+  for (int bt = 0; bt < 2; ++bt) {
+    key[bt] = cb * kBlockKeys + bt * 32 + kap;
+    const bool ok = wave_on && key[bt] >= first && key[bt] < last;
+    const int64_t krow = ok ? key[bt] : first;          // any valid row for masked lanes
+    float ss = 0.f;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(Kc + ubase + krow * a.stride_n + s * 16 + hh * 8);
+      B[bt][s] = __builtin_bit_cast(bf16x8, raw);
+      const uint32_t u[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float lo = __uint_as_float(u[i] << 16), hi = __uint_as_float(u[i] & 0xffff0000u);
+        ss += lo * lo + hi * hi;
+      }
+    }
+    ss += __shfl_xor(ss, 32);                            // the other half of the row
+    bnd[bt] = ok ? kGamma * (sqrtf(ss) * 1.000001f + munorm) * wmax + 1e-30f : -1.f;
+  }
+
+  const int nquads = (a.ntiles + 3) / 4;
+  const uint4* gA = reinterpret_cast<const uint4*>(a.afrag);
+  const float* gThr = a.thr + (int64_t)unit * a.ntiles * 32;
+  const int NW = a.NW;
+  uint32_t* blk_codes = a.codes + ((int64_t)unit * a.blocks_cap + cb) * (kBlockKeys * (int64_t)NW);
+
+  // stage 0
+  {
+    uint4 st[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int idx = i * 256 + tid;
+      st[i] = idx < a.ntiles * 512 ? gA[idx] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sA[0][i * 256 + tid] = st[i];
+    if (tid < 128) sThr[0][tid] = tid < a.ntiles * 32 ? gThr[tid] : -INFINITY;
+  }
+  __syncthreads();
+
+  for (int q = 0; q < nquads; ++q) {
+    const int cur = q & 1;
+    // request the next quad's fragments; they are written to LDS after this quad's math
+    uint4 st[8];
+    float stt = -INFINITY;
+    const bool more = q + 1 < nquads;
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int idx = (q + 1) * 2048 + i * 256 + tid;
+        st[i] = idx < a.ntiles * 512 ? gA[idx] : make_uint4(0, 0, 0, 0);
+      }
+      if (tid < 128) stt = (q + 1) * 128 + tid < a.ntiles * 32 ? gThr[(q + 1) * 128 + tid] : -INFINITY;
+    }
+
+    if (wave_on) {
+      uint32_t wd[2][2];                                 // [pair][key tile] inverted bits, MSB first
+#pragma unroll
+      for (int pair = 0; pair < 2; ++pair) {
+        wd[pair][0] = 0; wd[pair][1] = 0;
+#pragma unroll
+        for (int tau = 0; tau < 2; ++tau) {
+          const int tile = pair * 2 + tau;
+          f32x16 c;
+#pragma unroll
+          for (int v4 = 0; v4 < 4; ++v4) {
+            const float4 t4 = *reinterpret_cast<const float4*>(&sThr[cur][(tile * 2 + hh) * 16 + v4 * 4]);
+            c[v4 * 4] = t4.x; c[v4 * 4 + 1] = t4.y; c[v4 * 4 + 2] = t4.z; c[v4 * 4 + 3] = t4.w;
+          }
+          f32x16 acc0 = c, acc1 = c;
+#pragma unroll
+          for (int s = 0; s < 8; ++s) {
+            const bf16x8 af = __builtin_bit_cast(bf16x8, sA[cur][(tile * 8 + s) * 64 + lane]);
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, B[0][s], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, B[1][s], acc1, 0, 0, 0);
+          }
+          float mn0 = INFINITY, mn1 = INFINITY;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            // funnel shift: word = (word << 1) | sign(acc); the sign bit is exact for ">= 0"
+            // because the accumulator starts from +0 or a non-zero threshold, never -0
+            wd[pair][0] = __builtin_amdgcn_alignbit(wd[pair][0], __float_as_uint(acc0[r]), 31);
+            wd[pair][1] = __builtin_amdgcn_alignbit(wd[pair][1], __float_as_uint(acc1[r]), 31);
+            mn0 = fminf(mn0, fabsf(acc0[r]));
+            mn1 = fminf(mn1, fabsf(acc1[r]));
+          }
+          if (__ballot(mn0 <= bnd[0] || mn1 <= bnd[1])) {   // some element too close to zero
+            const int T = q * 4 + tile;
+            const int x = 2 * (T >> 1) + hh;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+#pragma unroll
+              for (int bt = 0; bt < 2; ++bt) {
+                const float v = bt ? acc1[r] : acc0[r];
+                if (fabsf(v) <= bnd[bt]) {
+                  const int beta = 31 - (16 * (T & 1) + r);
+                  const int j = (32 * (x / a.K) + beta) * a.K + x % a.K;
+                  const unsigned pos = atomicAdd(&sCount, 1u);
+                  if (pos < kListCapLocal)
+                    sList[pos] = ((unsigned long long)((int64_t)unit * a.n_cap + key[bt]) << 16) | (unsigned)j;
+                }
+              }
+            }
+          }
+        }
+        wd[pair][0] = ~wd[pair][0];
+        wd[pair][1] = ~wd[pair][1];
+      }
+      // lanes < 32 hold words x0 (pair 0) and x0+2 (pair 1) of keys kap / 32+kap, lanes >= 32
+      // hold x0+1 and x0+3: one half-swap per pair leaves lane l with the words of key l
+      const auto s0 = __builtin_amdgcn_permlane32_swap(wd[0][0], wd[0][1], false, false);
+      const auto s1 = __builtin_amdgcn_permlane32_swap(wd[1][0], wd[1][1], false, false);
+      const uint32_t w4[4] = {s0[0], s0[1], s1[0], s1[1]};
+      const int64_t mykey = cb * kBlockKeys + lane;
+      if (mykey >= first && mykey < last) {
+        const int x0 = q * 4;
+        if (x0 + 4 <= NW) {
+          *reinterpret_cast<uint4*>(blk_codes + q * 256 + lane * 4) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+        } else {
+          const int rem = NW - x0;                       // 1..3 words in the last group
+          for (int i = 0; i < rem; ++i) blk_codes[q * 256 + lane * rem + i] = w4[i];
+        }
+      }
+    }
+
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sA[cur ^ 1][i * 256 + tid] = st[i];
+      if (tid < 128) sThr[cur ^ 1][tid] = stt;
+    }
+    __syncthreads();
+  }
+
+  // ---- hand the flagged elements to the recheck kernel ----
+  const unsigned cnt = sCount;                           // visible: barrier above
+  if (cnt > kListCapLocal) { if (tid == 0) *a.overflow = 1; }
+  const unsigned keep = cnt < kListCapLocal ? cnt : kListCapLocal;
+  if (tid == 0) sBase = keep ? atomicAdd(a.list_count, keep) : 0u;
+  __syncthreads();
+  const unsigned base = sBase;
+  for (unsigned i = tid; i < keep; i += 256) {
+    if ((uint64_t)base + i < a.list_cap) a.list[base + i] = sList[i];
+    else *a.overflow = 1;
+  }
+}
+
+// Float64 / exact re-evaluation of the listed (key, projection) pairs; one lane per pair.
+__global__ __launch_bounds__(256) void recheck_kernel(HashMfmaArgs a) {
+  __shared__ long long limbs[4][kLimbs];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (lane < kLimbs) limbs[wave][lane] = 0;
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  if (*a.overflow) return;                               // the direct kernel redoes everything
+  const uint64_t count = *a.list_count < a.list_cap ? *a.list_count : a.list_cap;
+  const uint16_t* Kc = reinterpret_cast<const uint16_t*>(a.Kc);
+  const uint16_t* WT = reinterpret_cast<const uint16_t*>(a.wt);
+  const uint64_t stride = (uint64_t)gridDim.x * 256;
+  for (uint64_t i0 = (uint64_t)blockIdx.x * 256 + wave * 64; i0 < count; i0 += stride) {
+    const uint64_t i = i0 + lane;
+    const bool on = i < count;
+    const unsigned long long e = on ? a.list[i] : a.list[i0];
+    const int j = (int)(e & 0xffff);
+    const int64_t gk = (int64_t)(e >> 16);
+    const int64_t unit = gk / a.n_cap, k = gk % a.n_cap;
+    const int64_t xoff = (unit / a.n_kv_heads) * a.stride_b + (unit % a.n_kv_heads) * a.stride_h + k * a.stride_n;
+    const float* mu = a.mu ? a.mu + unit * kHeadDim : nullptr;
+    double s = 0.0, mag = 0.0;
+#pragma unroll 4
+    for (int p = 0; p < 16; ++p) {
+      float kv[8], wv[8];
+      load8<false>(Kc, xoff + p * 8, kv);
+      load8<false>(WT, (int64_t)j * kHeadDim + p * 8, wv);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const double w = (double)wv[t];
+        const double pr = (double)kv[t] * w;
+        s += pr;
+        mag += fabs(pr);
+        if (mu) {
+          const double pm = (double)mu[p * 8 + t] * w;
+          s -= pm;
+          mag += fabs(pm);
+        }
+      }
+    }
+    bool bit = s >= 0.0;
+    const bool unsure = on && mag > 0.0 && fabs(s) <= kF64Slack * mag;
+    uint64_t pending = __ballot(unsure);
+    while (pending) {
+      const int src = __ffsll((unsigned long long)pending) - 1;
+      const int64_t sx = ((int64_t)__shfl((int)(xoff >> 32), src) << 32) | (uint32_t)__shfl((int)(xoff & 0xffffffff), src);
+      const int sj = __shfl(j, src);
+      const int64_t su = ((int64_t)__shfl((int)(unit >> 32), src) << 32) | (uint32_t)__shfl((int)(unit & 0xffffffff), src);
+      const float* smu = a.mu ? a.mu + su * kHeadDim : nullptr;
+      const bool r = exact_sign_nonneg_wave(
+          limbs[wave],
+          [&](int d) { return (double)__uint_as_float((uint32_t)Kc[sx + d] << 16); },
+          [&](int d) { return (double)__uint_as_float((uint32_t)WT[(int64_t)sj * kHeadDim + d] << 16); },
+          [&](int d) { return smu ? (double)smu[d] : 0.0; }, smu != nullptr);
+      if (lane == src) bit = r;
+      pending &= pending - 1;
+    }
+    if (on) {
+      const int t = j / a.K, b = j % a.K;
+      const int x = (t >> 5) * a.K + b;
+      const uint32_t mask = 1u << (t & 31);
+      uint32_t* word = a.codes + (unit * a.blocks_cap + k / kBlockKeys) * (kBlockKeys * (int64_t)a.NW) +
+                       slot_in_block(a.NW, x, (int)(k % kBlockKeys));
+      if (bit) atomicOr(word, mask);
+      else atomicAnd(word, ~mask);
+    }
+  }
+}
+
+hipError_t launch_hash_keys_mfma(const HashMfmaArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(prep_zero_kernel, dim3(1), dim3(64), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int rows = a.ntiles * 32;
+  hipLaunchKernelGGL(prep_projector_kernel, dim3((unsigned)((rows * 16 + 255) / 256)), dim3(256), 0, s, a);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(prep_threshold_kernel, dim3((unsigned)((rows + 255) / 256), (unsigned)a.units), dim3(256), 0, s, a);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const int64_t first_blk = a.first_key / kBlockKeys;
+  const int64_t last_blk = (a.first_key + a.n_keys - 1) / kBlockKeys;
+  const int64_t nblk = last_blk - first_blk + 1;
+  hipLaunchKernelGGL(hash_keys_mfma_kernel, dim3((unsigned)((nblk + 3) / 4), (unsigned)a.units), dim3(256), 0, s, a);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(recheck_kernel, dim3(2048), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace mp

@@ -49,6 +49,29 @@ size_t ws_mean(const magicpig_params* p) {
   return align256((size_t)(units * nchunk * mp::kHeadDim) * sizeof(double));
 }
 
+// key-hashing workspace (bf16, matrix cores):
+// [A fragments | W transposed | thresholds | |mu| | scalars | flagged-element list]
+struct HashWs { size_t afrag_off, wt_off, thr_off, munorm_off, scalar_off, list_off, total; int ntiles; uint64_t list_cap; };
+HashWs ws_hash_layout(const magicpig_params* p) {
+  HashWs w{};
+  const int NW = mp::code_words(p->K, p->L);
+  const size_t units = (size_t)p->batch * p->n_kv_heads;
+  w.ntiles = 2 * ((NW + 1) / 2);
+  const size_t nquads = (w.ntiles + 3) / 4;
+  w.afrag_off = 0;
+  w.wt_off = align256(nquads * 4 * 8 * 64 * 16);
+  w.thr_off = w.wt_off + align256((size_t)p->K * p->L * mp::kHeadDim * 2);
+  w.munorm_off = w.thr_off + align256(units * w.ntiles * 32 * sizeof(float));
+  w.scalar_off = w.munorm_off + align256(units * sizeof(float));
+  w.list_off = w.scalar_off + 256;
+  // room for one flagged element in 512 (a few in ten thousand are expected), at least 64K
+  const uint64_t elems = (uint64_t)units * (uint64_t)p->n_cap * (uint64_t)(p->K * p->L);
+  w.list_cap = elems / 512 > 65536 ? elems / 512 : 65536;
+  w.total = w.list_off + align256(w.list_cap * sizeof(unsigned long long));
+  return w;
+}
+size_t ws_hash(const magicpig_params* p) { return p->dtype == MAGICPIG_BF16 ? ws_hash_layout(p).total : 256; }
+
 // decode workspace: [partials | ballots]
 struct AttnWs { size_t partial_off, masks_off, total; int nranges; };
 AttnWs ws_attention_layout(const magicpig_params* p) {
@@ -93,10 +116,16 @@ size_t magicpig_key_code_index(const magicpig_params* p, int32_t b, int32_t g, i
   return (size_t)(blk * mp::kBlockKeys * NW + mp::slot_in_block(NW, word, (int)(key % mp::kBlockKeys)));
 }
 
+size_t magicpig_hash_keys_stats_offset(const magicpig_params* p) {
+  if (check_params(p) != MAGICPIG_OK || p->dtype != MAGICPIG_BF16) return (size_t)-1;
+  return ws_hash_layout(p).scalar_off;
+}
+
 size_t magicpig_workspace_bytes(const magicpig_params* p) {
   if (check_params(p) != MAGICPIG_OK) return 0;
-  size_t a = ws_mean(p), b = ws_attention(p);
-  size_t m = a > b ? a : b;
+  size_t m = ws_mean(p);
+  if (ws_attention(p) > m) m = ws_attention(p);
+  if (ws_hash(p) > m) m = ws_hash(p);
   return m < 256 ? 256 : m;
 }
 
@@ -131,17 +160,41 @@ int magicpig_hash_keys(const magicpig_params* p, const void* K_cache, const floa
       (mu && !aligned16(mu)))
     return MAGICPIG_INVALID_ARG;
   if (workspace_bytes < magicpig_workspace_bytes(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
+  if (n_keys == 0 || p->batch == 0) return MAGICPIG_OK;
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   mp::HashDirectArgs a{};
   a.X = K_cache; a.W = W; a.mu = mu; a.codes = key_codes;
   a.is_fp32 = p->dtype == MAGICPIG_FP32;
   a.K = p->K; a.L = p->L; a.NW = mp::code_words(p->K, p->L);
   a.query_layout = 0;
-  a.n_keys = n_keys > 0 ? n_keys : 1; a.first_key = first_key;
+  a.n_keys = n_keys; a.first_key = first_key;
   a.n_kv_heads = p->n_kv_heads;
   a.stride_b = p->k_stride_b; a.stride_h = p->k_stride_h; a.stride_n = p->k_stride_n;
   a.blocks_cap = mp::key_blocks(p->n_cap);
   a.total_rows = (int64_t)p->batch * p->n_kv_heads * n_keys;
-  const hipError_t e = mp::launch_hash_direct(a, reinterpret_cast<hipStream_t>(hip_stream));
+  a.run_flag = nullptr;
+  if (p->dtype == MAGICPIG_BF16) {
+    // matrix-core path; the direct kernel runs afterwards only if its list overflowed
+    const HashWs wl = ws_hash_layout(p);
+    char* wsb = reinterpret_cast<char*>(workspace);
+    mp::HashMfmaArgs m{};
+    m.Kc = K_cache; m.W = W; m.mu = mu; m.codes = key_codes;
+    m.K = p->K; m.L = p->L; m.NW = a.NW; m.ntiles = wl.ntiles;
+    m.units = p->batch * p->n_kv_heads; m.n_kv_heads = p->n_kv_heads;
+    m.n_keys = n_keys; m.first_key = first_key; m.n_cap = p->n_cap; m.blocks_cap = a.blocks_cap;
+    m.stride_b = p->k_stride_b; m.stride_h = p->k_stride_h; m.stride_n = p->k_stride_n;
+    m.afrag = wsb + wl.afrag_off; m.wt = wsb + wl.wt_off;
+    m.thr = reinterpret_cast<float*>(wsb + wl.thr_off);
+    m.munorm = reinterpret_cast<float*>(wsb + wl.munorm_off);
+    m.wmax_bits = reinterpret_cast<unsigned*>(wsb + wl.scalar_off);
+    m.list_count = m.wmax_bits + 1;
+    m.overflow = reinterpret_cast<int*>(m.wmax_bits + 2);
+    m.list = reinterpret_cast<unsigned long long*>(wsb + wl.list_off); m.list_cap = wl.list_cap;
+    const hipError_t e = mp::launch_hash_keys_mfma(m, stream);
+    if (e != hipSuccess) return fail_hip(e);
+    a.run_flag = m.overflow;
+  }
+  const hipError_t e = mp::launch_hash_direct(a, stream);
   return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
 }
 

@@ -36,6 +36,23 @@ struct HashDirectArgs {
   int64_t stride_b, stride_h, stride_n;   // element strides (query layout: stride_n = 128, others 0)
   int64_t blocks_cap;   // code blocks per unit
   int64_t total_rows;
+  const int* run_flag;  // if not null the kernel does nothing unless *run_flag != 0
+};
+
+// Launch description of the matrix-core key hashing (bf16 keys).
+struct HashMfmaArgs {
+  const void* Kc; const void* W; const float* mu; uint32_t* codes;
+  int K, L, NW, ntiles, units, n_kv_heads;
+  int64_t n_keys, first_key, n_cap, blocks_cap;
+  int64_t stride_b, stride_h, stride_n;
+  // workspace pieces
+  void* afrag;                 // projector in MFMA A-fragment order, bf16
+  void* wt;                    // projector transposed [K*L][128], bf16
+  float* thr;                  // [units][ntiles][2][16] initial accumulators
+  float* munorm;               // [units]
+  unsigned* wmax_bits;         // max column norm of W (float bits)
+  unsigned* list_count; int* overflow;
+  unsigned long long* list; uint64_t list_cap;
 };
 
 struct MeanArgs {
@@ -63,6 +80,7 @@ constexpr int kRangeBlocks = 16;      // key blocks per gather wavefront (1024 k
 
 // host-side launchers (defined next to their kernels)
 hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s);
+hipError_t launch_hash_keys_mfma(const HashMfmaArgs& a, hipStream_t s);
 hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s);
 hipError_t launch_sampled_attention(const AttnArgs& a, hipStream_t s, hipEvent_t const* stage_events);
 

@@ -48,6 +48,14 @@ def run_case(oracle, w: wl.Workload, seed=0, alpha=0.8, use_mu=True, n_cap=None,
                 min_hits=w.min_hits, n_sink=w.n_sink, n_local=w.n_local)
     s.set_mu(mu)
     s.hash_keys(0, n)
+    if w.dtype == "bf16" and n >= 1000:
+        st = mp.hash_keys_stats(s.params, s.ws)
+        elems = w.batch * w.n_kv_heads * n * w.K * w.L
+        # the matrix-core path did the work: nothing overflowed, and only a small fraction
+        # of the projections was close enough to zero to need the exact re-evaluation
+        assert not st["overflowed"], st
+        assert 0 < st["rechecked"] < 2e-3 * elems, (st, elems)
+        print(f"   rechecked {st['rechecked']} of {elems} projections ({st['rechecked'] / elems:.2e})", flush=True)
     s.hash_query()
     pairs = heads if heads is not None else [(b, h) for b in range(w.batch) for h in range(w.n_q_heads)]
     if check_codes:
@@ -196,6 +204,20 @@ def test_hash_bits_follow_the_exact_sum(oracle):
     ref = oracle.hash_keys(rows2[0, 0], W, mu[0, 0], K, L)
     np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
     assert ref[0, 0] == 0          # x - mu = -2^-40 < 0 in both planes of table 0
+
+
+def test_overflow_of_the_recheck_list_falls_back_to_the_float64_kernel(oracle):
+    # all-zero keys: every matrix-core result is exactly zero, every projection is flagged,
+    # the list overflows and the direct kernel must produce the codes (all ones: 0 >= 0)
+    w = wl.scaled(wl.CONFIGS["C2"], n_ctx=512, n_q_heads=4, n_kv_heads=1)
+    data = wl.generate(w)
+    Kz = np.zeros_like(data["K"])
+    s = Session(K=w.K, L=w.L, dtype="bf16", Kc=Kz, Vc=data["V"], q=data["q"], W=data["W"])
+    s.hash_keys()
+    assert mp.hash_keys_stats(s.params, s.ws)["overflowed"]
+    ref = oracle.hash_keys(Kz[0, 0], data["W"], None, w.K, w.L)
+    np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
+    assert np.all(ref == (1 << w.K) - 1)
 
 
 def test_key_mean(oracle):
