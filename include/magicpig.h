@@ -102,11 +102,12 @@ int magicpig_hash_keys(const magicpig_params* params, const void* K_cache, const
                        const void* W, int64_t first_key, int64_t n_keys, uint32_t* key_codes,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Byte offset, inside the workspace a bf16 magicpig_hash_keys call used, of three uint32
- * statistics of that call: { float bits of max_j |W_j|, number of (key, projection) pairs whose
- * matrix-core result was too close to zero and was re-evaluated exactly, 1 if that list
- * overflowed and the whole call was redone by the float64 kernel }.  (size_t)-1 when the
- * params are invalid or not bf16. */
+/* Byte offset, inside the workspace a bf16 magicpig_hash_keys call used, of four uint32
+ * statistics of that call: { float bits of max_j |W_j|; number of (key, projection) pairs that
+ * did not fit a workgroup's own re-evaluation list and went through the global one; 1 if the
+ * global list overflowed and the whole call was redone by the float64 kernel; total number of
+ * pairs whose matrix-core result was too close to zero and was re-evaluated exactly }.
+ * (size_t)-1 when the params are invalid or not bf16. */
 size_t magicpig_hash_keys_stats_offset(const magicpig_params* params);
 
 /* SimHash codes of the decode queries (Algorithm 1 "Encode(q, W)"); queries are not centered. */

@@ -130,9 +130,9 @@ def magicpig_hash_keys_stats_offset(params) -> int:
 def hash_keys_stats(params, workspace) -> dict:
     """Reads the statistics a bf16 magicpig_hash_keys call left in its workspace (synchronises)."""
     off = magicpig_hash_keys_stats_offset(params)
-    raw = workspace[off:off + 12].cpu().numpy().view(np.uint32)
-    return {"w_max_norm": float(raw[:1].view(np.float32)[0]), "rechecked": int(raw[1]),
-            "overflowed": bool(raw[2])}
+    raw = workspace[off:off + 16].cpu().numpy().view(np.uint32)
+    return {"w_max_norm": float(raw[:1].view(np.float32)[0]), "spilled": int(raw[1]),
+            "overflowed": bool(raw[2]), "rechecked": int(raw[3])}
 
 
 def magicpig_key_code_index(params, b, g, key, word) -> int:

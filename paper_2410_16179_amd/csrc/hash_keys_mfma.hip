@@ -15,9 +15,10 @@
 // from it by at most  bound_i = kGamma * (|k_i| + |mu|) * max_j |W_j|:  every bf16 product is
 // exact in float32, each of the 129 additions on any summation order rounds (or truncates)
 // with relative error <= 2^-23, and sum|terms| <= (|k_i| + |mu|) |W_j| by Cauchy-Schwarz.
-// Elements with |acc| <= bound_i (a few in ten thousand) are listed and re-evaluated by
-// recheck_kernel in float64 with the exact fallback of exact_dot.h, which patches the bit.
-// If the list overflows, a flag makes the direct float64 kernel redo the whole call.
+// Elements with |acc| <= bound_i (a few in ten thousand) are listed in LDS and re-evaluated
+// at the end of the workgroup in float64 with the exact fallback of exact_dot.h, which
+// patches the bit.  Pairs beyond the LDS list go to a global list and recheck_kernel; if that
+// overflows too, a flag makes the direct float64 kernel redo the whole call.
 #include "mp_common.h"
 #include "exact_dot.h"
 #include "device_utils.h"
@@ -48,6 +49,7 @@ __global__ void prep_zero_kernel(HashMfmaArgs a) {
     *a.wmax_bits = 0u;
     *a.list_count = 0u;
     *a.overflow = 0;
+    *a.flagged_total = 0u;
   }
 }
 
@@ -116,11 +118,94 @@ __global__ __launch_bounds__(256) void prep_threshold_kernel(HashMfmaArgs a) {
   a.thr[(((int64_t)unit * a.ntiles + T) * 2 + eta) * 16 + r] = c;
 }
 
-__global__ __launch_bounds__(256) void hash_keys_mfma_kernel(HashMfmaArgs a) {
+// Float64 / exact re-evaluation of listed (key, projection) pairs, for one wavefront: pairs
+// first, first + step, ... below count, 64/LPP of them per sweep (step = 64/LPP * wavefronts).
+// LPP lanes share a pair (128/LPP elements each, read in 16-byte pieces from the key row and
+// from the transposed projector row); their float64 partial sums are combined by shuffles.
+// Any summation order is covered by the float64 error bound; what it cannot decide is summed
+// exactly.  The bit is then set or cleared in the stored code word.
+// List entry: unit (16 bits) | key (32 bits) | projector column (16 bits).
+template <int LPP, class GetEntry>
+__device__ inline void recheck_pairs(const HashMfmaArgs& a, long long* limb, uint64_t count,
+                                     uint64_t first, uint64_t step, GetEntry get) {
+  constexpr int kPieces = 16 / LPP;                      // 8-element pieces per lane
+  const int lane = threadIdx.x & 63;
+  const uint16_t* Kc = reinterpret_cast<const uint16_t*>(a.Kc);
+  const uint16_t* WT = reinterpret_cast<const uint16_t*>(a.wt);
+  const int grp = lane / LPP, sl = lane % LPP;
+  for (uint64_t i0 = first; i0 < count; i0 += step) {
+    const uint64_t i = i0 + grp;
+    const bool on = i < count;
+    const unsigned long long e = get(on ? i : i0);
+    const int j = (int)(e & 0xffff);
+    const int64_t unit = (int64_t)(e >> 48);
+    const int64_t k = (int64_t)((e >> 16) & 0xffffffffull);
+    const int ub = (int)unit / a.n_kv_heads, uh = (int)unit % a.n_kv_heads;
+    const int64_t xoff = (int64_t)ub * a.stride_b + (int64_t)uh * a.stride_h + k * a.stride_n;
+    float kv[kPieces][8], wv[kPieces][8], mv[kPieces][8];
+#pragma unroll
+    for (int p = 0; p < kPieces; ++p) {
+      const int d0 = (p * LPP + sl) * 8;
+      load8<false>(Kc, xoff + d0, kv[p]);
+      load8<false>(WT, (int64_t)j * kHeadDim + d0, wv[p]);
+      if (a.mu) load8<true>(a.mu + unit * kHeadDim, d0, mv[p]);
+    }
+    double s = 0.0, mag = 0.0;
+#pragma unroll
+    for (int p = 0; p < kPieces; ++p) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const double w = (double)wv[p][t];
+        const double pr = (double)kv[p][t] * w;
+        s += pr;
+        mag += fabs(pr);
+        if (a.mu) {
+          const double pm = (double)mv[p][t] * w;
+          s -= pm;
+          mag += fabs(pm);
+        }
+      }
+    }
+#pragma unroll
+    for (int o = LPP / 2; o > 0; o >>= 1) {
+      s += __shfl_xor(s, o);
+      mag += __shfl_xor(mag, o);
+    }
+    bool bit = s >= 0.0;
+    const bool unsure = on && sl == 0 && mag > 0.0 && fabs(s) <= kF64Slack * mag;
+    uint64_t pending = __ballot(unsure);
+    while (pending) {
+      const int src = __ffsll((unsigned long long)pending) - 1;
+      const int64_t sx = ((int64_t)__shfl((int)(xoff >> 32), src) << 32) | (uint32_t)__shfl((int)(xoff & 0xffffffff), src);
+      const int sj = __shfl(j, src);
+      const int64_t su = ((int64_t)__shfl((int)(unit >> 32), src) << 32) | (uint32_t)__shfl((int)(unit & 0xffffffff), src);
+      const float* smu = a.mu ? a.mu + su * kHeadDim : nullptr;
+      const bool r = exact_sign_nonneg_wave(
+          limb,
+          [&](int d) { return (double)__uint_as_float((uint32_t)Kc[sx + d] << 16); },
+          [&](int d) { return (double)__uint_as_float((uint32_t)WT[(int64_t)sj * kHeadDim + d] << 16); },
+          [&](int d) { return smu ? (double)smu[d] : 0.0; }, smu != nullptr);
+      if (lane == src) bit = r;
+      pending &= pending - 1;
+    }
+    if (on && sl == 0) {
+      const int t = j / a.K, b = j % a.K;
+      const int x = (t >> 5) * a.K + b;
+      const uint32_t mask = 1u << (t & 31);
+      uint32_t* word = a.codes + (unit * a.blocks_cap + k / kBlockKeys) * (kBlockKeys * (int64_t)a.NW) +
+                       slot_in_block(a.NW, x, (int)(k % kBlockKeys));
+      if (bit) atomicOr(word, mask);
+      else atomicAnd(word, ~mask);
+    }
+  }
+}
+
+__global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) {
   __shared__ uint4 sA[2][4 * 8 * 64];                  // two stages of one word quad: 4 tiles x 8 k-steps
   __shared__ float sThr[2][4 * 2 * 16];
   __shared__ unsigned long long sList[kListCapLocal];
-  __shared__ unsigned sCount, sBase;
+  __shared__ unsigned sCount;
+  __shared__ long long sLimbs[4][kLimbs];
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -157,7 +242,8 @@ __global__ __launch_bounds__(256) void hash_keys_mfma_kernel(HashMfmaArgs a) {
       }
     }
     ss += __shfl_xor(ss, 32);                            // the other half of the row
-    bnd[bt] = ok ? kGamma * (sqrtf(ss) * 1.000001f + munorm) * wmax + 1e-30f : -1.f;
+    // flagged iff |acc| < bnd, bnd being just above the rigorous bound (so "<=" is covered)
+    bnd[bt] = ok ? (kGamma * (sqrtf(ss) * 1.000001f + munorm) * wmax) * 1.000001f + 1e-30f : -1.f;
   }
 
   const int nquads = (a.ntiles + 3) / 4;
@@ -182,16 +268,25 @@ __global__ __launch_bounds__(256) void hash_keys_mfma_kernel(HashMfmaArgs a) {
 
   for (int q = 0; q < nquads; ++q) {
     const int cur = q & 1;
-    // request the next quad's fragments; they are written to LDS after this quad's math
-    uint4 st[8];
+    // The next quad's fragments travel global -> registers -> LDS in two halves, each
+    // requested before and written after the math of one tile pair, so only 16 registers
+    // are tied up while the loads are in flight.
+    uint4 st[4];
     float stt = -INFINITY;
     const bool more = q + 1 < nquads;
-    if (more) {
+    auto request = [&](int half) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int idx = (q + 1) * 2048 + i * 256 + tid;
+      for (int i = 0; i < 4; ++i) {
+        const int idx = (q + 1) * 2048 + (half * 4 + i) * 256 + tid;
         st[i] = idx < a.ntiles * 512 ? gA[idx] : make_uint4(0, 0, 0, 0);
       }
+    };
+    auto deposit = [&](int half) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sA[cur ^ 1][(half * 4 + i) * 256 + tid] = st[i];
+    };
+    if (more) {
+      request(0);
       if (tid < 128) stt = (q + 1) * 128 + tid < a.ntiles * 32 ? gThr[(q + 1) * 128 + tid] : -INFINITY;
     }
 
@@ -200,6 +295,7 @@ __global__ __launch_bounds__(256) void hash_keys_mfma_kernel(HashMfmaArgs a) {
 #pragma unroll
       for (int pair = 0; pair < 2; ++pair) {
         wd[pair][0] = 0; wd[pair][1] = 0;
+        uint32_t fl[2] = {0u, 0u};                       // same bit positions: |acc| <= bound
 #pragma unroll
         for (int tau = 0; tau < 2; ++tau) {
           const int tile = pair * 2 + tau;
@@ -216,37 +312,43 @@ __global__ __launch_bounds__(256) void hash_keys_mfma_kernel(HashMfmaArgs a) {
             acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, B[0][s], acc0, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, B[1][s], acc1, 0, 0, 0);
           }
-          float mn0 = INFINITY, mn1 = INFINITY;
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            // funnel shift: word = (word << 1) | sign(acc); the sign bit is exact for ">= 0"
-            // because the accumulator starts from +0 or a non-zero threshold, never -0
+            // funnel shift: word = (word << 1) | sign(x).  For the code bit x = acc: the sign
+            // is exact for ">= 0" because the accumulator starts from +0 or a non-zero
+            // threshold, never -0.  For the flag x = |acc| - bound', negative iff |acc| <= bound.
             wd[pair][0] = __builtin_amdgcn_alignbit(wd[pair][0], __float_as_uint(acc0[r]), 31);
             wd[pair][1] = __builtin_amdgcn_alignbit(wd[pair][1], __float_as_uint(acc1[r]), 31);
-            mn0 = fminf(mn0, fabsf(acc0[r]));
-            mn1 = fminf(mn1, fabsf(acc1[r]));
+            fl[0] = __builtin_amdgcn_alignbit(fl[0], __float_as_uint(fabsf(acc0[r]) - bnd[0]), 31);
+            fl[1] = __builtin_amdgcn_alignbit(fl[1], __float_as_uint(fabsf(acc1[r]) - bnd[1]), 31);
           }
-          if (__ballot(mn0 <= bnd[0] || mn1 <= bnd[1])) {   // some element too close to zero
-            const int T = q * 4 + tile;
-            const int x = 2 * (T >> 1) + hh;
+        }
+        if (__ballot((fl[0] | fl[1]) != 0)) {            // some projection too close to zero
+          const int x = 2 * (q * 2 + pair) + hh;
+          const int tb = 32 * (x / a.K), pb = x % a.K;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-#pragma unroll
-              for (int bt = 0; bt < 2; ++bt) {
-                const float v = bt ? acc1[r] : acc0[r];
-                if (fabsf(v) <= bnd[bt]) {
-                  const int beta = 31 - (16 * (T & 1) + r);
-                  const int j = (32 * (x / a.K) + beta) * a.K + x % a.K;
-                  const unsigned pos = atomicAdd(&sCount, 1u);
-                  if (pos < kListCapLocal)
-                    sList[pos] = ((unsigned long long)((int64_t)unit * a.n_cap + key[bt]) << 16) | (unsigned)j;
-                }
+          for (int bt = 0; bt < 2; ++bt) {
+            uint32_t f = fl[bt];
+            while (f) {
+              const int beta = __ffs(f) - 1;
+              f &= f - 1;
+              const int j = (tb + beta) * a.K + pb;
+              const unsigned long long ent =
+                  ((unsigned long long)unit << 48) | ((unsigned long long)key[bt] << 16) | (unsigned)j;
+              const unsigned pos = atomicAdd(&sCount, 1u);
+              if (pos < kListCapLocal) {
+                sList[pos] = ent;
+              } else {                                   // rare: the workgroup's list is full
+                const unsigned gpos = atomicAdd(a.list_count, 1u);
+                if (gpos < a.list_cap) a.list[gpos] = ent;
+                else *a.overflow = 1;
               }
             }
           }
         }
         wd[pair][0] = ~wd[pair][0];
         wd[pair][1] = ~wd[pair][1];
+        if (more && pair == 0) { deposit(0); request(1); }
       }
       // lanes < 32 hold words x0 (pair 0) and x0+2 (pair 1) of keys kap / 32+kap, lanes >= 32
       // hold x0+1 and x0+3: one half-swap per pair leaves lane l with the words of key l
@@ -266,27 +368,28 @@ __global__ __launch_bounds__(256) void hash_keys_mfma_kernel(HashMfmaArgs a) {
     }
 
     if (more) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) sA[cur ^ 1][i * 256 + tid] = st[i];
+      if (!wave_on) { deposit(0); request(1); }          // idle wavefronts still move their share
+      deposit(1);
       if (tid < 128) sThr[cur ^ 1][tid] = stt;
     }
     __syncthreads();
   }
 
-  // ---- hand the flagged elements to the recheck kernel ----
-  const unsigned cnt = sCount;                           // visible: barrier above
-  if (cnt > kListCapLocal) { if (tid == 0) *a.overflow = 1; }
-  const unsigned keep = cnt < kListCapLocal ? cnt : kListCapLocal;
-  if (tid == 0) sBase = keep ? atomicAdd(a.list_count, keep) : 0u;
+  // ---- re-evaluate this workgroup's flagged pairs while its key rows are still in L2 ----
+  // The code words were stored above; the fence waits until L2 has them, the barrier makes
+  // that true for all four wavefronts, so the atomic patches below land on top of them.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
-  const unsigned base = sBase;
-  for (unsigned i = tid; i < keep; i += 256) {
-    if ((uint64_t)base + i < a.list_cap) a.list[base + i] = sList[i];
-    else *a.overflow = 1;
-  }
+  if (lane < kLimbs) sLimbs[wave][lane] = 0;
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  const unsigned cnt = sCount;
+  const unsigned keep = cnt < kListCapLocal ? cnt : kListCapLocal;
+  if (tid == 0 && cnt) atomicAdd(a.flagged_total, cnt);    // statistics only
+  recheck_pairs<4>(a, sLimbs[wave], keep, (uint64_t)wave * 16, 64, [&](uint64_t i) { return sList[i]; });
 }
 
-// Float64 / exact re-evaluation of the listed (key, projection) pairs; one lane per pair.
+// Re-evaluates the pairs that did not fit a workgroup's own list (normally none).
 __global__ __launch_bounds__(256) void recheck_kernel(HashMfmaArgs a) {
   __shared__ long long limbs[4][kLimbs];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -295,64 +398,8 @@ __global__ __launch_bounds__(256) void recheck_kernel(HashMfmaArgs a) {
   __builtin_amdgcn_wave_barrier();
   if (*a.overflow) return;                               // the direct kernel redoes everything
   const uint64_t count = *a.list_count < a.list_cap ? *a.list_count : a.list_cap;
-  const uint16_t* Kc = reinterpret_cast<const uint16_t*>(a.Kc);
-  const uint16_t* WT = reinterpret_cast<const uint16_t*>(a.wt);
-  const uint64_t stride = (uint64_t)gridDim.x * 256;
-  for (uint64_t i0 = (uint64_t)blockIdx.x * 256 + wave * 64; i0 < count; i0 += stride) {
-    const uint64_t i = i0 + lane;
-    const bool on = i < count;
-    const unsigned long long e = on ? a.list[i] : a.list[i0];
-    const int j = (int)(e & 0xffff);
-    const int64_t gk = (int64_t)(e >> 16);
-    const int64_t unit = gk / a.n_cap, k = gk % a.n_cap;
-    const int64_t xoff = (unit / a.n_kv_heads) * a.stride_b + (unit % a.n_kv_heads) * a.stride_h + k * a.stride_n;
-    const float* mu = a.mu ? a.mu + unit * kHeadDim : nullptr;
-    double s = 0.0, mag = 0.0;
-#pragma unroll 4
-    for (int p = 0; p < 16; ++p) {
-      float kv[8], wv[8];
-      load8<false>(Kc, xoff + p * 8, kv);
-      load8<false>(WT, (int64_t)j * kHeadDim + p * 8, wv);
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const double w = (double)wv[t];
-        const double pr = (double)kv[t] * w;
-        s += pr;
-        mag += fabs(pr);
-        if (mu) {
-          const double pm = (double)mu[p * 8 + t] * w;
-          s -= pm;
-          mag += fabs(pm);
-        }
-      }
-    }
-    bool bit = s >= 0.0;
-    const bool unsure = on && mag > 0.0 && fabs(s) <= kF64Slack * mag;
-    uint64_t pending = __ballot(unsure);
-    while (pending) {
-      const int src = __ffsll((unsigned long long)pending) - 1;
-      const int64_t sx = ((int64_t)__shfl((int)(xoff >> 32), src) << 32) | (uint32_t)__shfl((int)(xoff & 0xffffffff), src);
-      const int sj = __shfl(j, src);
-      const int64_t su = ((int64_t)__shfl((int)(unit >> 32), src) << 32) | (uint32_t)__shfl((int)(unit & 0xffffffff), src);
-      const float* smu = a.mu ? a.mu + su * kHeadDim : nullptr;
-      const bool r = exact_sign_nonneg_wave(
-          limbs[wave],
-          [&](int d) { return (double)__uint_as_float((uint32_t)Kc[sx + d] << 16); },
-          [&](int d) { return (double)__uint_as_float((uint32_t)WT[(int64_t)sj * kHeadDim + d] << 16); },
-          [&](int d) { return smu ? (double)smu[d] : 0.0; }, smu != nullptr);
-      if (lane == src) bit = r;
-      pending &= pending - 1;
-    }
-    if (on) {
-      const int t = j / a.K, b = j % a.K;
-      const int x = (t >> 5) * a.K + b;
-      const uint32_t mask = 1u << (t & 31);
-      uint32_t* word = a.codes + (unit * a.blocks_cap + k / kBlockKeys) * (kBlockKeys * (int64_t)a.NW) +
-                       slot_in_block(a.NW, x, (int)(k % kBlockKeys));
-      if (bit) atomicOr(word, mask);
-      else atomicAnd(word, ~mask);
-    }
-  }
+  recheck_pairs<16>(a, limbs[wave], count, ((uint64_t)blockIdx.x * 4 + wave) * 4, (uint64_t)gridDim.x * 16,
+                [&](uint64_t i) { return a.list[i]; });
 }
 
 hipError_t launch_hash_keys_mfma(const HashMfmaArgs& a, hipStream_t s) {

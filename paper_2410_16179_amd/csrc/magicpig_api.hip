@@ -29,6 +29,7 @@ int check_params(const magicpig_params* p) {
   const int G = p->n_q_heads / p->n_kv_heads;
   if (G != 1 && G != 2 && G != 4 && G != 8) return MAGICPIG_UNSUPPORTED;
   if (p->n_cap > (int64_t)1 << 31) return MAGICPIG_UNSUPPORTED;
+  if ((int64_t)p->batch * p->n_kv_heads > 65535) return MAGICPIG_UNSUPPORTED;
   return MAGICPIG_OK;
 }
 
@@ -189,6 +190,7 @@ int magicpig_hash_keys(const magicpig_params* p, const void* K_cache, const floa
     m.wmax_bits = reinterpret_cast<unsigned*>(wsb + wl.scalar_off);
     m.list_count = m.wmax_bits + 1;
     m.overflow = reinterpret_cast<int*>(m.wmax_bits + 2);
+    m.flagged_total = m.wmax_bits + 3;
     m.list = reinterpret_cast<unsigned long long*>(wsb + wl.list_off); m.list_cap = wl.list_cap;
     const hipError_t e = mp::launch_hash_keys_mfma(m, stream);
     if (e != hipSuccess) return fail_hip(e);

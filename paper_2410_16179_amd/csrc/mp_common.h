@@ -51,7 +51,7 @@ struct HashMfmaArgs {
   float* thr;                  // [units][ntiles][2][16] initial accumulators
   float* munorm;               // [units]
   unsigned* wmax_bits;         // max column norm of W (float bits)
-  unsigned* list_count; int* overflow;
+  unsigned* list_count; int* overflow; unsigned* flagged_total;
   unsigned long long* list; uint64_t list_cap;
 };
 
