@@ -73,33 +73,47 @@ def time_prefill(params, w, Wd, sets, ws):
 
 
 def cpu_baseline(w, data, seed):
-    """The CPU oracle, as it stands, on a bounded sample: the decode step (query coding,
-    collision counts, sample, estimator) of the query heads of the first KV heads, at the
-    full context.  Key codes for those KV heads are computed by the oracle beforehand
-    (untimed here, like the GPU's prefill hashing)."""
+    """The CPU oracle, as it stands, single-threaded, on the first batch element of the
+    workload at its full context: the decode step (query coding, collision counts, sample,
+    inclusion probabilities, estimator) of all its query heads.  The oracle first hashes the
+    keys itself (timed and reported, not part of `value`, like the GPU's prefill hashing)."""
     from oracle import magicpig_oracle as oracle
     from threadpoolctl import threadpool_limits
-    n_groups = 2
-    G = w.group
-    heads = [(0, h) for h in range(n_groups * G)]
+    heads = [(0, h) for h in range(w.n_q_heads)]
+    sub = {k: (v[:1] if k != "W" else v) for k, v in data.items()}
     with threadpool_limits(limits=1):
-        mu = np.stack([[oracle.key_mean(data["K"][0, g]) for g in range(w.n_kv_heads)]]).astype(np.float32)
+        mu = np.stack([[oracle.key_mean(sub["K"][0, g]) for g in range(w.n_kv_heads)]]).astype(np.float32)
         t0 = time.time()
         codes = np.zeros((1, w.n_kv_heads, w.n_ctx, w.L), np.int32)
-        for g in range(n_groups):
-            codes[0, g] = oracle.hash_keys(data["K"][0, g], data["W"], mu[0, g], w.K, w.L)
+        for g in range(w.n_kv_heads):
+            codes[0, g] = oracle.hash_keys(sub["K"][0, g], sub["W"], mu[0, g], w.K, w.L)
         hash_s = time.time() - t0
         t0 = time.time()
-        ref = oracle.decode_step(data["q"], data["K"], data["V"], data["W"], w.K, w.L, mu=mu,
+        ref = oracle.decode_step(sub["q"], sub["K"], sub["V"], sub["W"], w.K, w.L, mu=mu,
                                  min_hits=w.min_hits, n_sink=w.n_sink, n_local=w.n_local,
                                  key_codes=codes, heads=heads)
         dec_s = time.time() - t0
     return {
         "value": len(heads) / dec_s, "unit": "query-heads/s", "cores": 1, "kind": "oracle",
-        "sample": f"decode step of {len(heads)} of {w.n_q_heads} query heads (KV heads 0..{n_groups - 1}) "
-                  f"at the full {w.n_ctx}-key context, {dec_s:.2f} s; oracle key hashing of those "
-                  f"{n_groups * w.n_ctx} keys took {hash_s:.1f} s (not in value)",
+        "sample": f"decode step of the {len(heads)} query heads of batch element 0 at the full "
+                  f"{w.n_ctx}-key context: {dec_s:.2f} s; before it the oracle hashed those "
+                  f"{w.n_kv_heads * w.n_ctx} keys in {hash_s:.1f} s "
+                  f"({w.n_kv_heads * w.n_ctx / hash_s:.0f} keys/s, not in value)",
     }, ref, heads
+
+
+def stored_traffic(workload: str):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE and WRITE_SIZE, calibrated on a copy of known size); None if absent."""
+    path = os.path.join(ROOT, "profiles", f"collision_scan_{workload}_pmc.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch"):
+                    return float(line.split()[1])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -242,7 +256,7 @@ def main():
                                f"{w.n_sink} sink + {w.n_local} local, {args.copies} rotating cache copies",
                    "step": "magicpig_hash_query + magicpig_sampled_attention"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": stored_traffic(w.name),
                      "kernel": "collision_scan_kernel (dominant kernel of magicpig_sampled_attention)",
                      "avg_launch_ms": scan_ms, "algorithmic_bytes": scan_bytes,
                      "scan_plus_gather": {"algorithmic_bytes": alg_bytes, "gather_bytes": gather_bytes,

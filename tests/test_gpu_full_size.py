@@ -1,0 +1,44 @@
+"""GPU parity at the full sizes of the named configurations, through the same calls and
+launch configuration that bench.py times.  Where the oracle cannot cover everything in
+seconds, it covers every key of some (batch, KV head) units and all their query heads."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2410_16179_amd import binding as mp
+from paper_2410_16179_amd import workloads as wl
+from tests.test_gpu_parity import run_case
+
+pytestmark = pytest.mark.gpu
+
+
+def test_c2_full_all_heads(oracle):
+    ref, res, worst = run_case(oracle, wl.CONFIGS["C2"], oracle_codes_too=False)
+    frac = np.mean([ref["S"][0][h].size for h in range(32)]) / 16384
+    assert 0.005 < frac < 0.04           # (10,150): a per cent or two of the keys
+    print(f"   C2 sampled fraction {frac:.4f}, worst output error {worst:.2e}", flush=True)
+
+
+def test_c3_full_two_kv_heads(oracle):
+    # 96k context, the benchmark workload: every key code of KV heads 0 and 5, and the eight
+    # query heads that use them (counts, sample sets, outputs)
+    heads = [(0, h) for h in (0, 1, 2, 3, 20, 21, 22, 23)]
+    ref, res, worst = run_case(oracle, wl.CONFIGS["C3"], heads=heads, oracle_codes_too=False)
+    print(f"   C3 worst output error {worst:.2e}", flush=True)
+    # properties that hold for all heads at any size: output finite, inside the value range
+    assert np.isfinite(res["out"]).all()
+    assert np.abs(res["out"]).max() < 6.0
+
+
+def test_c4_one_sequence_peaked_and_flat_heads(oracle):
+    # one of the 16 sequences at the full 65536 context; peaked (8 planted) and flat (512) heads
+    w = wl.scaled(wl.CONFIGS["C4"], batch=1)
+    heads = [(0, h) for h in (0, 3, 16, 19, 28, 31)]
+    run_case(oracle, w, heads=heads, oracle_codes_too=False)
+
+
+def test_c5_one_sequence_group_of_eight(oracle):
+    # 70B shapes (8 query heads per KV head, L = 170) at the full 131072 context, one sequence
+    w = wl.scaled(wl.CONFIGS["C5"], batch=1)
+    heads = [(0, h) for h in range(8, 16)]
+    run_case(oracle, w, heads=heads, oracle_codes_too=False)
