@@ -119,6 +119,102 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
   }
 }
 
+// Query coding (Algorithm 1 "Encode(q, W)"): one workgroup codes two query vectors against
+// the 32*K projector columns of one table word.  Thread = column, so the 128 loads of a
+// column are coalesced across the workgroup and all in flight at once; the two vectors are
+// wave-uniform scalar loads.  Sign bits go through LDS to be regrouped from column order
+// (table-major) into the bit-plane words of the code layout.
+template <bool FP32>
+__global__ __launch_bounds__(512) void hash_query_kernel(HashDirectArgs a) {
+  __shared__ long long limbs[8][kLimbs];
+  __shared__ unsigned char sbit[2][512];
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  if (lane < kLimbs) limbs[wave][lane] = 0;
+  const int w = blockIdx.x;
+  const int64_t r0 = (int64_t)blockIdx.y * 2;
+  const int nrow = a.total_rows - r0 >= 2 ? 2 : 1;
+  const int ncol = a.K * a.L;
+  const int t = 32 * w + tid / a.K, b = tid % a.K;
+  const bool col_ok = tid < 32 * a.K && t < a.L;
+  const int j = col_ok ? t * a.K + b : 0;
+  // 32-bit element offsets from the (uniform) projector base keep the 128 addresses cheap
+  float wf[kHeadDim];
+  const uint32_t ucol = (uint32_t)ncol, uj = (uint32_t)j;
+#pragma unroll
+  for (uint32_t i = 0; i < (uint32_t)kHeadDim; ++i) {
+    if constexpr (FP32) wf[i] = reinterpret_cast<const float*>(a.W)[i * ucol + uj];
+    else wf[i] = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(a.W)[i * ucol + uj] << 16);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  // both vectors in one pass over the column, so that each projector element is converted to
+  // float64 once and nothing but the four accumulators stays live; the vectors are
+  // wave-uniform: read through the constant address space they arrive in SGPRs
+  typedef const uint32_t __attribute__((address_space(4))) * const_u32_ptr;
+  const int64_t xb0 = r0 * a.stride_n, xb1 = (r0 + nrow - 1) * a.stride_n;
+  const const_u32_ptr xs0 = (const_u32_ptr)(reinterpret_cast<const char*>(a.X) + xb0 * (FP32 ? 4 : 2));
+  const const_u32_ptr xs1 = (const_u32_ptr)(reinterpret_cast<const char*>(a.X) + xb1 * (FP32 ? 4 : 2));
+  double s[2] = {0.0, 0.0}, mag[2] = {0.0, 0.0};
+#pragma unroll
+  for (int i = 0; i < kHeadDim; ++i) {
+    float x0, x1;
+    if constexpr (FP32) {
+      x0 = __uint_as_float(xs0[i]);
+      x1 = __uint_as_float(xs1[i]);
+    } else {
+      x0 = __uint_as_float((i & 1) ? (xs0[i >> 1] & 0xffff0000u) : (xs0[i >> 1] << 16));
+      x1 = __uint_as_float((i & 1) ? (xs1[i >> 1] & 0xffff0000u) : (xs1[i >> 1] << 16));
+    }
+    const double wv = (double)wf[i];
+    const double p0 = (double)x0 * wv, p1 = (double)x1 * wv;
+    s[0] += p0; mag[0] += fabs(p0);
+    s[1] += p1; mag[1] += fabs(p1);
+  }
+  for (int rr = 0; rr < nrow; ++rr) {
+    const int64_t xbase = rr ? xb1 : xb0;
+    bool bit = s[rr] >= 0.0;
+    const bool unsure = col_ok && mag[rr] > 0.0 && fabs(s[rr]) <= kF64Slack * mag[rr];
+    uint64_t pending = __ballot(unsure);
+    while (pending) {
+      const int src = __ffsll((unsigned long long)pending) - 1;
+      const int sj = __shfl(j, src);
+      const bool r = exact_sign_nonneg_wave(
+          limbs[wave],
+          [&](int d) { return load_elem<FP32>(a.X, xbase + d); },
+          [&](int d) { return load_elem<FP32>(a.W, (int64_t)d * ncol + sj); },
+          [&](int) { return 0.0; }, false);
+      if (lane == src) bit = r;
+      pending &= pending - 1;
+    }
+    sbit[rr][tid] = (unsigned char)(bit && col_ok);
+  }
+  __syncthreads();
+  // regroup: item (row, plane b, table beta) reads the bit of column beta*K + b
+  const int items = nrow * a.K * 32;
+  const int Wd = table_words(a.L);
+  for (int p0 = 0; p0 < items; p0 += 512) {
+    const int p = p0 + tid;
+    const bool on = p < items;
+    const int row = on ? p / (a.K * 32) : 0;
+    const int rem = on ? p % (a.K * 32) : 0;
+    const int pb = rem >> 5, beta = rem & 31;
+    const bool v = on && sbit[row][beta * a.K + pb];
+    const uint64_t m = __ballot(v);
+    uint32_t word = (lane >> 5) ? (uint32_t)(m >> 32) : (uint32_t)m;
+    if (w == Wd - 1 && (a.L & 31)) word |= ~0u << (a.L & 31);      // padding tables never collide
+    if (on && beta == 0) a.codes[(r0 + row) * a.NW + w * a.K + pb] = word;
+  }
+}
+
+hipError_t launch_hash_query(const HashDirectArgs& a, hipStream_t s) {
+  if (a.total_rows <= 0) return hipSuccess;
+  const dim3 grid((unsigned)table_words(a.L), (unsigned)((a.total_rows + 1) / 2)), block(512);
+  if (a.is_fp32) hipLaunchKernelGGL(hash_query_kernel<true>, grid, block, 0, s, a);
+  else hipLaunchKernelGGL(hash_query_kernel<false>, grid, block, 0, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s) {
   if (a.total_rows <= 0) return hipSuccess;
   const int64_t groups = (a.total_rows + 7) / 8;

@@ -74,12 +74,15 @@ HashWs ws_hash_layout(const magicpig_params* p) {
 size_t ws_hash(const magicpig_params* p) { return p->dtype == MAGICPIG_BF16 ? ws_hash_layout(p).total : 256; }
 
 // decode workspace: [partials | ballots]
-struct AttnWs { size_t partial_off, masks_off, total; int nranges; };
+struct AttnWs { size_t partial_off, masks_off, total; int nranges, nscan; int64_t n_static; };
 AttnWs ws_attention_layout(const magicpig_params* p) {
   AttnWs w{};
   const int64_t nblk = mp::key_blocks(p->n_ctx);
   const size_t heads = (size_t)p->batch * p->n_q_heads;
-  w.nranges = (int)((nblk + mp::kRangeBlocks - 1) / mp::kRangeBlocks);
+  w.nscan = (int)((nblk + mp::kRangeBlocks - 1) / mp::kRangeBlocks);
+  const int64_t st = (int64_t)p->n_sink + p->n_local;
+  w.n_static = st < p->n_ctx ? st : p->n_ctx;
+  w.nranges = w.nscan + (int)((w.n_static + mp::kStaticPerRange - 1) / mp::kStaticPerRange);
   w.partial_off = 0;
   w.masks_off = align256(heads * w.nranges * mp::kPartialStride * sizeof(float));
   w.total = w.masks_off + align256(heads * (size_t)nblk * sizeof(uint64_t));
@@ -217,7 +220,8 @@ int magicpig_hash_query(const magicpig_params* p, const void* q, const void* W, 
   a.n_kv_heads = 1;
   a.stride_b = 0; a.stride_h = 0; a.stride_n = mp::kHeadDim;
   a.blocks_cap = 0;
-  const hipError_t e = mp::launch_hash_direct(a, reinterpret_cast<hipStream_t>(hip_stream));
+  a.run_flag = nullptr;
+  const hipError_t e = mp::launch_hash_query(a, reinterpret_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
 }
 
@@ -244,7 +248,7 @@ int magicpig_sampled_attention(const magicpig_params* p, const void* q, const vo
   char* wsb = reinterpret_cast<char*>(workspace);
   a.partial = reinterpret_cast<float*>(wsb + wl.partial_off); a.out = out;
   a.masks = reinterpret_cast<uint64_t*>(wsb + wl.masks_off);
-  a.nranges = wl.nranges;
+  a.nranges = wl.nranges; a.nscan = wl.nscan; a.n_static = wl.n_static;
   a.dbg_counts = dbg_counts; a.dbg_cand = dbg_cand; a.dbg_ncand = dbg_ncand; a.dbg_cand_cap = dbg_cand_cap;
   a.is_fp32 = p->dtype == MAGICPIG_FP32;
   a.B = p->batch; a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.K = p->K; a.L = p->L;

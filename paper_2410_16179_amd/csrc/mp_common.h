@@ -71,15 +71,19 @@ struct AttnArgs {
   int B, Hq, Hkv, K, L, Wd, NW, tau, n_sink, n_local;
   int64_t n, blocks_cap;
   int64_t ks_b, ks_h, ks_n, vs_b, vs_h, vs_n;
-  int nranges;               // runs of kRangeBlocks key blocks (= partials) per head
+  int nranges;               // partials per head: nscan runs of kRangeBlocks key blocks + static runs
+  int nscan;
+  int64_t n_static;          // keys in the static set T
   float scale;
 };
 
 constexpr int kPartialStride = 132;   // 128 output elements, running max, running sum, pad
 constexpr int kRangeBlocks = 16;      // key blocks per gather wavefront (1024 keys)
+constexpr int kStaticPerRange = 32;   // static (sink / local) keys per gather wavefront
 
 // host-side launchers (defined next to their kernels)
 hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s);
+hipError_t launch_hash_query(const HashDirectArgs& a, hipStream_t s);
 hipError_t launch_hash_keys_mfma(const HashMfmaArgs& a, hipStream_t s);
 hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s);
 hipError_t launch_sampled_attention(const AttnArgs& a, hipStream_t s, hipEvent_t const* stage_events);

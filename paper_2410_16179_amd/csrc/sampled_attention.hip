@@ -5,13 +5,13 @@
 //   One wavefront per 64-key code block, lane = key: the block is a contiguous 256*NW-byte
 //   read, 16 bytes per lane and load.  For each of the G query heads of the KV head the K
 //   bit planes of every table word are XNOR-ed with the query's (scalar operands) and
-//   AND-ed together; a popcount adds the number of colliding tables.  Keys with
-//   count >= min_hits, and the static sink/local keys, are reported as one 64-bit ballot
-//   per (head, block).  No LDS, no barrier, about 60 VGPRs: eight wavefronts per SIMD keep
+//   AND-ed together; a popcount adds the number of colliding tables.  Keys outside the
+//   static set with count >= min_hits are reported as one 64-bit ballot per (head, block).  No LDS, no barrier, about 60 VGPRs: eight wavefronts per SIMD keep
 //   enough loads in flight to saturate HBM.
 // gather_estimate_kernel  (random 256-byte K and V rows)
 //   One wavefront per (query head, run of 16 key blocks): the ballots are expanded into an
-//   index list in LDS by a wavefront prefix sum; rows are gathered four at a time (a
+//   index list in LDS by a wavefront prefix sum (further wavefronts take the static sink and
+//   local-window keys, 32 each, so that no wavefront needs a second batch in the usual case); rows are gathered four at a time (a
 //   quarter wavefront holds one 128-element row) with up to 32 K rows and 32 V rows in
 //   flight; q.k, q.(k-mu), |k-mu|^2 are reduced over the 16 lanes of a row, the inclusion
 //   probability u_i and the logit q.k/sqrt(d) - log u_i are evaluated once per candidate,
@@ -25,7 +25,9 @@
 namespace mp {
 
 // u = P[Binomial(L, x) >= tau], x = p^K, in float32 without cancellation: the complement
-// 1 - P[< tau] when that is below one half, otherwise the positive upper-tail terms.
+// 1 - P[< tau] when that is below one half, otherwise the positive upper-tail terms.  The
+// hardware exp2/log2/rcp based intrinsics are accurate to about 1e-6 relative here, which
+// moves log u by about 1e-5: two orders below the output tolerance.
 __device__ inline float inclusion_probability(float cosv, int K, int L, int tau) {
   const float c = fminf(fmaxf(cosv, -1.f), 1.f);
   const float p = 1.f - acosf(c) * 0.31830988618379067f;
@@ -33,18 +35,18 @@ __device__ inline float inclusion_probability(float cosv, int K, int L, int tau)
   for (int i = 0; i < K; ++i) x *= p;
   if (x >= 1.f) return L >= tau ? 1.f : 0.f;
   if (!(x > 0.f)) return 0.f;
-  const float r = x / (1.f - x);
-  float t = expf((float)L * log1pf(-x));   // term j = 0
+  const float r = __fdividef(x, 1.f - x);
+  float t = __expf((float)L * log1pf(-x));   // term j = 0
   float head = 0.f;
   for (int j = 0; j < tau; ++j) {
     head += t;
-    t *= (float)(L - j) / (float)(j + 1) * r;
+    t *= (float)(L - j) * __frcp_rn((float)(j + 1)) * r;
   }
   if (head < 0.5f) return 1.f - head;
   float sum = 0.f;
   for (int j = tau; j <= L; ++j) {
     sum += t;
-    t *= (float)(L - j) / (float)(j + 1) * r;
+    t *= (float)(L - j) * __frcp_rn((float)(j + 1)) * r;
     if (t < 1e-9f * sum) break;
   }
   return sum;
@@ -121,11 +123,11 @@ __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
         cnt += __popc(same);
       }
     }
-    const bool hit = valid && (in_T || a.tau <= 0 || (int)cnt >= a.tau);
+    const bool hit = valid && !in_T && (a.tau <= 0 || (int)cnt >= a.tau);
     const uint64_t m = __ballot(hit);
     if (lane == 0) a.masks[(head0 + h) * nblk + blk] = m;
     if (a.dbg_counts && valid) a.dbg_counts[(head0 + h) * a.n + i] = (uint16_t)cnt;
-    if (a.dbg_cand && hit && !in_T) {
+    if (a.dbg_cand && hit) {
       const int pos = atomicAdd(&a.dbg_ncand[head0 + h], 1);
       if (pos < a.dbg_cand_cap) a.dbg_cand[(head0 + h) * a.dbg_cand_cap + pos] = (int32_t)i;
     }
@@ -147,31 +149,44 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
   const int64_t blk0 = (int64_t)range * kRangeBlocks;
   uint16_t* list = lists[wave];
 
-  // ---- expand the scan's ballots into an index list (wavefront prefix sum) ----
-  uint64_t m = 0;
-  if (lane < kRangeBlocks && blk0 + lane < nblk) m = a.masks[bh * nblk + blk0 + lane];
-  const int c = __popcll(m);
-  int incl = c;
+  // Ranges below nscan cover 16 key blocks of sampled keys; the ranges after them cover the
+  // static set T (sink + local window), kStaticPerRange keys each, taken exactly (u = 1).
+  const bool is_static = range >= a.nscan;
+  int total;
+  int64_t static_first = 0;
+  if (!is_static) {
+    // ---- expand the scan's ballots into an index list (wavefront prefix sum) ----
+    uint64_t m = 0;
+    if (lane < kRangeBlocks && blk0 + lane < nblk) m = a.masks[bh * nblk + blk0 + lane];
+    const int c = __popcll(m);
+    int incl = c;
 #pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int v = __shfl_up(incl, o);
-    if (lane >= o) incl += v;
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o);
+      if (lane >= o) incl += v;
+    }
+    total = __shfl(incl, 63);
+    int pos = incl - c;
+    while (m) {
+      const int bit = __ffsll((unsigned long long)m) - 1;
+      list[pos++] = (uint16_t)(lane * kBlockKeys + bit);
+      m &= m - 1;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+  } else {
+    static_first = (int64_t)(range - a.nscan) * kStaticPerRange;
+    const int64_t left = a.n_static - static_first;
+    total = (int)(left < kStaticPerRange ? left : kStaticPerRange);
   }
-  const int total = __shfl(incl, 63);
-  int pos = incl - c;
-  while (m) {
-    const int bit = __ffsll((unsigned long long)m) - 1;
-    list[pos++] = (uint16_t)(lane * kBlockKeys + bit);
-    m &= m - 1;
-  }
-  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-  __builtin_amdgcn_wave_barrier();
+  // j-th key of T: the sink keys, then the local window (all keys when the context is short)
+  const int64_t sink_keys = a.n_static < a.n ? a.n_sink : a.n_static;
+  const int64_t local_shift = a.n - a.n_local - a.n_sink;
 
   // ---- gather + estimator ----
   const int qd = lane >> 4, sl = lane & 15;
   const int64_t kbase = (int64_t)b * a.ks_b + (int64_t)g * a.ks_h + sl * 8;
   const int64_t vbase = (int64_t)b * a.vs_b + (int64_t)g * a.vs_h + sl * 8;
-  const int64_t local_lo = a.n - a.n_local;
   float muf[8], qf[8], o[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) { muf[e] = 0.f; o[e] = 0.f; }
@@ -198,7 +213,12 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
     for (int it = 0; it < kIters; ++it) {
       const int cc = base + it * 4 + qd;
       ok[it] = cc < total;
-      idx[it] = blk0 * kBlockKeys + (ok[it] ? list[cc] : 0);
+      if (!is_static) {
+        idx[it] = blk0 * kBlockKeys + (ok[it] ? list[cc] : 0);
+      } else {
+        const int64_t jt = static_first + (ok[it] ? cc : 0);
+        idx[it] = jt < sink_keys ? jt : jt + local_shift;
+      }
       if (ok[it]) {
         frag_load<FP32>(a.Kc, kbase + idx[it] * a.ks_n, kf[it]);
         frag_load<FP32>(a.Vc, vbase + idx[it] * a.vs_n, vf[it]);
@@ -231,17 +251,16 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
     float logit = -INFINITY;
     if (sl < kIters && my_ok) {
       logit = my_dq * a.scale;
-      const bool in_T = my_i < a.n_sink || my_i >= local_lo;
-      if (!in_T && a.tau > 0) {
+      if (!is_static && a.tau > 0) {
         const float den = qnorm * sqrtf(my_nn);
         const float cosv = den > 0.f ? my_dc / den : 0.f;
         const float u = fmaxf(inclusion_probability(cosv, a.K, a.L, a.tau), 1.17549435e-38f);
-        logit -= logf(u);
+        logit -= __logf(u);
       }
     }
     const float m_new = fmaxf(m_run, wave_max(logit));   // finite: the batch is not empty
-    const float alpha = expf(m_run - m_new);             // m_run = -inf gives 0
-    const float wgt = logit > -INFINITY ? expf(logit - m_new) : 0.f;
+    const float alpha = __expf(m_run - m_new);           // m_run = -inf gives 0
+    const float wgt = logit > -INFINITY ? __expf(logit - m_new) : 0.f;
     l_run = l_run * alpha + wave_sum(wgt);
     m_run = m_new;
 #pragma unroll
