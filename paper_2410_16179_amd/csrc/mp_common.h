@@ -72,7 +72,7 @@ struct AttnArgs {
   int64_t n, blocks_cap;
   int64_t ks_b, ks_h, ks_n, vs_b, vs_h, vs_n;
   int nranges;               // partials per head: nscan runs of kRangeBlocks key blocks + static runs
-  int nscan;
+  int nscan;                 // runs of kRangeBlocks key blocks per head
   int64_t n_static;          // keys in the static set T
   float scale;
 };
@@ -87,5 +87,6 @@ hipError_t launch_hash_query(const HashDirectArgs& a, hipStream_t s);
 hipError_t launch_hash_keys_mfma(const HashMfmaArgs& a, hipStream_t s);
 hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s);
 hipError_t launch_sampled_attention(const AttnArgs& a, hipStream_t s, hipEvent_t const* stage_events);
+
 
 }  // namespace mp
