@@ -11,14 +11,19 @@ struct Frag {
   uint4 a, b;
 };
 
+// The rows of a decode step are read once: non-temporal loads.
 template <bool FP32>
 __device__ inline void frag_load(const void* base, int64_t elem, Frag& f) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
   if constexpr (FP32) {
-    const uint4* p = reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(base) + elem);
-    f.a = p[0];
-    f.b = p[1];
+    const u32x4* p = reinterpret_cast<const u32x4*>(reinterpret_cast<const float*>(base) + elem);
+    const u32x4 a = __builtin_nontemporal_load(p), b = __builtin_nontemporal_load(p + 1);
+    f.a = make_uint4(a.x, a.y, a.z, a.w);
+    f.b = make_uint4(b.x, b.y, b.z, b.w);
   } else {
-    f.a = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(base) + elem);
+    const u32x4 a = __builtin_nontemporal_load(
+        reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(base) + elem));
+    f.a = make_uint4(a.x, a.y, a.z, a.w);
   }
 }
 

@@ -21,10 +21,16 @@
 //   Sec. 4.4) and writes the output row.
 #include "attention_common.h"
 
+#ifndef MP_SCAN_BPW
+#define MP_SCAN_BPW 1
+#endif
+
 namespace mp {
 
 // KT, WDT: compile-time K and ceil(L/32) for the tuned instantiations, 0 for the generic one.
-template <int KT, int WDT>
+// BPW: consecutive 64-key blocks per wavefront; all their code words are requested before the
+// first comparison, and each scalar-loaded query word serves BPW keys per lane.
+template <int KT, int WDT, int BPW>
 __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
   constexpr bool kGeneric = (KT == 0);
   // readfirstlane tells the compiler that the wavefront index (and everything derived from
@@ -32,8 +38,8 @@ __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int64_t nblk = key_blocks(a.n);
   const int unit = blockIdx.y;
-  const int64_t blk = (int64_t)blockIdx.x * 4 + wave;
-  if (blk >= nblk) return;
+  const int64_t blk0 = ((int64_t)blockIdx.x * 4 + wave) * BPW;
+  if (blk0 >= nblk) return;
   const int G = a.Hq / a.Hkv;
   const int K = kGeneric ? a.K : KT;
   const int Wd = kGeneric ? a.Wd : WDT;
@@ -42,25 +48,34 @@ __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
   // Query codes are wave-uniform and constant during the kernel: read through the constant
   // address space they are scalar loads into SGPRs and feed the bit operations directly.
   const const_u32_ptr qc = (const_u32_ptr)(a.qcodes + head0 * NW);
-  const uint32_t* blkp = a.kcodes + ((int64_t)unit * a.blocks_cap + blk) * (kBlockKeys * (int64_t)NW);
+  const uint32_t* blkp = a.kcodes + ((int64_t)unit * a.blocks_cap + blk0) * (kBlockKeys * (int64_t)NW);
 
-  [[maybe_unused]] uint32_t kw[kGeneric ? 1 : KT * WDT];
-  if constexpr (!kGeneric) load_code_block<KT * WDT>(blkp, lane, kw);
+  [[maybe_unused]] uint32_t kw[BPW][kGeneric ? 1 : KT * WDT];
+  if constexpr (!kGeneric) {
+#pragma unroll
+    for (int j = 0; j < BPW; ++j)
+      if (blk0 + j < nblk) load_code_block<KT * WDT>(blkp + j * (kBlockKeys * (int64_t)NW), lane, kw[j]);
+  }
 
-  const int64_t i = blk * kBlockKeys + lane;
-  const bool valid = i < a.n;
-  const bool in_T = i < a.n_sink || i >= a.n - a.n_local;
 #pragma unroll 1
   for (int h = 0; h < G; ++h) {
-    uint32_t cnt = 0;
     const const_u32_ptr qh = qc + h * NW;
+    uint32_t cnt[BPW];
+#pragma unroll
+    for (int j = 0; j < BPW; ++j) cnt[j] = 0;
     if constexpr (!kGeneric) {
 #pragma unroll
       for (int w = 0; w < WDT; ++w) {
-        uint32_t same = ~(kw[w * KT] ^ qh[w * KT]);
+        uint32_t same[BPW];
 #pragma unroll
-        for (int p = 1; p < KT; ++p) same &= ~(kw[w * KT + p] ^ qh[w * KT + p]);   // one 3-input op
-        cnt += __popc(same);
+        for (int j = 0; j < BPW; ++j) same[j] = ~(kw[j][w * KT] ^ qh[w * KT]);
+#pragma unroll
+        for (int p = 1; p < KT; ++p) {
+#pragma unroll
+          for (int j = 0; j < BPW; ++j) same[j] &= ~(kw[j][w * KT + p] ^ qh[w * KT + p]);   // one 3-input op
+        }
+#pragma unroll
+        for (int j = 0; j < BPW; ++j) cnt[j] += __popc(same[j]);
       }
     } else {
       for (int w = 0; w < Wd; ++w) {
@@ -69,16 +84,25 @@ __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
           const int x = w * K + p;
           same &= ~(blkp[slot_in_block(NW, x, lane)] ^ qh[x]);
         }
-        cnt += __popc(same);
+        cnt[0] += __popc(same);
       }
     }
-    const bool hit = valid && !in_T && (a.tau <= 0 || (int)cnt >= a.tau);
-    const uint64_t m = __ballot(hit);
-    if (lane == 0) a.masks[(head0 + h) * nblk + blk] = m;
-    if (a.dbg_counts && valid) a.dbg_counts[(head0 + h) * a.n + i] = (uint16_t)cnt;
-    if (a.dbg_cand && hit) {
-      const int pos = atomicAdd(&a.dbg_ncand[head0 + h], 1);
-      if (pos < a.dbg_cand_cap) a.dbg_cand[(head0 + h) * a.dbg_cand_cap + pos] = (int32_t)i;
+#pragma unroll
+    for (int j = 0; j < BPW; ++j) {
+      const int64_t blk = blk0 + j;
+      if (blk < nblk) {
+        const int64_t i = blk * kBlockKeys + lane;
+        const bool valid = i < a.n;
+        const bool in_T = i < a.n_sink || i >= a.n - a.n_local;
+        const bool hit = valid && !in_T && (a.tau <= 0 || (int)cnt[j] >= a.tau);
+        const uint64_t m = __ballot(hit);
+        if (lane == 0) a.masks[(head0 + h) * nblk + blk] = m;
+        if (a.dbg_counts && valid) a.dbg_counts[(head0 + h) * a.n + i] = (uint16_t)cnt[j];
+        if (a.dbg_cand && hit) {
+          const int pos = atomicAdd(&a.dbg_ncand[head0 + h], 1);
+          if (pos < a.dbg_cand_cap) a.dbg_cand[(head0 + h) * a.dbg_cand_cap + pos] = (int32_t)i;
+        }
+      }
     }
   }
 }
@@ -302,15 +326,18 @@ __global__ void zero_output_kernel(float* out, int64_t count) {
 }
 
 static hipError_t launch_scan(const AttnArgs& a, hipStream_t s) {
-  const dim3 grid((unsigned)((key_blocks(a.n) + 3) / 4), (unsigned)(a.B * a.Hkv)), block(256);
-#define MP_TUNED(KT, WDT)                                                           \
-  if (a.K == KT && a.Wd == WDT) {                                                   \
-    hipLaunchKernelGGL((collision_scan_kernel<KT, WDT>), grid, block, 0, s, a);     \
-    return hipGetLastError();                                                       \
+  constexpr int kBPW = MP_SCAN_BPW;
+  const dim3 block(256);
+  const dim3 grid_t((unsigned)((key_blocks(a.n) + 4 * kBPW - 1) / (4 * kBPW)), (unsigned)(a.B * a.Hkv));
+#define MP_TUNED(KT, WDT)                                                                  \
+  if (a.K == KT && a.Wd == WDT) {                                                          \
+    hipLaunchKernelGGL((collision_scan_kernel<KT, WDT, kBPW>), grid_t, block, 0, s, a);    \
+    return hipGetLastError();                                                              \
   }
   MP_TUNED(10, 5) MP_TUNED(9, 4) MP_TUNED(10, 6) MP_TUNED(8, 3)
 #undef MP_TUNED
-  hipLaunchKernelGGL((collision_scan_kernel<0, 0>), grid, block, 0, s, a);
+  const dim3 grid((unsigned)((key_blocks(a.n) + 3) / 4), (unsigned)(a.B * a.Hkv));
+  hipLaunchKernelGGL((collision_scan_kernel<0, 0, 1>), grid, block, 0, s, a);
   return hipGetLastError();
 }
 
