@@ -16,6 +16,7 @@ __global__ __launch_bounds__(256) void key_mean_partial_kernel(MeanArgs a) {
   const int64_t r0 = (int64_t)chunk * a.rows_per_chunk;
   const int64_t r1 = r0 + a.rows_per_chunk < a.n ? r0 + a.rows_per_chunk : a.n;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll 4
   for (int64_t i = r0 + rl; i < r1; i += 16) {
     float v[8];
     load8<FP32>(a.Kc, base + i * a.stride_n + cg * 8, v);
@@ -32,11 +33,23 @@ __global__ __launch_bounds__(256) void key_mean_partial_kernel(MeanArgs a) {
   }
 }
 
-__global__ __launch_bounds__(kHeadDim) void key_mean_final_kernel(MeanArgs a) {
+// Sums the chunk partials of one (batch, KV head) in a fixed order: eight groups of 128
+// threads take every eighth chunk (independent loads), LDS joins the groups.
+__global__ __launch_bounds__(1024) void key_mean_final_kernel(MeanArgs a) {
+  __shared__ double red[8][kHeadDim];
   const int unit = blockIdx.x;
+  const int d = threadIdx.x & (kHeadDim - 1), grp = threadIdx.x >> 7;
   double s = 0.0;
-  for (int c = 0; c < a.nchunk; ++c) s += a.partial[((int64_t)unit * a.nchunk + c) * kHeadDim + threadIdx.x];
-  a.mu[(int64_t)unit * kHeadDim + threadIdx.x] = a.n > 0 ? (float)(s / (double)a.n) : 0.f;
+#pragma unroll 4
+  for (int c = grp; c < a.nchunk; c += 8) s += a.partial[((int64_t)unit * a.nchunk + c) * kHeadDim + d];
+  red[grp][d] = s;
+  __syncthreads();
+  if (grp == 0) {
+    double t = 0.0;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) t += red[r][d];
+    a.mu[(int64_t)unit * kHeadDim + d] = a.n > 0 ? (float)(t / (double)a.n) : 0.f;
+  }
 }
 
 hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s) {
@@ -48,7 +61,7 @@ hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(key_mean_final_kernel, dim3((unsigned)a.units), dim3(kHeadDim), 0, s, a);
+  hipLaunchKernelGGL(key_mean_final_kernel, dim3((unsigned)a.units), dim3(1024), 0, s, a);
   return hipGetLastError();
 }
 

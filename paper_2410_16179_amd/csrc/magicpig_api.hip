@@ -40,7 +40,7 @@ int check_strides(int64_t sb, int64_t sh, int64_t sn) {
   return MAGICPIG_OK;
 }
 
-constexpr int64_t kMeanRowsPerChunk = 1024;
+constexpr int64_t kMeanRowsPerChunk = 256;
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
