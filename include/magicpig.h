@@ -133,6 +133,28 @@ int magicpig_sampled_attention(const magicpig_params* params, const void* q, con
                                int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---- bucketed hash tables (the paper's retrieval structure: Algorithm 1 "Query(HT, q_code)";
+ * App. E.2: L tables per key-value head, one key index per key and table) ----
+ * For every (batch, KV head) and table the keys [0, n_ctx) are grouped by their K-bit code:
+ * a decode step then reads only the L buckets selected by the query's codes instead of every
+ * key's code, and obtains the same counts on the keys it touches and the same sample S.
+ * Supported for K <= 12, L <= 255, batch * n_q_heads <= 65535 (otherwise the size is 0 and the
+ * calls return MAGICPIG_UNSUPPORTED).  The buffer holds [batch*n_kv_heads][L][2^K + 1] uint32
+ * bucket offsets followed (256-byte aligned) by [batch*n_kv_heads][L][n_cap] uint32 key indices;
+ * the order of the indices inside a bucket is unspecified.  Tables are rebuilt from the packed
+ * key codes; they are not extended incrementally. */
+size_t magicpig_table_bytes(const magicpig_params* params);
+int magicpig_build_tables(const magicpig_params* params, const uint32_t* key_codes, void* tables,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+/* magicpig_sampled_attention with the collision scan replaced by the table lookup; every other
+ * argument, the result and the debug outputs are as there (dbg_counts is 0 for keys that share
+ * no bucket with the query, which is also their true count). */
+int magicpig_sampled_attention_tables(const magicpig_params* params, const void* q, const void* K_cache,
+                                      const void* V_cache, const float* mu, const void* tables,
+                                      const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
+                                      int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Profiling aid (the only per-thread setting the library keeps): when `events` is non-NULL it
  * points to four hipEvent_t handles which later magicpig_sampled_attention calls on this host
  * thread record on their stream - before the collision scan, after it, after the gather /

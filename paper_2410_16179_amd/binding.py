@@ -40,7 +40,8 @@ EXPORTS = (
     "magicpig_key_code_index", "magicpig_workspace_bytes", "magicpig_key_mean",
     "magicpig_hash_keys", "magicpig_hash_query", "magicpig_sampled_attention",
     "magicpig_status_string", "magicpig_last_hip_error", "magicpig_profile_stage_events",
-    "magicpig_hash_keys_stats_offset",
+    "magicpig_hash_keys_stats_offset", "magicpig_table_bytes", "magicpig_build_tables",
+    "magicpig_sampled_attention_tables",
 )
 
 _lib = None
@@ -58,7 +59,7 @@ def lib() -> ctypes.CDLL:
     vp, sz, i32, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int64
     for name in ("magicpig_code_words_per_key", "magicpig_key_code_bytes",
                  "magicpig_query_code_bytes", "magicpig_workspace_bytes",
-                 "magicpig_hash_keys_stats_offset"):
+                 "magicpig_hash_keys_stats_offset", "magicpig_table_bytes"):
         getattr(L, name).restype, getattr(L, name).argtypes = sz, [P]
     L.magicpig_key_code_index.restype = sz
     L.magicpig_key_code_index.argtypes = [P, i32, i32, i64, i32]
@@ -70,6 +71,10 @@ def lib() -> ctypes.CDLL:
     L.magicpig_hash_query.argtypes = [P, vp, vp, vp, vp, sz, vp]
     L.magicpig_sampled_attention.restype = ctypes.c_int
     L.magicpig_sampled_attention.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
+    L.magicpig_build_tables.restype = ctypes.c_int
+    L.magicpig_build_tables.argtypes = [P, vp, vp, vp, sz, vp]
+    L.magicpig_sampled_attention_tables.restype = ctypes.c_int
+    L.magicpig_sampled_attention_tables.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
     L.magicpig_status_string.restype, L.magicpig_status_string.argtypes = ctypes.c_char_p, [ctypes.c_int]
     L.magicpig_last_hip_error.restype, L.magicpig_last_hip_error.argtypes = ctypes.c_char_p, []
     L.magicpig_profile_stage_events.restype = None
@@ -165,6 +170,24 @@ def magicpig_sampled_attention(params, q, K_cache, V_cache, mu, key_codes, q_cod
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
+def magicpig_table_bytes(params) -> int:
+    return lib().magicpig_table_bytes(ctypes.byref(params))
+
+
+def magicpig_build_tables(params, key_codes, tables, workspace) -> None:
+    _check(lib().magicpig_build_tables(ctypes.byref(params), _ptr(key_codes), _ptr(tables), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream()))
+
+
+def magicpig_sampled_attention_tables(params, q, K_cache, V_cache, mu, tables, q_codes, out,
+                                      dbg_counts=None, dbg_cand=None, dbg_ncand=None, workspace=None) -> None:
+    cap = 0 if dbg_cand is None else dbg_cand.shape[-1]
+    _check(lib().magicpig_sampled_attention_tables(
+        ctypes.byref(params), _ptr(q), _ptr(K_cache), _ptr(V_cache), _ptr(mu), _ptr(tables),
+        _ptr(q_codes), _ptr(out), _ptr(dbg_counts), _ptr(dbg_cand), _ptr(dbg_ncand), cap,
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
 def magicpig_profile_stage_events(events) -> None:
     """events: None, or four hipEvent_t handles (ints) recorded around the decode kernels."""
     if events is None:
@@ -181,6 +204,13 @@ def alloc_key_codes(params, device="cuda") -> torch.Tensor:
 
 def alloc_query_codes(params, device="cuda") -> torch.Tensor:
     return torch.zeros(max(magicpig_query_code_bytes(params) // 4, 4), dtype=torch.int32, device=device)
+
+
+def alloc_tables(params, device="cuda") -> torch.Tensor:
+    nbytes = magicpig_table_bytes(params)
+    if nbytes == 0:
+        raise MagicpigError("hash tables are not supported for these parameters")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
 def alloc_workspace(params, device="cuda") -> torch.Tensor:

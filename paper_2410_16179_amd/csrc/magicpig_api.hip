@@ -90,9 +90,69 @@ AttnWs ws_attention_layout(const magicpig_params* p) {
 }
 size_t ws_attention(const magicpig_params* p) { return ws_attention_layout(p).total; }
 
+bool tables_supported(const magicpig_params* p) {
+  // bucket offsets are 2^K + 1 words per table; hit counters are bytes; one grid row per head
+  return p->K <= 12 && p->L <= 255 && (int64_t)p->batch * p->n_q_heads <= 65535;
+}
+
+void fill_table_args(const magicpig_params* p, const void* tables, mp::TableArgs* t) {
+  const size_t units = (size_t)p->batch * p->n_kv_heads;
+  char* base = reinterpret_cast<char*>(const_cast<void*>(tables));
+  t->kcodes = nullptr;
+  t->offsets = reinterpret_cast<uint32_t*>(base);
+  t->indices = reinterpret_cast<uint32_t*>(base + align256(units * p->L * (((size_t)1 << p->K) + 1) * 4));
+  t->K = p->K; t->L = p->L; t->NW = mp::code_words(p->K, p->L); t->units = (int)units;
+  t->n = p->n_ctx; t->n_cap = p->n_cap; t->blocks_cap = mp::key_blocks(p->n_cap);
+}
+
 }  // namespace
 
 extern "C" {
+
+int run_attention_impl(const magicpig_params* p, const void* q, const void* K_cache,
+                         const void* V_cache, const float* mu, const uint32_t* key_codes,
+                         const void* tables, const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
+                         int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int st = check_params(p);
+  if (st != MAGICPIG_OK) return st;
+  if ((st = check_strides(p->k_stride_b, p->k_stride_h, p->k_stride_n)) != MAGICPIG_OK) return st;
+  if ((st = check_strides(p->v_stride_b, p->v_stride_h, p->v_stride_n)) != MAGICPIG_OK) return st;
+  const bool has_keys = p->n_ctx > 0 && p->batch > 0;
+  if (!out || !workspace || (!q && p->batch > 0)) return MAGICPIG_INVALID_ARG;
+  if (has_keys && (!K_cache || !V_cache || (!key_codes && !tables) || !q_codes)) return MAGICPIG_INVALID_ARG;
+  if ((dbg_cand != nullptr) != (dbg_ncand != nullptr) || dbg_cand_cap < 0) return MAGICPIG_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(K_cache) || !aligned16(V_cache) || !aligned16(key_codes) || !aligned16(tables) ||
+      !aligned16(q_codes) || !aligned16(out) || !aligned16(workspace) || (mu && !aligned16(mu)))
+    return MAGICPIG_INVALID_ARG;
+  if (workspace_bytes < ws_attention(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
+  mp::AttnArgs a{};
+  a.q = q; a.Kc = K_cache; a.Vc = V_cache; a.mu = mu; a.kcodes = key_codes; a.qcodes = q_codes;
+  const AttnWs wl = ws_attention_layout(p);
+  char* wsb = reinterpret_cast<char*>(workspace);
+  a.partial = reinterpret_cast<float*>(wsb + wl.partial_off); a.out = out;
+  a.masks = reinterpret_cast<uint64_t*>(wsb + wl.masks_off);
+  a.nranges = wl.nranges; a.nscan = wl.nscan; a.n_static = wl.n_static;
+  a.dbg_counts = dbg_counts; a.dbg_cand = dbg_cand; a.dbg_ncand = dbg_ncand; a.dbg_cand_cap = dbg_cand_cap;
+  a.is_fp32 = p->dtype == MAGICPIG_FP32;
+  a.B = p->batch; a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.K = p->K; a.L = p->L;
+  a.Wd = mp::table_words(p->L); a.NW = mp::code_words(p->K, p->L);
+  a.tau = p->min_hits; a.n_sink = p->n_sink; a.n_local = p->n_local;
+  a.n = p->n_ctx; a.blocks_cap = mp::key_blocks(p->n_cap);
+  a.ks_b = p->k_stride_b; a.ks_h = p->k_stride_h; a.ks_n = p->k_stride_n;
+  a.vs_b = p->v_stride_b; a.vs_h = p->v_stride_h; a.vs_n = p->v_stride_n;
+  a.scale = 0.08838834764831845f;   // 1/sqrt(128)
+  mp::TableArgs t{};
+  if (tables) {
+    if (!tables_supported(p)) return MAGICPIG_UNSUPPORTED;
+    fill_table_args(p, tables, &t);
+  }
+  const hipError_t e = mp::launch_sampled_attention(a, tables ? &t : nullptr, reinterpret_cast<hipStream_t>(hip_stream),
+                                                    g_have_stage_events ? g_stage_events : nullptr);
+  return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
+}
+
+
 
 size_t magicpig_code_words_per_key(const magicpig_params* p) {
   if (check_params(p) != MAGICPIG_OK) return 0;
@@ -230,37 +290,39 @@ int magicpig_sampled_attention(const magicpig_params* p, const void* q, const vo
                                const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
                                int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (p && p->n_ctx > 0 && p->batch > 0 && !key_codes) return MAGICPIG_INVALID_ARG;
+  return run_attention_impl(p, q, K_cache, V_cache, mu, key_codes, nullptr, q_codes, out, dbg_counts, dbg_cand,
+                       dbg_ncand, dbg_cand_cap, workspace, workspace_bytes, hip_stream);
+}
+
+size_t magicpig_table_bytes(const magicpig_params* p) {
+  if (check_params(p) != MAGICPIG_OK || !tables_supported(p)) return 0;
+  const size_t units = (size_t)p->batch * p->n_kv_heads;
+  return align256(units * p->L * (((size_t)1 << p->K) + 1) * 4) + align256(units * p->L * (size_t)p->n_cap * 4);
+}
+
+int magicpig_build_tables(const magicpig_params* p, const uint32_t* key_codes, void* tables,
+                          void* workspace, size_t workspace_bytes, void* hip_stream) {
   int st = check_params(p);
   if (st != MAGICPIG_OK) return st;
-  if ((st = check_strides(p->k_stride_b, p->k_stride_h, p->k_stride_n)) != MAGICPIG_OK) return st;
-  if ((st = check_strides(p->v_stride_b, p->v_stride_h, p->v_stride_n)) != MAGICPIG_OK) return st;
-  const bool has_keys = p->n_ctx > 0 && p->batch > 0;
-  if (!out || !workspace || (!q && p->batch > 0)) return MAGICPIG_INVALID_ARG;
-  if (has_keys && (!K_cache || !V_cache || !key_codes || !q_codes)) return MAGICPIG_INVALID_ARG;
-  if ((dbg_cand != nullptr) != (dbg_ncand != nullptr) || dbg_cand_cap < 0) return MAGICPIG_INVALID_ARG;
-  if (!aligned16(q) || !aligned16(K_cache) || !aligned16(V_cache) || !aligned16(key_codes) ||
-      !aligned16(q_codes) || !aligned16(out) || !aligned16(workspace) || (mu && !aligned16(mu)))
-    return MAGICPIG_INVALID_ARG;
-  if (workspace_bytes < ws_attention(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
-  mp::AttnArgs a{};
-  a.q = q; a.Kc = K_cache; a.Vc = V_cache; a.mu = mu; a.kcodes = key_codes; a.qcodes = q_codes;
-  const AttnWs wl = ws_attention_layout(p);
-  char* wsb = reinterpret_cast<char*>(workspace);
-  a.partial = reinterpret_cast<float*>(wsb + wl.partial_off); a.out = out;
-  a.masks = reinterpret_cast<uint64_t*>(wsb + wl.masks_off);
-  a.nranges = wl.nranges; a.nscan = wl.nscan; a.n_static = wl.n_static;
-  a.dbg_counts = dbg_counts; a.dbg_cand = dbg_cand; a.dbg_ncand = dbg_ncand; a.dbg_cand_cap = dbg_cand_cap;
-  a.is_fp32 = p->dtype == MAGICPIG_FP32;
-  a.B = p->batch; a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.K = p->K; a.L = p->L;
-  a.Wd = mp::table_words(p->L); a.NW = mp::code_words(p->K, p->L);
-  a.tau = p->min_hits; a.n_sink = p->n_sink; a.n_local = p->n_local;
-  a.n = p->n_ctx; a.blocks_cap = mp::key_blocks(p->n_cap);
-  a.ks_b = p->k_stride_b; a.ks_h = p->k_stride_h; a.ks_n = p->k_stride_n;
-  a.vs_b = p->v_stride_b; a.vs_h = p->v_stride_h; a.vs_n = p->v_stride_n;
-  a.scale = 0.08838834764831845f;   // 1/sqrt(128)
-  const hipError_t e = mp::launch_sampled_attention(a, reinterpret_cast<hipStream_t>(hip_stream),
-                                                    g_have_stage_events ? g_stage_events : nullptr);
+  if (!tables_supported(p)) return MAGICPIG_UNSUPPORTED;
+  if (!key_codes || !tables || !aligned16(key_codes) || !aligned16(tables)) return MAGICPIG_INVALID_ARG;
+  (void)workspace; (void)workspace_bytes;
+  mp::TableArgs t{};
+  fill_table_args(p, tables, &t);
+  t.kcodes = key_codes;
+  const hipError_t e = mp::launch_build_tables(t, reinterpret_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
+}
+
+int magicpig_sampled_attention_tables(const magicpig_params* p, const void* q, const void* K_cache,
+                                      const void* V_cache, const float* mu, const void* tables,
+                                      const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
+                                      int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (p && p->n_ctx > 0 && p->batch > 0 && !tables) return MAGICPIG_INVALID_ARG;
+  return run_attention_impl(p, q, K_cache, V_cache, mu, nullptr, tables, q_codes, out, dbg_counts, dbg_cand,
+                       dbg_ncand, dbg_cand_cap, workspace, workspace_bytes, hip_stream);
 }
 
 void magicpig_profile_stage_events(void* const* events) {

@@ -77,6 +77,15 @@ struct AttnArgs {
   float scale;
 };
 
+// Bucketed hash tables of the cached keys.
+struct TableArgs {
+  const uint32_t* kcodes;      // packed key codes (build only)
+  uint32_t* offsets;           // [units][L][2^K + 1]
+  uint32_t* indices;           // [units][L][n_cap]
+  int K, L, NW, units;
+  int64_t n, n_cap, blocks_cap;
+};
+
 constexpr int kPartialStride = 132;   // 128 output elements, running max, running sum, pad
 constexpr int kRangeBlocks = 16;      // key blocks per gather wavefront (1024 keys)
 constexpr int kStaticPerRange = 32;   // static (sink / local) keys per gather wavefront
@@ -86,7 +95,9 @@ hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s);
 hipError_t launch_hash_query(const HashDirectArgs& a, hipStream_t s);
 hipError_t launch_hash_keys_mfma(const HashMfmaArgs& a, hipStream_t s);
 hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s);
-hipError_t launch_sampled_attention(const AttnArgs& a, hipStream_t s, hipEvent_t const* stage_events);
+hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, hipStream_t s, hipEvent_t const* stage_events);
+hipError_t launch_build_tables(const TableArgs& t, hipStream_t s);
+hipError_t launch_table_lookup(const AttnArgs& a, const TableArgs& t, hipStream_t s);
 
 
 }  // namespace mp

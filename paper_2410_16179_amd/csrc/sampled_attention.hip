@@ -341,7 +341,7 @@ static hipError_t launch_scan(const AttnArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_sampled_attention(const AttnArgs& a, hipStream_t s, hipEvent_t const* ev) {
+hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, hipStream_t s, hipEvent_t const* ev) {
   const int64_t heads = (int64_t)a.B * a.Hq;
   if (heads <= 0) return hipSuccess;
   if (a.nranges <= 0) {      // no keys: the output is defined as the zero vector
@@ -351,7 +351,8 @@ hipError_t launch_sampled_attention(const AttnArgs& a, hipStream_t s, hipEvent_t
   }
   hipError_t e;
   if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return e;
-  if ((e = launch_scan(a, s)) != hipSuccess) return e;
+  // retrieval: stream every key's code, or look the query's codes up in the hash tables
+  if ((e = tables ? launch_table_lookup(a, *tables, s) : launch_scan(a, s)) != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return e;
   const dim3 grid((unsigned)a.nranges, (unsigned)(a.B * a.Hkv)), block(64 * (a.Hq / a.Hkv));
   if (a.is_fp32) hipLaunchKernelGGL(gather_estimate_kernel<true>, grid, block, 0, s, a);

@@ -91,18 +91,26 @@ class Session:
         qw = pack_table_codes(q_codes, self.K, self.L, 1).ravel()
         self.q_codes[: qw.size].copy_(torch.from_numpy(qw.view(np.int32)))
 
-    def attend(self, debug=True, cand_cap=None):
+    def build_tables(self):
+        self.tables = mp.alloc_tables(self.params)
+        mp.magicpig_build_tables(self.params, self.key_codes, self.tables, self.ws)
+
+    def attend(self, debug=True, cand_cap=None, tables=False):
         B, Hq, n = self.B, self.Hq, self.n
         out = torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device="cuda")
         if debug:
             cap = max(n, 1) if cand_cap is None else cand_cap
-            counts = torch.full((B, Hq, max(n, 1)), -1, dtype=torch.int16, device="cuda")
+            counts = torch.full((B, Hq, max(n, 1)), -1 if not tables else 0, dtype=torch.int16, device="cuda")
             cand = torch.full((B, Hq, cap), -1, dtype=torch.int32, device="cuda")
             ncand = torch.zeros((B, Hq), dtype=torch.int32, device="cuda")
         else:
             counts = cand = ncand = None
-        mp.magicpig_sampled_attention(self.params, self.q, self.Kc, self.Vc, self.mu, self.key_codes,
-                                      self.q_codes, out, counts, cand, ncand, self.ws)
+        if tables:
+            mp.magicpig_sampled_attention_tables(self.params, self.q, self.Kc, self.Vc, self.mu, self.tables,
+                                                 self.q_codes, out, counts, cand, ncand, self.ws)
+        else:
+            mp.magicpig_sampled_attention(self.params, self.q, self.Kc, self.Vc, self.mu, self.key_codes,
+                                          self.q_codes, out, counts, cand, ncand, self.ws)
         torch.cuda.synchronize()
         res = {"out": out.cpu().numpy()}
         if debug:
