@@ -156,9 +156,10 @@ int magicpig_sampled_attention_tables(const magicpig_params* params, const void*
                                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Profiling aid (the only per-thread setting the library keeps): when `events` is non-NULL it
- * points to four hipEvent_t handles which later magicpig_sampled_attention calls on this host
- * thread record on their stream - before the collision scan, after it, after the gather /
- * estimator kernel, after the merge.  NULL switches the recording off again. */
+ * points to four hipEvent_t handles which later magicpig_sampled_attention[_tables] calls on
+ * this host thread attach to their kernels: events[0] / events[1] receive the begin / end
+ * timestamp of the retrieval kernel (collision scan or table lookup), events[2] the end of the
+ * gather / estimator kernel, events[3] the end of the merge kernel.  NULL switches it off. */
 void magicpig_profile_stage_events(void* const* events);
 
 const char* magicpig_status_string(int status);

@@ -13,6 +13,7 @@
 //       (count >= min_hits, key not static) that collision_scan_kernel emits, so the gather
 //       and merge kernels are shared by both retrieval forms.
 #include "attention_common.h"
+#include <hip/hip_ext.h>
 
 namespace mp {
 
@@ -208,10 +209,11 @@ hipError_t launch_build_tables(const TableArgs& t, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_table_lookup(const AttnArgs& a, const TableArgs& t, hipStream_t s) {
+hipError_t launch_table_lookup(const AttnArgs& a, const TableArgs& t, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
   const int64_t nblk = key_blocks(a.n);
   const dim3 grid((unsigned)((nblk + kLookupRunBlocks - 1) / kLookupRunBlocks), (unsigned)((int64_t)a.B * a.Hq));
-  hipLaunchKernelGGL(table_lookup_kernel, grid, dim3(1024), 0, s, a, t);
+  if (start || stop) hipExtLaunchKernelGGL(table_lookup_kernel, grid, dim3(1024), 0, s, start, stop, 0, a, t);
+  else hipLaunchKernelGGL(table_lookup_kernel, grid, dim3(1024), 0, s, a, t);
   return hipGetLastError();
 }
 

@@ -97,7 +97,7 @@ hipError_t launch_hash_keys_mfma(const HashMfmaArgs& a, hipStream_t s);
 hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s);
 hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, hipStream_t s, hipEvent_t const* stage_events);
 hipError_t launch_build_tables(const TableArgs& t, hipStream_t s);
-hipError_t launch_table_lookup(const AttnArgs& a, const TableArgs& t, hipStream_t s);
+hipError_t launch_table_lookup(const AttnArgs& a, const TableArgs& t, hipStream_t s, hipEvent_t start, hipEvent_t stop);
 
 
 }  // namespace mp

@@ -20,6 +20,7 @@
 // merge_partials_kernel combines a head's partials (the "recursive attention" merge of
 //   Sec. 4.4) and writes the output row.
 #include "attention_common.h"
+#include <hip/hip_ext.h>
 
 #ifndef MP_SCAN_BPW
 #define MP_SCAN_BPW 1
@@ -325,19 +326,27 @@ __global__ void zero_output_kernel(float* out, int64_t count) {
   if (i < count) out[i] = 0.f;
 }
 
-static hipError_t launch_scan(const AttnArgs& a, hipStream_t s) {
+// Ordinary launch, or - when events are given - a launch whose events carry the kernel's own
+// begin / end timestamps (what a profiler reports), not the stream's dispatch times.
+template <class F, class... Args>
+static void launch_timed(F kernel, dim3 grid, dim3 block, hipStream_t s, hipEvent_t start, hipEvent_t stop, Args... args) {
+  if (start || stop) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, start, stop, 0, args...);
+  else hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
+}
+
+static hipError_t launch_scan(const AttnArgs& a, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
   constexpr int kBPW = MP_SCAN_BPW;
   const dim3 block(256);
   const dim3 grid_t((unsigned)((key_blocks(a.n) + 4 * kBPW - 1) / (4 * kBPW)), (unsigned)(a.B * a.Hkv));
 #define MP_TUNED(KT, WDT)                                                                  \
   if (a.K == KT && a.Wd == WDT) {                                                          \
-    hipLaunchKernelGGL((collision_scan_kernel<KT, WDT, kBPW>), grid_t, block, 0, s, a);    \
+    launch_timed(collision_scan_kernel<KT, WDT, kBPW>, grid_t, block, s, start, stop, a);  \
     return hipGetLastError();                                                              \
   }
   MP_TUNED(10, 5) MP_TUNED(9, 4) MP_TUNED(10, 6) MP_TUNED(8, 3)
 #undef MP_TUNED
   const dim3 grid((unsigned)((key_blocks(a.n) + 3) / 4), (unsigned)(a.B * a.Hkv));
-  hipLaunchKernelGGL((collision_scan_kernel<0, 0, 1>), grid, block, 0, s, a);
+  launch_timed(collision_scan_kernel<0, 0, 1>, grid, block, s, start, stop, a);
   return hipGetLastError();
 }
 
@@ -350,18 +359,16 @@ hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, 
     return hipGetLastError();
   }
   hipError_t e;
-  if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return e;
   // retrieval: stream every key's code, or look the query's codes up in the hash tables
-  if ((e = tables ? launch_table_lookup(a, *tables, s) : launch_scan(a, s)) != hipSuccess) return e;
-  if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return e;
+  e = tables ? launch_table_lookup(a, *tables, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr)
+             : launch_scan(a, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr);
+  if (e != hipSuccess) return e;
   const dim3 grid((unsigned)a.nranges, (unsigned)(a.B * a.Hkv)), block(64 * (a.Hq / a.Hkv));
-  if (a.is_fp32) hipLaunchKernelGGL(gather_estimate_kernel<true>, grid, block, 0, s, a);
-  else hipLaunchKernelGGL(gather_estimate_kernel<false>, grid, block, 0, s, a);
+  if (a.is_fp32) launch_timed(gather_estimate_kernel<true>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);
+  else launch_timed(gather_estimate_kernel<false>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
-  hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)heads), dim3(256), 0, s, a);
+  launch_timed(merge_partials_kernel, dim3((unsigned)heads), dim3(256), s, nullptr, ev ? ev[3] : nullptr, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (ev && (e = hipEventRecord(ev[3], s)) != hipSuccess) return e;
   return hipSuccess;
 }
 
