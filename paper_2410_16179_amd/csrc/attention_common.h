@@ -59,4 +59,118 @@ __device__ inline void load_code_block(const uint32_t* blkp, int lane, uint32_t 
   }
 }
 
+// j-th key of the static set T: the sink keys, then the local window (every key when the
+// context is no longer than n_sink + n_local).
+__device__ inline int64_t static_key(const AttnArgs& a, int64_t j) {
+  const int64_t sink_keys = a.n_static < a.n ? a.n_sink : a.n_static;
+  return j < sink_keys ? j : j + (a.n - a.n_local - a.n_sink);
+}
+
+// One wavefront attends the keys key_of(0) .. key_of(total - 1) of query head bh (KV unit
+// `unit`) and stores one (output[128], max, sum) partial at `pp`.  A quarter wavefront holds
+// one 128-element row; all K and V rows of a batch are requested before any is used; q.k,
+// q.(k-mu), |k-mu|^2 are reduced over the 16 lanes of a row; the inclusion probability and
+// the logit q.k/sqrt(d) - log u are evaluated once per key (sampled keys only: static keys
+// enter with u = 1); an online max/sum softmax accumulates the weighted V rows.
+template <bool FP32, class KeyOf>
+__device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t bh, int total, bool sampled,
+                                            KeyOf key_of, float* pp) {
+  constexpr int kIters = FP32 ? 4 : 8;                    // rows per quarter-wavefront and batch
+  const int lane = threadIdx.x & 63;
+  const int b = unit / a.Hkv, g = unit % a.Hkv;
+  const int qd = lane >> 4, sl = lane & 15;
+  const int64_t kbase = (int64_t)b * a.ks_b + (int64_t)g * a.ks_h + sl * 8;
+  const int64_t vbase = (int64_t)b * a.vs_b + (int64_t)g * a.vs_h + sl * 8;
+  float muf[8], qf[8], o[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { muf[e] = 0.f; o[e] = 0.f; }
+  if (a.mu) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) muf[e] = a.mu[(int64_t)unit * kHeadDim + sl * 8 + e];
+  }
+  {
+    Frag f;
+    frag_load<FP32>(a.q, bh * kHeadDim + sl * 8, f);
+    frag_to_float<FP32>(f, qf);
+  }
+  float qq = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) qq += qf[e] * qf[e];
+  const float qnorm = sqrtf(row_sum16(qq));
+  float m_run = -INFINITY, l_run = 0.f;
+
+  for (int base = 0; base < total; base += 4 * kIters) {
+    Frag kf[kIters], vf[kIters];
+    bool ok[kIters];
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+      const int cc = base + it * 4 + qd;
+      ok[it] = cc < total;
+      const int64_t idx = key_of(ok[it] ? cc : base);
+      if (ok[it]) {
+        frag_load<FP32>(a.Kc, kbase + idx * a.ks_n, kf[it]);
+        frag_load<FP32>(a.Vc, vbase + idx * a.vs_n, vf[it]);
+      } else {
+        frag_zero<FP32>(kf[it]);
+        frag_zero<FP32>(vf[it]);
+      }
+    }
+    // lane sl == it of quarter qd keeps candidate base + 4*it + qd
+    float my_dq = 0.f, my_dc = 0.f, my_nn = 0.f;
+    bool my_ok = false;
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+      float kv[8];
+      frag_to_float<FP32>(kf[it], kv);
+      float dq = 0.f, dc = 0.f, nn = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float kc = kv[e] - muf[e];
+        dq += qf[e] * kv[e];
+        dc += qf[e] * kc;
+        nn += kc * kc;
+      }
+      dq = row_sum16(dq);
+      dc = row_sum16(dc);
+      nn = row_sum16(nn);
+      if (sl == it) { my_dq = dq; my_dc = dc; my_nn = nn; my_ok = ok[it]; }
+    }
+    float logit = -INFINITY;
+    if (sl < kIters && my_ok) {
+      logit = my_dq * a.scale;
+      if (sampled && a.tau > 0) {
+        const float den = qnorm * sqrtf(my_nn);
+        const float cosv = den > 0.f ? my_dc / den : 0.f;
+        const float u = fmaxf(inclusion_probability(cosv, a.K, a.L, a.tau), 1.17549435e-38f);
+        logit -= __logf(u);
+      }
+    }
+    const float m_new = fmaxf(m_run, wave_max(logit));   // finite: the batch is not empty
+    const float alpha = __expf(m_run - m_new);           // m_run = -inf gives 0
+    const float wgt = logit > -INFINITY ? __expf(logit - m_new) : 0.f;
+    l_run = l_run * alpha + wave_sum(wgt);
+    m_run = m_new;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] *= alpha;
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+      const float wv = __shfl(wgt, (lane & 48) | it);
+      float vv[8];
+      frag_to_float<FP32>(vf[it], vv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] += wv * vv[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    o[e] += __shfl_xor(o[e], 16);
+    o[e] += __shfl_xor(o[e], 32);
+  }
+  if (lane < 16) {
+    *reinterpret_cast<float4*>(pp + sl * 8) = make_float4(o[0], o[1], o[2], o[3]);
+    *reinterpret_cast<float4*>(pp + sl * 8 + 4) = make_float4(o[4], o[5], o[6], o[7]);
+  }
+  if (lane == 0) { pp[128] = m_run; pp[129] = l_run; }
+}
+
 }  // namespace mp

@@ -112,7 +112,6 @@ __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
 // the G wavefronts of a workgroup serve the G heads of one KV head on the same run.
 template <bool FP32>
 __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
-  constexpr int kIters = FP32 ? 4 : 8;                    // rows per quarter-wavefront and batch
   __shared__ uint16_t lists[8][kRangeBlocks * kBlockKeys];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int unit = blockIdx.y, range = blockIdx.x;
@@ -153,113 +152,14 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
     const int64_t left = a.n_static - static_first;
     total = (int)(left < kStaticPerRange ? left : kStaticPerRange);
   }
-  // j-th key of T: the sink keys, then the local window (all keys when the context is short)
-  const int64_t sink_keys = a.n_static < a.n ? a.n_sink : a.n_static;
-  const int64_t local_shift = a.n - a.n_local - a.n_sink;
-
-  // ---- gather + estimator ----
-  const int qd = lane >> 4, sl = lane & 15;
-  const int64_t kbase = (int64_t)b * a.ks_b + (int64_t)g * a.ks_h + sl * 8;
-  const int64_t vbase = (int64_t)b * a.vs_b + (int64_t)g * a.vs_h + sl * 8;
-  float muf[8], qf[8], o[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) { muf[e] = 0.f; o[e] = 0.f; }
-  if (a.mu) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) muf[e] = a.mu[(int64_t)unit * kHeadDim + sl * 8 + e];
-  }
-  {
-    Frag f;
-    frag_load<FP32>(a.q, bh * kHeadDim + sl * 8, f);
-    frag_to_float<FP32>(f, qf);
-  }
-  float qq = 0.f;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) qq += qf[e] * qf[e];
-  const float qnorm = sqrtf(row_sum16(qq));
-  float m_run = -INFINITY, l_run = 0.f;
-
-  for (int base = 0; base < total; base += 4 * kIters) {
-    Frag kf[kIters], vf[kIters];
-    int64_t idx[kIters];
-    bool ok[kIters];
-#pragma unroll
-    for (int it = 0; it < kIters; ++it) {
-      const int cc = base + it * 4 + qd;
-      ok[it] = cc < total;
-      if (!is_static) {
-        idx[it] = blk0 * kBlockKeys + (ok[it] ? list[cc] : 0);
-      } else {
-        const int64_t jt = static_first + (ok[it] ? cc : 0);
-        idx[it] = jt < sink_keys ? jt : jt + local_shift;
-      }
-      if (ok[it]) {
-        frag_load<FP32>(a.Kc, kbase + idx[it] * a.ks_n, kf[it]);
-        frag_load<FP32>(a.Vc, vbase + idx[it] * a.vs_n, vf[it]);
-      } else {
-        frag_zero<FP32>(kf[it]);
-        frag_zero<FP32>(vf[it]);
-      }
-    }
-    // lane sl == it of quarter qd keeps candidate base + 4*it + qd
-    float my_dq = 0.f, my_dc = 0.f, my_nn = 0.f;
-    int64_t my_i = 0;
-    bool my_ok = false;
-#pragma unroll
-    for (int it = 0; it < kIters; ++it) {
-      float kv[8];
-      frag_to_float<FP32>(kf[it], kv);
-      float dq = 0.f, dc = 0.f, nn = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float kc = kv[e] - muf[e];
-        dq += qf[e] * kv[e];
-        dc += qf[e] * kc;
-        nn += kc * kc;
-      }
-      dq = row_sum16(dq);
-      dc = row_sum16(dc);
-      nn = row_sum16(nn);
-      if (sl == it) { my_dq = dq; my_dc = dc; my_nn = nn; my_i = idx[it]; my_ok = ok[it]; }
-    }
-    float logit = -INFINITY;
-    if (sl < kIters && my_ok) {
-      logit = my_dq * a.scale;
-      if (!is_static && a.tau > 0) {
-        const float den = qnorm * sqrtf(my_nn);
-        const float cosv = den > 0.f ? my_dc / den : 0.f;
-        const float u = fmaxf(inclusion_probability(cosv, a.K, a.L, a.tau), 1.17549435e-38f);
-        logit -= __logf(u);
-      }
-    }
-    const float m_new = fmaxf(m_run, wave_max(logit));   // finite: the batch is not empty
-    const float alpha = __expf(m_run - m_new);           // m_run = -inf gives 0
-    const float wgt = logit > -INFINITY ? __expf(logit - m_new) : 0.f;
-    l_run = l_run * alpha + wave_sum(wgt);
-    m_run = m_new;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] *= alpha;
-#pragma unroll
-    for (int it = 0; it < kIters; ++it) {
-      const float wv = __shfl(wgt, (lane & 48) | it);
-      float vv[8];
-      frag_to_float<FP32>(vf[it], vv);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] += wv * vv[e];
-    }
-  }
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    o[e] += __shfl_xor(o[e], 16);
-    o[e] += __shfl_xor(o[e], 32);
-  }
   float* pp = a.partial + (bh * a.nranges + range) * kPartialStride;
-  if (lane < 16) {
-    *reinterpret_cast<float4*>(pp + sl * 8) = make_float4(o[0], o[1], o[2], o[3]);
-    *reinterpret_cast<float4*>(pp + sl * 8 + 4) = make_float4(o[4], o[5], o[6], o[7]);
+  if (!is_static) {
+    gather_estimate_wave<FP32>(a, unit, bh, total, true,
+                               [&](int c) { return blk0 * kBlockKeys + (int64_t)list[c]; }, pp);
+  } else {
+    gather_estimate_wave<FP32>(a, unit, bh, total, false,
+                               [&](int c) { return static_key(a, static_first + c); }, pp);
   }
-  if (lane == 0) { pp[128] = m_run; pp[129] = l_run; }
-
 }
 
 // Merges the (max, sum, output) partials of one query head (256 threads: wavefront w takes
