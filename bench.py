@@ -315,7 +315,7 @@ def main():
         "input_generation_s": gen_s,
     }
     if tables_info is not None:
-        tables_info["same_output_as_scan"] = bool(np.array_equal(out_t[: w.batch], out0[: w.batch]))
+        tables_info["max_abs_diff_vs_scan_output"] = float(np.abs(out_t - out0).max())
         result["hash_tables"] = tables_info
     if not args.no_cpu_baseline:
         cb, ref, ref_heads = cpu_baseline(w, data, args.seed)

@@ -83,10 +83,11 @@ def run_case(oracle, w: wl.Workload, seed=0, alpha=0.8, use_mu=True, n_cap=None,
             np.testing.assert_array_equal(rt["counts"][b, h], ref["counts"][b, h])
             np.testing.assert_array_equal(rt["S"][b][h], ref["S"][b][h])
             assert rel_err(rt["out"][b, h][None], ref["out"][b, h][None]) <= TOL
-            np.testing.assert_array_equal(rt["out"][b, h], res["out"][b, h])
+            # same sample, same arithmetic; only the grouping of the partial sums differs
+            assert rel_err(rt["out"][b, h][None], res["out"][b, h][None]) <= 1e-5
         rt2 = s.attend(debug=False, tables=True)
         for b, h in pairs:
-            np.testing.assert_array_equal(rt2["out"][b, h], res["out"][b, h])
+            np.testing.assert_array_equal(rt2["out"][b, h], rt["out"][b, h])
     if oracle_codes_too and heads is None:       # scan fed with the oracle's own codes
         s.upload_codes(np.concatenate([ref["key_codes"], np.zeros((w.batch, w.n_kv_heads, Kc.shape[2] - n, w.L), np.int32)], axis=2),
                        ref["q_codes"])
