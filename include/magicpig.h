@@ -6,15 +6,17 @@
  * inputs K, V in R^{n x d}, q in R^{1 x d}, random projectors W in R^{d x (K*L)}, a hash
  * structure over the cached keys, and a static set T of sink + local tokens.  Here the
  * hash structure is the array of packed SimHash codes of all keys, kept in HBM and
- * scanned on every decode step; the sample S is the same set a hash-table lookup gives.
+ * scanned on every decode step, or bucketed hash tables built from those codes and
+ * looked up on every step; both give the same sample S.
  *
  * Conventions for every call
  *  - `params` is HOST memory, read during the call only.  Every other pointer is a
- *    DEVICE pointer owned by the caller (the library allocates and frees nothing and
- *    keeps no state between calls).  `workspace` is caller-owned device scratch of at
- *    least magicpig_workspace_bytes(params) bytes, 256-byte aligned; its contents need
- *    not be preserved or initialised between calls, and two calls that share it must be
- *    ordered on one stream.
+ *    DEVICE pointer owned by the caller (the library allocates and frees nothing; the
+ *    only state it keeps is the per-thread event setting of
+ *    magicpig_profile_stage_events and the last HIP error).  `workspace` is
+ *    caller-owned device scratch of at least magicpig_workspace_bytes(params) bytes,
+ *    256-byte aligned; its contents need not be preserved or initialised between calls,
+ *    and two calls that share it must be ordered on one stream.
  *  - `hip_stream` is a hipStream_t (NULL = default stream).  Calls enqueue work and
  *    return without synchronising.
  *  - Return value: MAGICPIG_OK or a negative status.  Arguments are validated before any
