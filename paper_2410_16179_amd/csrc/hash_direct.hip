@@ -30,9 +30,11 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
   __builtin_amdgcn_wave_barrier();
 
-  const int64_t row0 = ((int64_t)blockIdx.x * 4 + wave) * 2;
-  if (row0 >= a.total_rows) return;
   const int half = lane >> 5, beta = lane & 31;
+  // workgroups walk the groups of eight vectors (one step unless the grid was capped)
+  for (int64_t grp = blockIdx.x; grp * 8 < a.total_rows; grp += gridDim.x) {
+  const int64_t row0 = (grp * 4 + wave) * 2;
+  if (row0 >= a.total_rows) continue;
   const int64_t row = row0 + half;
   const bool row_ok = row < a.total_rows;
   const int64_t rr = row_ok ? row : row0;
@@ -116,6 +118,7 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
         a.codes[blk * (kBlockKeys * (int64_t)a.NW) + slot_in_block(a.NW, x, (int)(key % kBlockKeys))] = word;
       }
     }
+  }
   }
 }
 
@@ -220,8 +223,11 @@ hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s) {
   const int64_t groups = (a.total_rows + 7) / 8;
   // few vectors (queries): one workgroup per (8 vectors, word); many (keys): words looped
   const unsigned ny = groups >= 4096 ? 1u : (unsigned)a.NW;
-  if (a.is_fp32) hipLaunchKernelGGL(hash_direct_kernel<true>, dim3((unsigned)groups, ny), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(hash_direct_kernel<false>, dim3((unsigned)groups, ny), dim3(256), 0, s, a);
+  // behind the matrix-core path the kernel normally only reads its flag and leaves: a capped
+  // grid keeps that cheap, and the groups are walked in a loop if it does have to run
+  const unsigned nx = (unsigned)(a.run_flag && groups > 2048 ? 2048 : groups);
+  if (a.is_fp32) hipLaunchKernelGGL(hash_direct_kernel<true>, dim3(nx, ny), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(hash_direct_kernel<false>, dim3(nx, ny), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

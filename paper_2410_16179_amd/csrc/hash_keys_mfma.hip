@@ -44,19 +44,16 @@ __host__ __device__ inline void tile_row_to_bit(int T, int rho, int* x, int* bet
   *beta = 31 - (16 * (T & 1) + r);
 }
 
-__global__ void prep_zero_kernel(HashMfmaArgs a) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    *a.wmax_bits = 0u;
+// A-operand fragments, transposed bf16 copy of W for the recheck, norm of every projector
+// column (by tile row).  One thread per (tile row, 8-element piece of d).  Also clears the
+// counters the later kernels of the call add to.
+__global__ __launch_bounds__(256) void prep_projector_kernel(HashMfmaArgs a) {
+  const int gid = blockIdx.x * 256 + threadIdx.x;
+  if (gid == 0) {
     *a.list_count = 0u;
     *a.overflow = 0;
     *a.flagged_total = 0u;
   }
-}
-
-// A-operand fragments, transposed bf16 copy of W for the recheck, max column norm.
-// One thread per (tile row, 8-element piece of d).
-__global__ __launch_bounds__(256) void prep_projector_kernel(HashMfmaArgs a) {
-  const int gid = blockIdx.x * 256 + threadIdx.x;
   const int row = gid >> 4, piece = gid & 15;        // row = T*32 + rho
   if (row >= a.ntiles * 32) return;
   const int T = row >> 5, rho = row & 31;
@@ -81,11 +78,9 @@ __global__ __launch_bounds__(256) void prep_projector_kernel(HashMfmaArgs a) {
   pk.x = v[0] | ((uint32_t)v[1] << 16); pk.y = v[2] | ((uint32_t)v[3] << 16);
   pk.z = v[4] | ((uint32_t)v[5] << 16); pk.w = v[6] | ((uint32_t)v[7] << 16);
   reinterpret_cast<uint4*>(a.afrag)[((int64_t)T * 8 + s) * 64 + lane] = pk;
-  if (real) {
-    reinterpret_cast<uint4*>(a.wt)[(int64_t)j * 16 + piece] = pk;
-    ss = row_sum16(ss);                                // the 16 pieces of a row sit in one DPP row
-    if (piece == 0) atomicMax(a.wmax_bits, __float_as_uint(sqrtf(ss) * 1.000001f));
-  }
+  if (real) reinterpret_cast<uint4*>(a.wt)[(int64_t)j * 16 + piece] = pk;
+  ss = row_sum16(ss);                                  // the 16 pieces of a row sit in one DPP row
+  if (piece == 0) a.rownorm[row] = sqrtf(ss) * 1.000001f;   // 0 for padding rows
 }
 
 // Per (batch, KV head): initial accumulators -fl(mu.W_j) in fragment order, and |mu|.
@@ -124,7 +119,7 @@ __global__ __launch_bounds__(256) void prep_threshold_kernel(HashMfmaArgs a) {
 // from the transposed projector row); their float64 partial sums are combined by shuffles.
 // Any summation order is covered by the float64 error bound; what it cannot decide is summed
 // exactly.  The bit is then set or cleared in the stored code word.
-// List entry: unit (16 bits) | key (32 bits) | projector column (16 bits).
+// List entry: unit (16 bits) | key (32 bits) | code word x (11 bits) | bit of the word (5 bits).
 template <int LPP, class GetEntry>
 __device__ inline void recheck_pairs(const HashMfmaArgs& a, long long* limb, uint64_t count,
                                      uint64_t first, uint64_t step, GetEntry get) {
@@ -137,7 +132,8 @@ __device__ inline void recheck_pairs(const HashMfmaArgs& a, long long* limb, uin
     const uint64_t i = i0 + grp;
     const bool on = i < count;
     const unsigned long long e = get(on ? i : i0);
-    const int j = (int)(e & 0xffff);
+    const int x = (int)((e >> 5) & 0x7ff), tbit = (int)(e & 31);
+    const int j = (32 * (x / a.K) + tbit) * a.K + x % a.K;
     const int64_t unit = (int64_t)(e >> 48);
     const int64_t k = (int64_t)((e >> 16) & 0xffffffffull);
     const int ub = (int)unit / a.n_kv_heads, uh = (int)unit % a.n_kv_heads;
@@ -189,9 +185,7 @@ __device__ inline void recheck_pairs(const HashMfmaArgs& a, long long* limb, uin
       pending &= pending - 1;
     }
     if (on && sl == 0) {
-      const int t = j / a.K, b = j % a.K;
-      const int x = (t >> 5) * a.K + b;
-      const uint32_t mask = 1u << (t & 31);
+      const uint32_t mask = 1u << tbit;
       uint32_t* word = a.codes + (unit * a.blocks_cap + k / kBlockKeys) * (kBlockKeys * (int64_t)a.NW) +
                        slot_in_block(a.NW, x, (int)(k % kBlockKeys));
       if (bit) atomicOr(word, mask);
@@ -200,8 +194,20 @@ __device__ inline void recheck_pairs(const HashMfmaArgs& a, long long* limb, uin
   }
 }
 
+// One quad of fragments (4 tiles x 8 k-steps x 64 lanes x 16 bytes = 32 KB), global -> LDS
+// without passing through registers: lane l of a wavefront supplies the address of its 16
+// bytes, the hardware writes them to (wave-uniform LDS base) + 16 l.  The caller waits for
+// the vector-memory counter before the barrier that publishes the stage.
+__device__ inline void stage_quad(const uint4* gquad, uint4* stage, int tid, int wave) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(gquad + i * 256 + tid),
+        (__attribute__((address_space(3))) void*)(stage + i * 256 + wave * 64), 16, 0, 0);
+}
+
 __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) {
-  __shared__ uint4 sA[2][4 * 8 * 64];                  // two stages of one word quad: 4 tiles x 8 k-steps
+  __shared__ uint4 sA0[4 * 8 * 64], sA1[4 * 8 * 64];   // two stages of one word quad: 4 tiles x 8 k-steps
   __shared__ float sThr[2][4 * 2 * 16];
   __shared__ unsigned long long sList[kListCapLocal];
   __shared__ unsigned sCount;
@@ -216,13 +222,29 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
   const bool wave_on = cb * kBlockKeys < last;
   if (tid == 0) sCount = 0;
 
+  const int nquads = a.ntiles / 4;                       // the fragment array holds whole quads
+  const uint4* gA = reinterpret_cast<const uint4*>(a.afrag);
+  const float* gThr = a.thr + (int64_t)unit * a.ntiles * 32;
+  stage_quad(gA, sA0, tid, wave);
+  if (tid < 128) sThr[0][tid] = gThr[tid];
+
   // ---- B operand: my 64 keys, resident in registers for the whole kernel ----
   const uint16_t* Kc = reinterpret_cast<const uint16_t*>(a.Kc);
   const int64_t ubase = (int64_t)(unit / a.n_kv_heads) * a.stride_b + (int64_t)(unit % a.n_kv_heads) * a.stride_h;
   bf16x8 B[2][8];
   float bnd[2];
   int64_t key[2];
-  const float wmax = __uint_as_float(*a.wmax_bits);
+  // largest column norm of the projector
+  __shared__ float sWmax[4];
+  {
+    float wm = 0.f;
+    for (int i = tid; i < a.ntiles * 32; i += 256) wm = fmaxf(wm, a.rownorm[i]);
+    wm = wave_max(wm);
+    if (lane == 0) sWmax[wave] = wm;
+  }
+  __syncthreads();
+  const float wmax = fmaxf(fmaxf(sWmax[0], sWmax[1]), fmaxf(sWmax[2], sWmax[3]));
+  if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *a.wmax_bits = __float_as_uint(wmax);   // statistics
   const float munorm = a.munorm[unit];
 #pragma unroll
   for (int bt = 0; bt < 2; ++bt) {
@@ -246,56 +268,45 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
     bnd[bt] = ok ? (kGamma * (sqrtf(ss) * 1.000001f + munorm) * wmax) * 1.000001f + 1e-30f : -1.f;
   }
 
-  const int nquads = (a.ntiles + 3) / 4;
-  const uint4* gA = reinterpret_cast<const uint4*>(a.afrag);
-  const float* gThr = a.thr + (int64_t)unit * a.ntiles * 32;
   const int NW = a.NW;
   uint32_t* blk_codes = a.codes + ((int64_t)unit * a.blocks_cap + cb) * (kBlockKeys * (int64_t)NW);
-
-  // stage 0
-  {
-    uint4 st[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int idx = i * 256 + tid;
-      st[i] = idx < a.ntiles * 512 ? gA[idx] : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) sA[0][i * 256 + tid] = st[i];
-    if (tid < 128) sThr[0][tid] = tid < a.ntiles * 32 ? gThr[tid] : -INFINITY;
-  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
-  for (int q = 0; q < nquads; ++q) {
+  // The four words a quad produces are stored one quad later, so that the wait for the
+  // staged fragments at the end of a quad does not also wait for a store just issued.
+  uint4 pend = make_uint4(0, 0, 0, 0);
+  const int64_t mykey = cb * kBlockKeys + lane;
+  const bool store_on = wave_on && mykey >= first && mykey < last;
+  auto store_quad = [&](int q) {
+    if (!store_on) return;
+    const int x0 = q * 4;
+    if (x0 + 4 <= NW) {
+      *reinterpret_cast<uint4*>(blk_codes + q * 256 + lane * 4) = pend;
+    } else {
+      const int rem = NW - x0;                           // 1..3 words in the last group
+      const uint32_t w4[4] = {pend.x, pend.y, pend.z, pend.w};
+      for (int i = 0; i < rem; ++i) blk_codes[q * 256 + lane * rem + i] = w4[i];
+    }
+  };
+  // One quad: 4 MFMA tiles (2 pairs = 4 code words) against the 64 keys of this wavefront.
+  auto do_quad = [&](int q, const uint4* sCur, uint4* sNext) {
     const int cur = q & 1;
-    // The next quad's fragments travel global -> registers -> LDS in two halves, each
-    // requested before and written after the math of one tile pair, so only 16 registers
-    // are tied up while the loads are in flight.
-    uint4 st[4];
-    float stt = -INFINITY;
     const bool more = q + 1 < nquads;
-    auto request = [&](int half) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int idx = (q + 1) * 2048 + (half * 4 + i) * 256 + tid;
-        st[i] = idx < a.ntiles * 512 ? gA[idx] : make_uint4(0, 0, 0, 0);
-      }
-    };
-    auto deposit = [&](int half) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) sA[cur ^ 1][(half * 4 + i) * 256 + tid] = st[i];
-    };
-    if (more) {
-      request(0);
-      if (tid < 128) stt = (q + 1) * 128 + tid < a.ntiles * 32 ? gThr[(q + 1) * 128 + tid] : -INFINITY;
+    float stt = -INFINITY;
+    if (q > 0) store_quad(q - 1);
+    if (more) {                                          // next quad travels while this one is used
+      stage_quad(gA + (int64_t)(q + 1) * 2048, sNext, tid, wave);
+      if (tid < 128) stt = gThr[(q + 1) * 128 + tid];
     }
 
     if (wave_on) {
       uint32_t wd[2][2];                                 // [pair][key tile] inverted bits, MSB first
+      uint32_t fl[2][2];                                 // same bit positions: |acc| <= bound
 #pragma unroll
       for (int pair = 0; pair < 2; ++pair) {
         wd[pair][0] = 0; wd[pair][1] = 0;
-        uint32_t fl[2] = {0u, 0u};                       // same bit positions: |acc| <= bound
+        fl[pair][0] = 0; fl[pair][1] = 0;
 #pragma unroll
         for (int tau = 0; tau < 2; ++tau) {
           const int tile = pair * 2 + tau;
@@ -308,7 +319,7 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
           f32x16 acc0 = c, acc1 = c;
 #pragma unroll
           for (int s = 0; s < 8; ++s) {
-            const bf16x8 af = __builtin_bit_cast(bf16x8, sA[cur][(tile * 8 + s) * 64 + lane]);
+            const bf16x8 af = __builtin_bit_cast(bf16x8, sCur[(tile * 8 + s) * 64 + lane]);
             acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, B[0][s], acc0, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, B[1][s], acc1, 0, 0, 0);
           }
@@ -319,22 +330,33 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
             // threshold, never -0.  For the flag x = |acc| - bound', negative iff |acc| <= bound.
             wd[pair][0] = __builtin_amdgcn_alignbit(wd[pair][0], __float_as_uint(acc0[r]), 31);
             wd[pair][1] = __builtin_amdgcn_alignbit(wd[pair][1], __float_as_uint(acc1[r]), 31);
-            fl[0] = __builtin_amdgcn_alignbit(fl[0], __float_as_uint(fabsf(acc0[r]) - bnd[0]), 31);
-            fl[1] = __builtin_amdgcn_alignbit(fl[1], __float_as_uint(fabsf(acc1[r]) - bnd[1]), 31);
+            fl[pair][0] = __builtin_amdgcn_alignbit(fl[pair][0], __float_as_uint(fabsf(acc0[r]) - bnd[0]), 31);
+            fl[pair][1] = __builtin_amdgcn_alignbit(fl[pair][1], __float_as_uint(fabsf(acc1[r]) - bnd[1]), 31);
           }
         }
-        if (__ballot((fl[0] | fl[1]) != 0)) {            // some projection too close to zero
-          const int x = 2 * (q * 2 + pair) + hh;
-          const int tb = 32 * (x / a.K), pb = x % a.K;
+        wd[pair][0] = ~wd[pair][0];
+        wd[pair][1] = ~wd[pair][1];
+      }
+      // lanes < 32 hold words x0 (pair 0) and x0+2 (pair 1) of keys kap / 32+kap, lanes >= 32
+      // hold x0+1 and x0+3: one half-swap per pair leaves lane l with the words of key l
+      const auto s0 = __builtin_amdgcn_permlane32_swap(wd[0][0], wd[0][1], false, false);
+      const auto s1 = __builtin_amdgcn_permlane32_swap(wd[1][0], wd[1][1], false, false);
+      pend = make_uint4(s0[0], s0[1], s1[0], s1[1]);     // stored at the start of the next quad
+      // Projections too close to zero are queued once per quad, after the staged fragments
+      // have landed (the list lives in LDS too).
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (__ballot((fl[0][0] | fl[0][1] | fl[1][0] | fl[1][1]) != 0)) {
+#pragma unroll
+        for (int pair = 0; pair < 2; ++pair) {
+          const unsigned xw = (unsigned)(2 * (q * 2 + pair) + hh) << 5;   // code word of this lane half
 #pragma unroll
           for (int bt = 0; bt < 2; ++bt) {
-            uint32_t f = fl[bt];
+            uint32_t f = fl[pair][bt];
             while (f) {
               const int beta = __ffs(f) - 1;
               f &= f - 1;
-              const int j = (tb + beta) * a.K + pb;
               const unsigned long long ent =
-                  ((unsigned long long)unit << 48) | ((unsigned long long)key[bt] << 16) | (unsigned)j;
+                  ((unsigned long long)unit << 48) | ((unsigned long long)key[bt] << 16) | (xw + (unsigned)beta);
               const unsigned pos = atomicAdd(&sCount, 1u);
               if (pos < kListCapLocal) {
                 sList[pos] = ent;
@@ -346,38 +368,23 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
             }
           }
         }
-        wd[pair][0] = ~wd[pair][0];
-        wd[pair][1] = ~wd[pair][1];
-        if (more && pair == 0) { deposit(0); request(1); }
-      }
-      // lanes < 32 hold words x0 (pair 0) and x0+2 (pair 1) of keys kap / 32+kap, lanes >= 32
-      // hold x0+1 and x0+3: one half-swap per pair leaves lane l with the words of key l
-      const auto s0 = __builtin_amdgcn_permlane32_swap(wd[0][0], wd[0][1], false, false);
-      const auto s1 = __builtin_amdgcn_permlane32_swap(wd[1][0], wd[1][1], false, false);
-      const uint32_t w4[4] = {s0[0], s0[1], s1[0], s1[1]};
-      const int64_t mykey = cb * kBlockKeys + lane;
-      if (mykey >= first && mykey < last) {
-        const int x0 = q * 4;
-        if (x0 + 4 <= NW) {
-          *reinterpret_cast<uint4*>(blk_codes + q * 256 + lane * 4) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
-        } else {
-          const int rem = NW - x0;                       // 1..3 words in the last group
-          for (int i = 0; i < rem; ++i) blk_codes[q * 256 + lane * rem + i] = w4[i];
-        }
       }
     }
 
-    if (more) {
-      if (!wave_on) { deposit(0); request(1); }          // idle wavefronts still move their share
-      deposit(1);
-      if (tid < 128) sThr[cur ^ 1][tid] = stt;
-    }
+    if (more && tid < 128) sThr[cur ^ 1][tid] = stt;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the next stage has landed in LDS
     __syncthreads();
+  };
+  for (int q = 0; q < nquads; q += 2) {
+    do_quad(q, sA0, sA1);
+    if (q + 1 < nquads) do_quad(q + 1, sA1, sA0);
   }
+  store_quad(nquads - 1);
 
   // ---- re-evaluate this workgroup's flagged pairs while its key rows are still in L2 ----
-  // The code words were stored above; the fence waits until L2 has them, the barrier makes
+  // The code words were stored above; the wait holds until L2 has them, the barrier makes
   // that true for all four wavefronts, so the atomic patches below land on top of them.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
   if (lane < kLimbs) sLimbs[wave][lane] = 0;
@@ -403,12 +410,10 @@ __global__ __launch_bounds__(256) void recheck_kernel(HashMfmaArgs a) {
 }
 
 hipError_t launch_hash_keys_mfma(const HashMfmaArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(prep_zero_kernel, dim3(1), dim3(64), 0, s, a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
   const int rows = a.ntiles * 32;
   hipLaunchKernelGGL(prep_projector_kernel, dim3((unsigned)((rows * 16 + 255) / 256)), dim3(256), 0, s, a);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(prep_threshold_kernel, dim3((unsigned)((rows + 255) / 256), (unsigned)a.units), dim3(256), 0, s, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const int64_t first_blk = a.first_key / kBlockKeys;
@@ -416,7 +421,7 @@ hipError_t launch_hash_keys_mfma(const HashMfmaArgs& a, hipStream_t s) {
   const int64_t nblk = last_blk - first_blk + 1;
   hipLaunchKernelGGL(hash_keys_mfma_kernel, dim3((unsigned)((nblk + 3) / 4), (unsigned)a.units), dim3(256), 0, s, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(recheck_kernel, dim3(2048), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(recheck_kernel, dim3(256), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -51,19 +51,20 @@ size_t ws_mean(const magicpig_params* p) {
 }
 
 // key-hashing workspace (bf16, matrix cores):
-// [A fragments | W transposed | thresholds | |mu| | scalars | flagged-element list]
-struct HashWs { size_t afrag_off, wt_off, thr_off, munorm_off, scalar_off, list_off, total; int ntiles; uint64_t list_cap; };
+// [A fragments | W transposed | thresholds | |mu| | column norms | scalars | flagged-element list]
+struct HashWs { size_t afrag_off, wt_off, thr_off, munorm_off, rownorm_off, scalar_off, list_off, total; int ntiles; uint64_t list_cap; };
 HashWs ws_hash_layout(const magicpig_params* p) {
   HashWs w{};
   const int NW = mp::code_words(p->K, p->L);
   const size_t units = (size_t)p->batch * p->n_kv_heads;
-  w.ntiles = 2 * ((NW + 1) / 2);
-  const size_t nquads = (w.ntiles + 3) / 4;
+  const size_t nquads = (NW + 3) / 4;                    // one tile pair makes two code words
+  w.ntiles = (int)(4 * nquads);                          // whole quads, padded with empty rows
   w.afrag_off = 0;
   w.wt_off = align256(nquads * 4 * 8 * 64 * 16);
   w.thr_off = w.wt_off + align256((size_t)p->K * p->L * mp::kHeadDim * 2);
   w.munorm_off = w.thr_off + align256(units * w.ntiles * 32 * sizeof(float));
-  w.scalar_off = w.munorm_off + align256(units * sizeof(float));
+  w.rownorm_off = w.munorm_off + align256(units * sizeof(float));
+  w.scalar_off = w.rownorm_off + align256((size_t)w.ntiles * 32 * sizeof(float));
   w.list_off = w.scalar_off + 256;
   // room for one flagged element in 512 (a few in ten thousand are expected), at least 64K
   const uint64_t elems = (uint64_t)units * (uint64_t)p->n_cap * (uint64_t)(p->K * p->L);
@@ -250,6 +251,7 @@ int magicpig_hash_keys(const magicpig_params* p, const void* K_cache, const floa
     m.afrag = wsb + wl.afrag_off; m.wt = wsb + wl.wt_off;
     m.thr = reinterpret_cast<float*>(wsb + wl.thr_off);
     m.munorm = reinterpret_cast<float*>(wsb + wl.munorm_off);
+    m.rownorm = reinterpret_cast<float*>(wsb + wl.rownorm_off);
     m.wmax_bits = reinterpret_cast<unsigned*>(wsb + wl.scalar_off);
     m.list_count = m.wmax_bits + 1;
     m.overflow = reinterpret_cast<int*>(m.wmax_bits + 2);

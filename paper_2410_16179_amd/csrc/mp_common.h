@@ -50,7 +50,8 @@ struct HashMfmaArgs {
   void* wt;                    // projector transposed [K*L][128], bf16
   float* thr;                  // [units][ntiles][2][16] initial accumulators
   float* munorm;               // [units]
-  unsigned* wmax_bits;         // max column norm of W (float bits)
+  float* rownorm;              // [ntiles*32] norm of the projector column behind each tile row
+  unsigned* wmax_bits;         // max column norm of W (float bits), kept for the statistics
   unsigned* list_count; int* overflow; unsigned* flagged_total;
   unsigned long long* list; uint64_t list_cap;
 };

@@ -233,6 +233,20 @@ def test_overflow_of_the_recheck_list_falls_back_to_the_float64_kernel(oracle):
     assert np.all(ref == (1 << w.K) - 1)
 
 
+def test_fallback_walks_every_key_when_its_grid_is_capped(oracle):
+    # 512 all-zero keys overflow the list; the other keys are ordinary.  With more than 16384
+    # rows the float64 kernel behind the matrix-core path runs on a capped grid and loops.
+    w = wl.scaled(wl.CONFIGS["C2"], n_ctx=20000, n_q_heads=4, n_kv_heads=1)
+    data = wl.generate(w)
+    Kc = data["K"].copy()
+    Kc[:, :, 3000:3512] = 0
+    s = Session(K=w.K, L=w.L, dtype="bf16", Kc=Kc, Vc=data["V"], q=data["q"], W=data["W"])
+    s.hash_keys()                                   # no centering: the zero keys project to exactly 0
+    assert mp.hash_keys_stats(s.params, s.ws)["overflowed"]
+    ref = oracle.hash_keys(Kc[0, 0], data["W"], None, w.K, w.L)
+    np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
+
+
 def test_key_mean(oracle):
     w = wl.scaled(wl.CONFIGS["C2"], n_ctx=5003, n_q_heads=8, n_kv_heads=2, batch=2)
     data = wl.generate(w)
