@@ -234,7 +234,17 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
   bf16x8 B[2][8];
   float bnd[2];
   int64_t key[2];
-  // largest column norm of the projector
+  bool key_ok[2];
+#pragma unroll
+  for (int bt = 0; bt < 2; ++bt) {
+    key[bt] = cb * kBlockKeys + bt * 32 + kap;
+    key_ok[bt] = wave_on && key[bt] >= first && key[bt] < last;
+    const int64_t krow = key_ok[bt] ? key[bt] : first;  // any valid row for masked lanes
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+      B[bt][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(Kc + ubase + krow * a.stride_n + s * 16 + hh * 8));
+  }
+  // largest column norm of the projector (requested together with the keys)
   __shared__ float sWmax[4];
   {
     float wm = 0.f;
@@ -242,20 +252,14 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
     wm = wave_max(wm);
     if (lane == 0) sWmax[wave] = wm;
   }
-  __syncthreads();
-  const float wmax = fmaxf(fmaxf(sWmax[0], sWmax[1]), fmaxf(sWmax[2], sWmax[3]));
-  if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *a.wmax_bits = __float_as_uint(wmax);   // statistics
   const float munorm = a.munorm[unit];
+  float knorm[2];
 #pragma unroll
   for (int bt = 0; bt < 2; ++bt) {
-    key[bt] = cb * kBlockKeys + bt * 32 + kap;
-    const bool ok = wave_on && key[bt] >= first && key[bt] < last;
-    const int64_t krow = ok ? key[bt] : first;          // any valid row for masked lanes
     float ss = 0.f;
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
-      const uint4 raw = *reinterpret_cast<const uint4*>(Kc + ubase + krow * a.stride_n + s * 16 + hh * 8);
-      B[bt][s] = __builtin_bit_cast(bf16x8, raw);
+      const uint4 raw = __builtin_bit_cast(uint4, B[bt][s]);
       const uint32_t u[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -264,14 +268,19 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
       }
     }
     ss += __shfl_xor(ss, 32);                            // the other half of the row
-    // flagged iff |acc| < bnd, bnd being just above the rigorous bound (so "<=" is covered)
-    bnd[bt] = ok ? (kGamma * (sqrtf(ss) * 1.000001f + munorm) * wmax) * 1.000001f + 1e-30f : -1.f;
+    knorm[bt] = sqrtf(ss) * 1.000001f;
   }
 
   const int NW = a.NW;
   uint32_t* blk_codes = a.codes + ((int64_t)unit * a.blocks_cap + cb) * (kBlockKeys * (int64_t)NW);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
+  const float wmax = fmaxf(fmaxf(sWmax[0], sWmax[1]), fmaxf(sWmax[2], sWmax[3]));
+  if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *a.wmax_bits = __float_as_uint(wmax);   // statistics
+  // flagged iff |acc| < bnd, bnd being just above the rigorous bound (so "<=" is covered)
+#pragma unroll
+  for (int bt = 0; bt < 2; ++bt)
+    bnd[bt] = key_ok[bt] ? (kGamma * (knorm[bt] + munorm) * wmax) * 1.000001f + 1e-30f : -1.f;
 
   // The four words a quad produces are stored one quad later, so that the wait for the
   // staged fragments at the end of a quad does not also wait for a store just issued.
@@ -345,7 +354,10 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
       // Projections too close to zero are queued once per quad, after the staged fragments
       // have landed (the list lives in LDS too).
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      if (__ballot((fl[0][0] | fl[0][1] | fl[1][0] | fl[1][1]) != 0)) {
+      const int nfl = __popc(fl[0][0]) + __popc(fl[0][1]) + __popc(fl[1][0]) + __popc(fl[1][1]);
+      if (__ballot(nfl != 0)) {
+        unsigned pos = 0;
+        if (nfl) pos = atomicAdd(&sCount, (unsigned)nfl);  // one reservation per lane and quad
 #pragma unroll
         for (int pair = 0; pair < 2; ++pair) {
           const unsigned xw = (unsigned)(2 * (q * 2 + pair) + hh) << 5;   // code word of this lane half
@@ -357,7 +369,6 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
               f &= f - 1;
               const unsigned long long ent =
                   ((unsigned long long)unit << 48) | ((unsigned long long)key[bt] << 16) | (xw + (unsigned)beta);
-              const unsigned pos = atomicAdd(&sCount, 1u);
               if (pos < kListCapLocal) {
                 sList[pos] = ent;
               } else {                                   // rare: the workgroup's list is full
@@ -365,6 +376,7 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
                 if (gpos < a.list_cap) a.list[gpos] = ent;
                 else *a.overflow = 1;
               }
+              ++pos;
             }
           }
         }
