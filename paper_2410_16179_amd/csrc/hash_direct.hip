@@ -122,13 +122,14 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
   }
 }
 
-// Query coding (Algorithm 1 "Encode(q, W)"): one workgroup codes two query vectors against
-// the 32*K projector columns of one table word.  Thread = column, so the 128 loads of a
-// column are coalesced across the workgroup and all in flight at once; the two vectors are
-// wave-uniform scalar loads.  Sign bits go through LDS to be regrouped from column order
-// (table-major) into the bit-plane words of the code layout.
+// Coding of a few vectors: the queries of a decode step (Algorithm 1 "Encode(q, W)") or the
+// keys appended to the cache since the last call.  One workgroup codes two vectors against the
+// 32*K projector columns of one table word.  Thread = column, so the 128 loads of a column
+// are coalesced across the workgroup and all in flight at once; the two vectors (and the
+// centering vectors of their units) are wave-uniform scalar loads.  Sign bits go through LDS
+// to be regrouped from column order (table-major) into the bit-plane words of the code layout.
 template <bool FP32>
-__global__ __launch_bounds__(512) void hash_query_kernel(HashDirectArgs a) {
+__global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a) {
   __shared__ long long limbs[8][kLimbs];
   __shared__ unsigned char sbit[2][512];
   const int tid = threadIdx.x;
@@ -151,13 +152,21 @@ __global__ __launch_bounds__(512) void hash_query_kernel(HashDirectArgs a) {
   }
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
   __builtin_amdgcn_wave_barrier();
+  // vector r of the call is key first_key + r % n_keys of unit r / n_keys (queries: one unit)
+  int64_t unit[2], key[2], xb[2];
+#pragma unroll
+  for (int rr = 0; rr < 2; ++rr) {
+    const int64_t r = r0 + (rr < nrow ? rr : 0);
+    unit[rr] = r / a.n_keys;
+    key[rr] = a.first_key + r % a.n_keys;
+    xb[rr] = (unit[rr] / a.n_kv_heads) * a.stride_b + (unit[rr] % a.n_kv_heads) * a.stride_h + key[rr] * a.stride_n;
+  }
   // both vectors in one pass over the column, so that each projector element is converted to
   // float64 once and nothing but the four accumulators stays live; the vectors are
   // wave-uniform: read through the constant address space they arrive in SGPRs
   typedef const uint32_t __attribute__((address_space(4))) * const_u32_ptr;
-  const int64_t xb0 = r0 * a.stride_n, xb1 = (r0 + nrow - 1) * a.stride_n;
-  const const_u32_ptr xs0 = (const_u32_ptr)(reinterpret_cast<const char*>(a.X) + xb0 * (FP32 ? 4 : 2));
-  const const_u32_ptr xs1 = (const_u32_ptr)(reinterpret_cast<const char*>(a.X) + xb1 * (FP32 ? 4 : 2));
+  const const_u32_ptr xs0 = (const_u32_ptr)(reinterpret_cast<const char*>(a.X) + xb[0] * (FP32 ? 4 : 2));
+  const const_u32_ptr xs1 = (const_u32_ptr)(reinterpret_cast<const char*>(a.X) + xb[1] * (FP32 ? 4 : 2));
   double s[2] = {0.0, 0.0}, mag[2] = {0.0, 0.0};
 #pragma unroll
   for (int i = 0; i < kHeadDim; ++i) {
@@ -174,19 +183,31 @@ __global__ __launch_bounds__(512) void hash_query_kernel(HashDirectArgs a) {
     s[0] += p0; mag[0] += fabs(p0);
     s[1] += p1; mag[1] += fabs(p1);
   }
+  if (a.mu) {                                            // keys: subtract the centering term mu.w
+    const const_u32_ptr ms0 = (const_u32_ptr)(a.mu + unit[0] * kHeadDim);
+    const const_u32_ptr ms1 = (const_u32_ptr)(a.mu + unit[1] * kHeadDim);
+#pragma unroll
+    for (int i = 0; i < kHeadDim; ++i) {
+      const double wv = (double)wf[i];
+      const double p0 = (double)__uint_as_float(ms0[i]) * wv, p1 = (double)__uint_as_float(ms1[i]) * wv;
+      s[0] -= p0; mag[0] += fabs(p0);
+      s[1] -= p1; mag[1] += fabs(p1);
+    }
+  }
   for (int rr = 0; rr < nrow; ++rr) {
-    const int64_t xbase = rr ? xb1 : xb0;
     bool bit = s[rr] >= 0.0;
     const bool unsure = col_ok && mag[rr] > 0.0 && fabs(s[rr]) <= kF64Slack * mag[rr];
     uint64_t pending = __ballot(unsure);
     while (pending) {
       const int src = __ffsll((unsigned long long)pending) - 1;
       const int sj = __shfl(j, src);
+      const float* smu = a.mu ? a.mu + unit[rr] * kHeadDim : nullptr;
+      const int64_t xbase = xb[rr];
       const bool r = exact_sign_nonneg_wave(
           limbs[wave],
           [&](int d) { return load_elem<FP32>(a.X, xbase + d); },
           [&](int d) { return load_elem<FP32>(a.W, (int64_t)d * ncol + sj); },
-          [&](int) { return 0.0; }, false);
+          [&](int d) { return smu ? (double)smu[d] : 0.0; }, smu != nullptr);
       if (lane == src) bit = r;
       pending &= pending - 1;
     }
@@ -205,16 +226,24 @@ __global__ __launch_bounds__(512) void hash_query_kernel(HashDirectArgs a) {
     const bool v = on && sbit[row][beta * a.K + pb];
     const uint64_t m = __ballot(v);
     uint32_t word = (lane >> 5) ? (uint32_t)(m >> 32) : (uint32_t)m;
-    if (w == Wd - 1 && (a.L & 31)) word |= ~0u << (a.L & 31);      // padding tables never collide
-    if (on && beta == 0) a.codes[(r0 + row) * a.NW + w * a.K + pb] = word;
+    if (on && beta == 0) {
+      const int x = w * a.K + pb;
+      if (a.query_layout) {
+        if (w == Wd - 1 && (a.L & 31)) word |= ~0u << (a.L & 31);  // padding tables never collide
+        a.codes[(r0 + row) * a.NW + x] = word;
+      } else {
+        const int64_t blk = unit[row] * a.blocks_cap + key[row] / kBlockKeys;
+        a.codes[blk * (kBlockKeys * (int64_t)a.NW) + slot_in_block(a.NW, x, (int)(key[row] % kBlockKeys))] = word;
+      }
+    }
   }
 }
 
-hipError_t launch_hash_query(const HashDirectArgs& a, hipStream_t s) {
+hipError_t launch_hash_rows(const HashDirectArgs& a, hipStream_t s) {
   if (a.total_rows <= 0) return hipSuccess;
   const dim3 grid((unsigned)table_words(a.L), (unsigned)((a.total_rows + 1) / 2)), block(512);
-  if (a.is_fp32) hipLaunchKernelGGL(hash_query_kernel<true>, grid, block, 0, s, a);
-  else hipLaunchKernelGGL(hash_query_kernel<false>, grid, block, 0, s, a);
+  if (a.is_fp32) hipLaunchKernelGGL(hash_rows_kernel<true>, grid, block, 0, s, a);
+  else hipLaunchKernelGGL(hash_rows_kernel<false>, grid, block, 0, s, a);
   return hipGetLastError();
 }
 

@@ -41,6 +41,7 @@ int check_strides(int64_t sb, int64_t sh, int64_t sn) {
 }
 
 constexpr int64_t kMeanRowsPerChunk = 256;
+constexpr int64_t kFewRows = 128;   // key vectors per call up to which magicpig_hash_keys takes the few-rows kernel
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -238,6 +239,11 @@ int magicpig_hash_keys(const magicpig_params* p, const void* K_cache, const floa
   a.blocks_cap = mp::key_blocks(p->n_cap);
   a.total_rows = (int64_t)p->batch * p->n_kv_heads * n_keys;
   a.run_flag = nullptr;
+  if (a.total_rows <= kFewRows) {
+    // a few appended keys (a decode step): one latency-bound kernel instead of the prefill pipeline
+    const hipError_t e = mp::launch_hash_rows(a, stream);
+    return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
+  }
   if (p->dtype == MAGICPIG_BF16) {
     // matrix-core path; the direct kernel runs afterwards only if its list overflowed
     const HashWs wl = ws_hash_layout(p);
@@ -283,7 +289,7 @@ int magicpig_hash_query(const magicpig_params* p, const void* q, const void* W, 
   a.stride_b = 0; a.stride_h = 0; a.stride_n = mp::kHeadDim;
   a.blocks_cap = 0;
   a.run_flag = nullptr;
-  const hipError_t e = mp::launch_hash_query(a, reinterpret_cast<hipStream_t>(hip_stream));
+  const hipError_t e = mp::launch_hash_rows(a, reinterpret_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
 }
 

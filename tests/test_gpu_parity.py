@@ -185,14 +185,15 @@ def test_append_keys_with_frozen_mean(oracle):
     np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
 
 
-def test_hash_bits_follow_the_exact_sum(oracle):
+@pytest.mark.parametrize("nrows", [64, 320])     # few-vectors kernel / matrix-core and float64 kernels
+def test_hash_bits_follow_the_exact_sum(oracle, nrows):
     # projections that cancel to (almost) nothing: the bit is the sign of the exact sum
     K, L = 2, 3
     big, tiny = 2.0 ** 40, 2.0 ** -40
     W = np.zeros((128, K * L), np.float32)
     W[:4, :] = 1.0
     W[4, 1] = 1.0
-    rows = np.zeros((1, 1, 64, 128), np.float32)
+    rows = np.zeros((1, 1, nrows, 128), np.float32)
     rows[0, 0, 0, :3] = [-tiny, big, -big]
     rows[0, 0, 1, :3] = [tiny, big, -big]
     rows[0, 0, 2, :3] = [big, -big, 0]
@@ -200,7 +201,7 @@ def test_hash_bits_follow_the_exact_sum(oracle):
     rows[0, 0, 4, :3] = [1.5, -1.5, 0]
     for dtype in ("fp32", "bf16"):
         for mu in (None, np.zeros((1, 1, 128), np.float32), None):
-            s = Session(K=K, L=L, dtype=dtype, Kc=rows, Vc=rows, q=rows[:, :, 0], W=W, n_ctx=64)
+            s = Session(K=K, L=L, dtype=dtype, Kc=rows, Vc=rows, q=rows[:, :, 0], W=W, n_ctx=nrows)
             s.set_mu(mu)
             s.hash_keys()
             ref = oracle.hash_keys(rows[0, 0], W, None if mu is None else mu[0, 0], K, L)
@@ -209,9 +210,9 @@ def test_hash_bits_follow_the_exact_sum(oracle):
     mu = np.zeros((1, 1, 128), np.float32)
     mu[0, 0, 0] = big
     mu[0, 0, 1] = tiny
-    rows2 = np.zeros((1, 1, 64, 128), np.float32)
+    rows2 = np.zeros((1, 1, nrows, 128), np.float32)
     rows2[0, 0, :, 0] = big
-    s = Session(K=K, L=L, dtype="fp32", Kc=rows2, Vc=rows2, q=rows2[:, :, 0], W=W, n_ctx=64)
+    s = Session(K=K, L=L, dtype="fp32", Kc=rows2, Vc=rows2, q=rows2[:, :, 0], W=W, n_ctx=nrows)
     s.set_mu(mu)
     s.hash_keys()
     ref = oracle.hash_keys(rows2[0, 0], W, mu[0, 0], K, L)
