@@ -255,8 +255,8 @@ def main():
         def tstep(i):
             s_ = sets[i % len(sets)]
             mp.magicpig_hash_query(params, qd, Wd, qcodes, ws)
-            mp.magicpig_sampled_attention_tables(params, qd, s_["K"], s_["V"], s_["mu"], s_["tables"], qcodes,
-                                                 out, workspace=ws)
+            mp.magicpig_sampled_attention_tables(params, qd, s_["K"], s_["V"], s_["mu"], s_["tables"], w.n_ctx,
+                                                 s_["codes"], qcodes, out, workspace=ws)
         for i in range(args.warmup):
             tstep(i)
         torch.cuda.synchronize()

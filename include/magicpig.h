@@ -144,15 +144,21 @@ int magicpig_sampled_attention(const magicpig_params* params, const void* q, con
  * calls return MAGICPIG_UNSUPPORTED).  The buffer holds [batch*n_kv_heads][L][2^K + 1] uint32
  * bucket offsets followed (256-byte aligned) by [batch*n_kv_heads][L][n_cap] uint32 key indices;
  * the order of the indices inside a bucket is unspecified.  Tables are rebuilt from the packed
- * key codes; they are not extended incrementally. */
+ * key codes; they are not extended incrementally: keys appended after a build are found by
+ * scanning their packed codes (see n_indexed below) until the next build. */
 size_t magicpig_table_bytes(const magicpig_params* params);
 int magicpig_build_tables(const magicpig_params* params, const uint32_t* key_codes, void* tables,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
-/* magicpig_sampled_attention with the collision scan replaced by the table lookup; every other
- * argument, the result and the debug outputs are as there (dbg_counts is 0 for keys that share
- * no bucket with the query, which is also their true count). */
+/* magicpig_sampled_attention with the collision scan replaced by the table lookup for the keys
+ * [0, n_indexed) the tables were built over (magicpig_build_tables with n_ctx = n_indexed and
+ * the same n_cap); the keys [n_indexed, n_ctx) appended since are found by the collision scan
+ * of their packed codes.  n_indexed is n_ctx or a multiple of 64 (one code block) below it;
+ * key_codes may be NULL when no block lies behind the indexed keys.  Every other argument,
+ * the result and the debug outputs are as in magicpig_sampled_attention (dbg_counts is 0 for
+ * indexed keys that share no bucket with the query, which is also their true count). */
 int magicpig_sampled_attention_tables(const magicpig_params* params, const void* q, const void* K_cache,
                                       const void* V_cache, const float* mu, const void* tables,
+                                      int64_t n_indexed, const uint32_t* key_codes,
                                       const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
                                       int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
                                       void* workspace, size_t workspace_bytes, void* hip_stream);

@@ -74,7 +74,7 @@ def lib() -> ctypes.CDLL:
     L.magicpig_build_tables.restype = ctypes.c_int
     L.magicpig_build_tables.argtypes = [P, vp, vp, vp, sz, vp]
     L.magicpig_sampled_attention_tables.restype = ctypes.c_int
-    L.magicpig_sampled_attention_tables.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
+    L.magicpig_sampled_attention_tables.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
     L.magicpig_status_string.restype, L.magicpig_status_string.argtypes = ctypes.c_char_p, [ctypes.c_int]
     L.magicpig_last_hip_error.restype, L.magicpig_last_hip_error.argtypes = ctypes.c_char_p, []
     L.magicpig_profile_stage_events.restype = None
@@ -179,12 +179,12 @@ def magicpig_build_tables(params, key_codes, tables, workspace) -> None:
                                        workspace.numel() * workspace.element_size(), _stream()))
 
 
-def magicpig_sampled_attention_tables(params, q, K_cache, V_cache, mu, tables, q_codes, out,
-                                      dbg_counts=None, dbg_cand=None, dbg_ncand=None, workspace=None) -> None:
+def magicpig_sampled_attention_tables(params, q, K_cache, V_cache, mu, tables, n_indexed, key_codes, q_codes,
+                                      out, dbg_counts=None, dbg_cand=None, dbg_ncand=None, workspace=None) -> None:
     cap = 0 if dbg_cand is None else dbg_cand.shape[-1]
     _check(lib().magicpig_sampled_attention_tables(
         ctypes.byref(params), _ptr(q), _ptr(K_cache), _ptr(V_cache), _ptr(mu), _ptr(tables),
-        _ptr(q_codes), _ptr(out), _ptr(dbg_counts), _ptr(dbg_cand), _ptr(dbg_ncand), cap,
+        int(n_indexed), _ptr(key_codes), _ptr(q_codes), _ptr(out), _ptr(dbg_counts), _ptr(dbg_cand), _ptr(dbg_ncand), cap,
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 

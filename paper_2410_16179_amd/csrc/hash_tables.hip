@@ -160,10 +160,10 @@ __global__ __launch_bounds__(1024) void table_lookup_kernel(AttnArgs a, TableArg
   }
   __syncthreads();
 
-  // ballots: thread = 32 consecutive keys (half a block)
+  // ballots of the blocks the tables cover: thread = 32 consecutive keys (half a block)
   const int64_t nblk = key_blocks(a.n);
   const int64_t kfirst = key0 + (int64_t)tid * 32;
-  if (kfirst < nblk * kBlockKeys) {
+  if (kfirst < key_blocks(tb.n) * kBlockKeys) {
     // positions of this thread's keys that are real and outside the static set
     const int64_t lo = (a.n_sink > kfirst ? a.n_sink : kfirst) - kfirst;
     const int64_t hi_key = a.n - a.n_local < a.n ? a.n - a.n_local : a.n;
@@ -210,7 +210,7 @@ hipError_t launch_build_tables(const TableArgs& t, hipStream_t s) {
 }
 
 hipError_t launch_table_lookup(const AttnArgs& a, const TableArgs& t, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
-  const int64_t nblk = key_blocks(a.n);
+  const int64_t nblk = key_blocks(t.n);
   const dim3 grid((unsigned)((nblk + kLookupRunBlocks - 1) / kLookupRunBlocks), (unsigned)((int64_t)a.B * a.Hq));
   if (start || stop) hipExtLaunchKernelGGL(table_lookup_kernel, grid, dim3(1024), 0, s, start, stop, 0, a, t);
   else hipLaunchKernelGGL(table_lookup_kernel, grid, dim3(1024), 0, s, a, t);

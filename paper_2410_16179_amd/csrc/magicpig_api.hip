@@ -113,7 +113,7 @@ extern "C" {
 
 int run_attention_impl(const magicpig_params* p, const void* q, const void* K_cache,
                          const void* V_cache, const float* mu, const uint32_t* key_codes,
-                         const void* tables, const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
+                         const void* tables, int64_t n_indexed, const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
                          int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
                          void* workspace, size_t workspace_bytes, void* hip_stream) {
   int st = check_params(p);
@@ -123,6 +123,13 @@ int run_attention_impl(const magicpig_params* p, const void* q, const void* K_ca
   const bool has_keys = p->n_ctx > 0 && p->batch > 0;
   if (!out || !workspace || (!q && p->batch > 0)) return MAGICPIG_INVALID_ARG;
   if (has_keys && (!K_cache || !V_cache || (!key_codes && !tables) || !q_codes)) return MAGICPIG_INVALID_ARG;
+  if (tables) {
+    if (!tables_supported(p)) return MAGICPIG_UNSUPPORTED;
+    // the tables cover whole code blocks, or everything
+    if (n_indexed < 0 || n_indexed > p->n_ctx || (n_indexed != p->n_ctx && n_indexed % mp::kBlockKeys != 0))
+      return MAGICPIG_INVALID_ARG;
+    if (has_keys && !key_codes && mp::key_blocks(n_indexed) < mp::key_blocks(p->n_ctx)) return MAGICPIG_INVALID_ARG;
+  }
   if ((dbg_cand != nullptr) != (dbg_ncand != nullptr) || dbg_cand_cap < 0) return MAGICPIG_INVALID_ARG;
   if (!aligned16(q) || !aligned16(K_cache) || !aligned16(V_cache) || !aligned16(key_codes) || !aligned16(tables) ||
       !aligned16(q_codes) || !aligned16(out) || !aligned16(workspace) || (mu && !aligned16(mu)))
@@ -146,8 +153,8 @@ int run_attention_impl(const magicpig_params* p, const void* q, const void* K_ca
   a.scale = 0.08838834764831845f;   // 1/sqrt(128)
   mp::TableArgs t{};
   if (tables) {
-    if (!tables_supported(p)) return MAGICPIG_UNSUPPORTED;
     fill_table_args(p, tables, &t);
+    t.n = n_indexed;
   }
   const hipError_t e = mp::launch_sampled_attention(a, tables ? &t : nullptr, reinterpret_cast<hipStream_t>(hip_stream),
                                                     g_have_stage_events ? g_stage_events : nullptr);
@@ -299,7 +306,7 @@ int magicpig_sampled_attention(const magicpig_params* p, const void* q, const vo
                                int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
                                void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (p && p->n_ctx > 0 && p->batch > 0 && !key_codes) return MAGICPIG_INVALID_ARG;
-  return run_attention_impl(p, q, K_cache, V_cache, mu, key_codes, nullptr, q_codes, out, dbg_counts, dbg_cand,
+  return run_attention_impl(p, q, K_cache, V_cache, mu, key_codes, nullptr, 0, q_codes, out, dbg_counts, dbg_cand,
                        dbg_ncand, dbg_cand_cap, workspace, workspace_bytes, hip_stream);
 }
 
@@ -325,11 +332,12 @@ int magicpig_build_tables(const magicpig_params* p, const uint32_t* key_codes, v
 
 int magicpig_sampled_attention_tables(const magicpig_params* p, const void* q, const void* K_cache,
                                       const void* V_cache, const float* mu, const void* tables,
+                                      int64_t n_indexed, const uint32_t* key_codes,
                                       const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
                                       int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (p && p->n_ctx > 0 && p->batch > 0 && !tables) return MAGICPIG_INVALID_ARG;
-  return run_attention_impl(p, q, K_cache, V_cache, mu, nullptr, tables, q_codes, out, dbg_counts, dbg_cand,
+  return run_attention_impl(p, q, K_cache, V_cache, mu, key_codes, tables, n_indexed, q_codes, out, dbg_counts, dbg_cand,
                        dbg_ncand, dbg_cand_cap, workspace, workspace_bytes, hip_stream);
 }
 

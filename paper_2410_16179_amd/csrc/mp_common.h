@@ -71,6 +71,7 @@ struct AttnArgs {
   int is_fp32;
   int B, Hq, Hkv, K, L, Wd, NW, tau, n_sink, n_local;
   int64_t n, blocks_cap;
+  int64_t blk_begin;         // first key block the collision scan covers (blocks before it: table lookup)
   int64_t ks_b, ks_h, ks_n, vs_b, vs_h, vs_n;
   int nranges;               // partials per head: nscan runs of kRangeBlocks key blocks + static runs
   int nscan;                 // runs of kRangeBlocks key blocks per head
@@ -84,7 +85,7 @@ struct TableArgs {
   uint32_t* offsets;           // [units][L][2^K + 1]
   uint32_t* indices;           // [units][L][n_cap]
   int K, L, NW, units;
-  int64_t n, n_cap, blocks_cap;
+  int64_t n, n_cap, blocks_cap;   // n: keys [0, n) are in the tables
 };
 
 constexpr int kPartialStride = 132;   // 128 output elements, running max, running sum, pad

@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int64_t nblk = key_blocks(a.n);
   const int unit = blockIdx.y;
-  const int64_t blk0 = ((int64_t)blockIdx.x * 4 + wave) * BPW;
+  const int64_t blk0 = a.blk_begin + ((int64_t)blockIdx.x * 4 + wave) * BPW;
   if (blk0 >= nblk) return;
   const int G = a.Hq / a.Hkv;
   const int K = kGeneric ? a.K : KT;
@@ -237,7 +237,8 @@ static void launch_timed(F kernel, dim3 grid, dim3 block, hipStream_t s, hipEven
 static hipError_t launch_scan(const AttnArgs& a, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
   constexpr int kBPW = MP_SCAN_BPW;
   const dim3 block(256);
-  const dim3 grid_t((unsigned)((key_blocks(a.n) + 4 * kBPW - 1) / (4 * kBPW)), (unsigned)(a.B * a.Hkv));
+  const int64_t nscanned = key_blocks(a.n) - a.blk_begin;   // > 0
+  const dim3 grid_t((unsigned)((nscanned + 4 * kBPW - 1) / (4 * kBPW)), (unsigned)(a.B * a.Hkv));
 #define MP_TUNED(KT, WDT)                                                                  \
   if (a.K == KT && a.Wd == WDT) {                                                          \
     launch_timed(collision_scan_kernel<KT, WDT, kBPW>, grid_t, block, s, start, stop, a);  \
@@ -245,7 +246,7 @@ static hipError_t launch_scan(const AttnArgs& a, hipStream_t s, hipEvent_t start
   }
   MP_TUNED(10, 5) MP_TUNED(9, 4) MP_TUNED(10, 6) MP_TUNED(8, 3)
 #undef MP_TUNED
-  const dim3 grid((unsigned)((key_blocks(a.n) + 3) / 4), (unsigned)(a.B * a.Hkv));
+  const dim3 grid((unsigned)((nscanned + 3) / 4), (unsigned)(a.B * a.Hkv));
   launch_timed(collision_scan_kernel<0, 0, 1>, grid, block, s, start, stop, a);
   return hipGetLastError();
 }
@@ -259,10 +260,24 @@ hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, 
     return hipGetLastError();
   }
   hipError_t e;
-  // retrieval: stream every key's code, or look the query's codes up in the hash tables
-  e = tables ? launch_table_lookup(a, *tables, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr)
-             : launch_scan(a, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr);
-  if (e != hipSuccess) return e;
+  // retrieval: stream every key's code, or look the query's codes up in the hash tables and
+  // stream only the codes of the keys appended since the tables were built
+  if (tables) {
+    AttnArgs b = a;
+    b.blk_begin = key_blocks(tables->n);                 // tables->n is a.n or a multiple of the block size
+    const bool lookup = tables->n > 0, scan = b.blk_begin < key_blocks(a.n);
+    if (lookup) {
+      e = launch_table_lookup(a, *tables, s, ev ? ev[0] : nullptr, ev && !scan ? ev[1] : nullptr);
+      if (e != hipSuccess) return e;
+    }
+    if (scan) {
+      e = launch_scan(b, s, ev && !lookup ? ev[0] : nullptr, ev ? ev[1] : nullptr);
+      if (e != hipSuccess) return e;
+    }
+  } else {
+    e = launch_scan(a, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr);
+    if (e != hipSuccess) return e;
+  }
   const dim3 grid((unsigned)a.nranges, (unsigned)(a.B * a.Hkv)), block(64 * (a.Hq / a.Hkv));
   if (a.is_fp32) launch_timed(gather_estimate_kernel<true>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);
   else launch_timed(gather_estimate_kernel<false>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);

@@ -44,9 +44,9 @@ class Session:
         self.n_cap = n_cap
         self.n = n_cap if n_ctx is None else n_ctx
         self.dtype = dtype
-        self.params = mp.make_params(batch=B, n_q_heads=self.Hq, n_kv_heads=Hkv, K=K, L=L,
-                                     n_ctx=self.n, n_cap=n_cap, dtype=dtype, min_hits=min_hits,
-                                     n_sink=n_sink, n_local=n_local)
+        self._pkw = dict(batch=B, n_q_heads=self.Hq, n_kv_heads=Hkv, K=K, L=L, n_cap=n_cap, dtype=dtype,
+                         min_hits=min_hits, n_sink=n_sink, n_local=n_local)
+        self.params = mp.make_params(n_ctx=self.n, **self._pkw)
         self.Kc, self.Vc, self.q, self.W = (to_dev(x, dtype) for x in (Kc, Vc, q, W))
         self.key_codes = mp.alloc_key_codes(self.params)
         self.q_codes = mp.alloc_query_codes(self.params)
@@ -91,9 +91,12 @@ class Session:
         qw = pack_table_codes(q_codes, self.K, self.L, 1).ravel()
         self.q_codes[: qw.size].copy_(torch.from_numpy(qw.view(np.int32)))
 
-    def build_tables(self):
+    def build_tables(self, n_indexed=None):
+        """Tables over the keys [0, n_indexed) (default: all); later keys are left to the scan."""
+        self.n_indexed = self.n if n_indexed is None else n_indexed
         self.tables = mp.alloc_tables(self.params)
-        mp.magicpig_build_tables(self.params, self.key_codes, self.tables, self.ws)
+        mp.magicpig_build_tables(mp.make_params(n_ctx=self.n_indexed, **self._pkw), self.key_codes, self.tables,
+                                 self.ws)
 
     def attend(self, debug=True, cand_cap=None, tables=False):
         B, Hq, n = self.B, self.Hq, self.n
@@ -107,7 +110,8 @@ class Session:
             counts = cand = ncand = None
         if tables:
             mp.magicpig_sampled_attention_tables(self.params, self.q, self.Kc, self.Vc, self.mu, self.tables,
-                                                 self.q_codes, out, counts, cand, ncand, self.ws)
+                                                 self.n_indexed, self.key_codes, self.q_codes, out, counts, cand,
+                                                 ncand, self.ws)
         else:
             mp.magicpig_sampled_attention(self.params, self.q, self.Kc, self.Vc, self.mu, self.key_codes,
                                           self.q_codes, out, counts, cand, ncand, self.ws)

@@ -26,7 +26,7 @@ def oracle_mu(oracle, Kc, n):
 
 
 def run_case(oracle, w: wl.Workload, seed=0, alpha=0.8, use_mu=True, n_cap=None, check_codes=True,
-             oracle_codes_too=True, heads=None, centered_query=False, say=""):
+             oracle_codes_too=True, heads=None, centered_query=False, say="", indexed=()):
     print(f"[case] {say or w.name} B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} n={w.n_ctx} "
           f"K={w.K} L={w.L} tau={w.min_hits} dtype={w.dtype} seed={seed}", flush=True)
     data = wl.generate(w, seed, alpha)
@@ -88,6 +88,14 @@ def run_case(oracle, w: wl.Workload, seed=0, alpha=0.8, use_mu=True, n_cap=None,
         rt2 = s.attend(debug=False, tables=True)
         for b, h in pairs:
             np.testing.assert_array_equal(rt2["out"][b, h], rt["out"][b, h])
+        # tables over a prefix of the keys, the rest found by the scan of their codes
+        for ni in indexed:
+            s.build_tables(ni)
+            rh = s.attend(tables=True)
+            for b, h in pairs:
+                np.testing.assert_array_equal(rh["counts"][b, h], ref["counts"][b, h])
+                np.testing.assert_array_equal(rh["S"][b][h], ref["S"][b][h])
+                assert rel_err(rh["out"][b, h][None], res["out"][b, h][None]) <= 1e-5
     if oracle_codes_too and heads is None:       # scan fed with the oracle's own codes
         s.upload_codes(np.concatenate([ref["key_codes"], np.zeros((w.batch, w.n_kv_heads, Kc.shape[2] - n, w.L), np.int32)], axis=2),
                        ref["q_codes"])
@@ -183,6 +191,40 @@ def test_append_keys_with_frozen_mean(oracle):
     s.hash_keys(537, 163)
     ref = oracle.hash_keys(data["K"][0, 0], data["W"], mu[0, 0], w.K, w.L)
     np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
+
+
+def test_tables_over_a_prefix_and_scan_of_the_appended_keys(oracle):
+    # 0: nothing indexed; 64: one block; 1984: most; 2944: what is left lies inside the local window
+    w = wl.scaled(wl.CONFIGS["C2"], n_ctx=3000, n_q_heads=8, n_kv_heads=2)
+    run_case(oracle, w, oracle_codes_too=False, indexed=(0, 64, 1984, 2944))
+    w4 = wl.scaled(wl.CONFIGS["C4"], batch=2, n_ctx=1500)
+    run_case(oracle, w4, oracle_codes_too=False, indexed=(1024,))
+
+
+def test_decode_steps_append_keys_behind_the_tables(oracle):
+    # prefill 1920 keys (mean frozen there, tables built there), then 80 decode steps each
+    # hashing one new key per KV head; the last step is checked against the oracle
+    w = wl.scaled(wl.CONFIGS["C2"], n_ctx=2000, n_q_heads=8, n_kv_heads=2)
+    data = wl.generate(w)
+    n0 = 1920
+    mu = oracle_mu(oracle, data["K"], n0)
+    s = Session(K=w.K, L=w.L, dtype=w.dtype, Kc=data["K"], Vc=data["V"], q=data["q"], W=data["W"])
+    s.set_mu(mu)
+    s.hash_keys(0, n0)
+    s.build_tables(n0)
+    for i in range(n0, w.n_ctx):
+        s.hash_keys(i, 1)
+    s.hash_query()
+    ref = oracle.decode_step(data["q"], data["K"], data["V"], data["W"], w.K, w.L, mu=mu,
+                             min_hits=w.min_hits, n_sink=w.n_sink, n_local=w.n_local)
+    for b in range(w.batch):
+        for g in range(w.n_kv_heads):
+            np.testing.assert_array_equal(s.key_table_codes()[b, g], ref["key_codes"][b, g])
+    for res in (s.attend(tables=True), s.attend()):
+        for h in range(w.n_q_heads):
+            np.testing.assert_array_equal(res["counts"][0, h], ref["counts"][0, h])
+            np.testing.assert_array_equal(res["S"][0][h], ref["S"][0][h])
+            assert rel_err(res["out"][0, h][None], ref["out"][0, h][None]) <= TOL
 
 
 @pytest.mark.parametrize("nrows", [64, 320])     # few-vectors kernel / matrix-core and float64 kernels

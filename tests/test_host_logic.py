@@ -113,6 +113,21 @@ def test_argument_validation_without_a_gpu():
     assert lib.magicpig_sampled_attention(ctypes.byref(p), fake, fake, fake, None, fake, fake, fake,
                                           None, None, None, 0, fake, 16, None) == -3
     assert lib.magicpig_key_mean(ctypes.byref(p), fake, None, fake, big, None) == -1
+
+    def attend_tables(pp, n_indexed, codes=fake, tables=fake):
+        return lib.magicpig_sampled_attention_tables(ctypes.byref(pp), fake, fake, fake, None, tables, n_indexed,
+                                                     codes, fake, fake, None, None, None, 0, fake, 16, None)
+
+    n = p.n_ctx
+    assert attend_tables(p, n - n % 64 - 64) == -3               # valid arguments get as far as the workspace check
+    assert attend_tables(p, n) == -3
+    assert attend_tables(p, n, codes=None) == -3                 # nothing behind the tables: no codes needed
+    assert attend_tables(p, 0, codes=None) == -1                 # everything behind the tables: codes needed
+    assert attend_tables(p, n + 64) == -1
+    assert attend_tables(p, -64) == -1
+    assert attend_tables(p, 100) == -1                           # neither everything nor whole blocks
+    assert attend_tables(p, n, tables=None) == -1
+    assert attend_tables(params(K=13), 64) == -2                 # tables unsupported beyond K = 12
     assert mp.magicpig_workspace_bytes(params(K=0)) == 0
     assert lib.magicpig_status_string(-3) == b"workspace too small"
     assert lib.magicpig_status_string(0) == b"ok"
