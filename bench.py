@@ -126,6 +126,7 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tables", action="store_true")
+    ap.add_argument("--no-decode-loop", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path "
@@ -281,6 +282,60 @@ def main():
                        "what": "magicpig_hash_query + magicpig_sampled_attention_tables, HIP graph; "
                                "build = magicpig_build_tables per cache copy (one-time)"}
 
+    # ---- one generated token of a 32-layer model, the loop this path sits in: per layer the
+    # token's key is coded behind the frozen mean (magicpig_hash_keys, one key per KV head), the
+    # query is coded and the attention runs.  Layers cycle over the cache copies; the whole
+    # token is one HIP graph.  In the table form the tables were built `appended` keys ago, so
+    # those keys are found by the scan of their codes.
+    loop_info = None
+    if not args.no_decode_loop:
+        layers, appended, reps = 32, 2048, 10
+        n_idx = max(0, (w.n_ctx - appended) // 64 * 64)
+
+        def token(form):
+            for l in range(layers):
+                s_ = sets[l % len(sets)]
+                mp.magicpig_hash_decode_step(params, qd, s_["K"], s_["mu"], Wd, w.n_ctx - 1, 1, s_["codes"], qcodes,
+                                             ws)
+                if form == "tables":
+                    mp.magicpig_sampled_attention_tables(params, qd, s_["K"], s_["V"], s_["mu"], s_["tables"],
+                                                         n_idx, s_["codes"], qcodes, out, workspace=ws)
+                else:
+                    mp.magicpig_sampled_attention(params, qd, s_["K"], s_["V"], s_["mu"], s_["codes"], qcodes,
+                                                  out, workspace=ws)
+
+        def time_token(form):
+            token(form)
+            torch.cuda.synchronize()
+            side3 = torch.cuda.Stream()
+            side3.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side3):
+                g3 = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g3, stream=side3):
+                    token(form)
+            torch.cuda.current_stream().wait_stream(side3)
+            g3.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                g3.replay()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / reps
+
+        loop_info = {"layers": layers, "tokens_timed": reps,
+                     "scan_ms_per_token": time_token("scan"),
+                     "what": "per layer: magicpig_hash_decode_step (the token's key, 1 per KV head, and the queries) "
+                             "+ attention; 32 layers in one HIP graph"}
+        if tables_info is not None:
+            p_idx = mp.make_params(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, K=w.K, L=w.L,
+                                   n_ctx=n_idx, n_cap=w.n_ctx, dtype=w.dtype, min_hits=w.min_hits,
+                                   n_sink=w.n_sink, n_local=w.n_local)
+            for s_ in sets:
+                mp.magicpig_build_tables(p_idx, s_["codes"], s_["tables"], ws)
+            loop_info["tables_ms_per_token"] = time_token("tables")
+            loop_info["keys_appended_since_table_build"] = w.n_ctx - n_idx
+            loop_info["max_abs_diff_tables_vs_scan_output"] = float(np.abs(out.cpu().numpy() - out0).max())
+
     n_static = min(w.n_ctx, w.n_sink + w.n_local)
     scan_bytes = w.batch * w.n_kv_heads * max(w.n_ctx - n_static, 0) * w.K * w.L / 8.0
     gather_bytes = float((n_sampled + n_static).sum()) * 2 * 128 * (2 if w.dtype == "bf16" else 4)
@@ -317,6 +372,8 @@ def main():
     if tables_info is not None:
         tables_info["max_abs_diff_vs_scan_output"] = float(np.abs(out_t - out0).max())
         result["hash_tables"] = tables_info
+    if loop_info is not None:
+        result["decode_loop"] = loop_info
     if not args.no_cpu_baseline:
         cb, ref, ref_heads = cpu_baseline(w, data, args.seed)
         result["cpu_baseline"] = cb

@@ -117,6 +117,16 @@ int magicpig_hash_query(const magicpig_params* params, const void* q, const void
                         uint32_t* q_codes, void* workspace, size_t workspace_bytes,
                         void* hip_stream);
 
+/* The hashing of one decode step in a single launch (Algorithm 1: the new token's key joins the
+ * hash structure, "Encode(q, W)" codes its query): magicpig_hash_keys for the keys
+ * [first_key, first_key + n_keys) (normally the one key the step appended) together with
+ * magicpig_hash_query, same arguments, same results.  With more than 128 key vectors
+ * (batch * n_kv_heads * n_keys) it simply makes the two calls one after the other. */
+int magicpig_hash_decode_step(const magicpig_params* params, const void* q, const void* K_cache,
+                              const float* mu, const void* W, int64_t first_key, int64_t n_keys,
+                              uint32_t* key_codes, uint32_t* q_codes, void* workspace,
+                              size_t workspace_bytes, void* hip_stream);
+
 /* One decode step of sampled attention (Algorithm 1; Eq. "lsh sampling probability" and Eq.
  * "close form"): for every query head h with KV head g,
  *   count(h,i) = #{ t : code_q(h,t) == code_k(g,i,t) },

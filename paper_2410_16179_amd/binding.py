@@ -41,7 +41,7 @@ EXPORTS = (
     "magicpig_hash_keys", "magicpig_hash_query", "magicpig_sampled_attention",
     "magicpig_status_string", "magicpig_last_hip_error", "magicpig_profile_stage_events",
     "magicpig_hash_keys_stats_offset", "magicpig_table_bytes", "magicpig_build_tables",
-    "magicpig_sampled_attention_tables",
+    "magicpig_sampled_attention_tables", "magicpig_hash_decode_step",
 )
 
 _lib = None
@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
     L.magicpig_hash_keys.argtypes = [P, vp, vp, vp, i64, i64, vp, vp, sz, vp]
     L.magicpig_hash_query.restype = ctypes.c_int
     L.magicpig_hash_query.argtypes = [P, vp, vp, vp, vp, sz, vp]
+    L.magicpig_hash_decode_step.restype = ctypes.c_int
+    L.magicpig_hash_decode_step.argtypes = [P, vp, vp, vp, vp, i64, i64, vp, vp, vp, sz, vp]
     L.magicpig_sampled_attention.restype = ctypes.c_int
     L.magicpig_sampled_attention.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
     L.magicpig_build_tables.restype = ctypes.c_int
@@ -159,6 +161,12 @@ def magicpig_hash_query(params, q, W, q_codes, workspace) -> None:
     _check(lib().magicpig_hash_query(ctypes.byref(params), _ptr(q), _ptr(W), _ptr(q_codes),
                                      _ptr(workspace), workspace.numel() * workspace.element_size(),
                                      _stream()))
+
+
+def magicpig_hash_decode_step(params, q, K_cache, mu, W, first_key, n_keys, key_codes, q_codes, workspace) -> None:
+    _check(lib().magicpig_hash_decode_step(ctypes.byref(params), _ptr(q), _ptr(K_cache), _ptr(mu), _ptr(W),
+                                           first_key, n_keys, _ptr(key_codes), _ptr(q_codes), _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream()))
 
 
 def magicpig_sampled_attention(params, q, K_cache, V_cache, mu, key_codes, q_codes, out,

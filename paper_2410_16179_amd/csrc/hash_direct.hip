@@ -128,15 +128,19 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
 // are coalesced across the workgroup and all in flight at once; the two vectors (and the
 // centering vectors of their units) are wave-uniform scalar loads.  Sign bits go through LDS
 // to be regrouped from column order (table-major) into the bit-plane words of the code layout.
+// A launch takes two sets of vectors (the first `pairs0` rows of the grid code a0's, the rest
+// a1's), so that a decode step codes its queries and its new keys together.
 template <bool FP32>
-__global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a) {
+__global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashDirectArgs a1, int pairs0) {
   __shared__ long long limbs[8][kLimbs];
   __shared__ unsigned char sbit[2][512];
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   if (lane < kLimbs) limbs[wave][lane] = 0;
   const int w = blockIdx.x;
-  const int64_t r0 = (int64_t)blockIdx.y * 2;
+  const bool second = (int)blockIdx.y >= pairs0;
+  const HashDirectArgs& a = second ? a1 : a0;
+  const int64_t r0 = (int64_t)((int)blockIdx.y - (second ? pairs0 : 0)) * 2;
   const int nrow = a.total_rows - r0 >= 2 ? 2 : 1;
   const int ncol = a.K * a.L;
   const int t = 32 * w + tid / a.K, b = tid % a.K;
@@ -239,11 +243,15 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a) {
   }
 }
 
-hipError_t launch_hash_rows(const HashDirectArgs& a, hipStream_t s) {
-  if (a.total_rows <= 0) return hipSuccess;
-  const dim3 grid((unsigned)table_words(a.L), (unsigned)((a.total_rows + 1) / 2)), block(512);
-  if (a.is_fp32) hipLaunchKernelGGL(hash_rows_kernel<true>, grid, block, 0, s, a);
-  else hipLaunchKernelGGL(hash_rows_kernel<false>, grid, block, 0, s, a);
+// `b` may be null (one set of vectors); both sets share K, L, the projector and the element type.
+hipError_t launch_hash_rows(const HashDirectArgs& a, const HashDirectArgs* b, hipStream_t s) {
+  const int64_t rows0 = a.total_rows > 0 ? a.total_rows : 0, rows1 = b && b->total_rows > 0 ? b->total_rows : 0;
+  if (rows0 + rows1 <= 0) return hipSuccess;
+  const int pairs0 = (int)((rows0 + 1) / 2), pairs1 = (int)((rows1 + 1) / 2);
+  const dim3 grid((unsigned)table_words(a.L), (unsigned)(pairs0 + pairs1)), block(512);
+  const HashDirectArgs& a1 = b ? *b : a;
+  if (a.is_fp32) hipLaunchKernelGGL(hash_rows_kernel<true>, grid, block, 0, s, a, a1, pairs0);
+  else hipLaunchKernelGGL(hash_rows_kernel<false>, grid, block, 0, s, a, a1, pairs0);
   return hipGetLastError();
 }
 

@@ -107,6 +107,64 @@ void fill_table_args(const magicpig_params* p, const void* tables, mp::TableArgs
   t->n = p->n_ctx; t->n_cap = p->n_cap; t->blocks_cap = mp::key_blocks(p->n_cap);
 }
 
+int check_hash_keys_args(const magicpig_params* p, const void* K_cache, const float* mu, const void* W,
+                         int64_t first_key, int64_t n_keys, const uint32_t* key_codes, const void* workspace,
+                         size_t workspace_bytes) {
+  int st = check_params(p);
+  if (st != MAGICPIG_OK) return st;
+  if ((st = check_strides(p->k_stride_b, p->k_stride_h, p->k_stride_n)) != MAGICPIG_OK) return st;
+  if (first_key < 0 || n_keys < 0 || first_key + n_keys > p->n_cap) return MAGICPIG_INVALID_ARG;
+  if (!W || !key_codes || !workspace || (!K_cache && n_keys > 0 && p->batch > 0)) return MAGICPIG_INVALID_ARG;
+  if (!aligned16(K_cache) || !aligned16(W) || !aligned16(key_codes) || !aligned16(workspace) ||
+      (mu && !aligned16(mu)))
+    return MAGICPIG_INVALID_ARG;
+  if (workspace_bytes < magicpig_workspace_bytes(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
+  return MAGICPIG_OK;
+}
+
+int check_hash_query_args(const magicpig_params* p, const void* q, const void* W, const uint32_t* q_codes,
+                          const void* workspace, size_t workspace_bytes) {
+  const int st = check_params(p);
+  if (st != MAGICPIG_OK) return st;
+  if (!W || !q_codes || !workspace || (!q && p->batch > 0)) return MAGICPIG_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(W) || !aligned16(q_codes) || !aligned16(workspace)) return MAGICPIG_INVALID_ARG;
+  if (workspace_bytes < magicpig_workspace_bytes(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
+  return MAGICPIG_OK;
+}
+
+// keys [first_key, first_key + n_keys) of every (batch, KV head) as a set of vectors to code
+mp::HashDirectArgs key_rows(const magicpig_params* p, const void* K_cache, const float* mu, const void* W,
+                            int64_t first_key, int64_t n_keys, uint32_t* key_codes) {
+  mp::HashDirectArgs a{};
+  a.X = K_cache; a.W = W; a.mu = mu; a.codes = key_codes;
+  a.is_fp32 = p->dtype == MAGICPIG_FP32;
+  a.K = p->K; a.L = p->L; a.NW = mp::code_words(p->K, p->L);
+  a.query_layout = 0;
+  a.n_keys = n_keys > 0 ? n_keys : 1; a.first_key = first_key;
+  a.n_kv_heads = p->n_kv_heads;
+  a.stride_b = p->k_stride_b; a.stride_h = p->k_stride_h; a.stride_n = p->k_stride_n;
+  a.blocks_cap = mp::key_blocks(p->n_cap);
+  a.total_rows = (int64_t)p->batch * p->n_kv_heads * n_keys;
+  a.run_flag = nullptr;
+  return a;
+}
+
+// the query vectors of a decode step: one unit holding every query row
+mp::HashDirectArgs query_rows(const magicpig_params* p, const void* q, const void* W, uint32_t* q_codes) {
+  mp::HashDirectArgs a{};
+  a.X = q; a.W = W; a.mu = nullptr; a.codes = q_codes;
+  a.is_fp32 = p->dtype == MAGICPIG_FP32;
+  a.K = p->K; a.L = p->L; a.NW = mp::code_words(p->K, p->L);
+  a.query_layout = 1;
+  a.total_rows = (int64_t)p->batch * p->n_q_heads;
+  a.n_keys = a.total_rows > 0 ? a.total_rows : 1; a.first_key = 0;
+  a.n_kv_heads = 1;
+  a.stride_b = 0; a.stride_h = 0; a.stride_n = mp::kHeadDim;
+  a.blocks_cap = 0;
+  a.run_flag = nullptr;
+  return a;
+}
+
 }  // namespace
 
 extern "C" {
@@ -224,31 +282,14 @@ int magicpig_key_mean(const magicpig_params* p, const void* K_cache, float* mu_o
 int magicpig_hash_keys(const magicpig_params* p, const void* K_cache, const float* mu, const void* W,
                        int64_t first_key, int64_t n_keys, uint32_t* key_codes, void* workspace,
                        size_t workspace_bytes, void* hip_stream) {
-  int st = check_params(p);
+  const int st = check_hash_keys_args(p, K_cache, mu, W, first_key, n_keys, key_codes, workspace, workspace_bytes);
   if (st != MAGICPIG_OK) return st;
-  if ((st = check_strides(p->k_stride_b, p->k_stride_h, p->k_stride_n)) != MAGICPIG_OK) return st;
-  if (first_key < 0 || n_keys < 0 || first_key + n_keys > p->n_cap) return MAGICPIG_INVALID_ARG;
-  if (!W || !key_codes || !workspace || (!K_cache && n_keys > 0 && p->batch > 0)) return MAGICPIG_INVALID_ARG;
-  if (!aligned16(K_cache) || !aligned16(W) || !aligned16(key_codes) || !aligned16(workspace) ||
-      (mu && !aligned16(mu)))
-    return MAGICPIG_INVALID_ARG;
-  if (workspace_bytes < magicpig_workspace_bytes(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
   if (n_keys == 0 || p->batch == 0) return MAGICPIG_OK;
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-  mp::HashDirectArgs a{};
-  a.X = K_cache; a.W = W; a.mu = mu; a.codes = key_codes;
-  a.is_fp32 = p->dtype == MAGICPIG_FP32;
-  a.K = p->K; a.L = p->L; a.NW = mp::code_words(p->K, p->L);
-  a.query_layout = 0;
-  a.n_keys = n_keys; a.first_key = first_key;
-  a.n_kv_heads = p->n_kv_heads;
-  a.stride_b = p->k_stride_b; a.stride_h = p->k_stride_h; a.stride_n = p->k_stride_n;
-  a.blocks_cap = mp::key_blocks(p->n_cap);
-  a.total_rows = (int64_t)p->batch * p->n_kv_heads * n_keys;
-  a.run_flag = nullptr;
+  mp::HashDirectArgs a = key_rows(p, K_cache, mu, W, first_key, n_keys, key_codes);
   if (a.total_rows <= kFewRows) {
     // a few appended keys (a decode step): one latency-bound kernel instead of the prefill pipeline
-    const hipError_t e = mp::launch_hash_rows(a, stream);
+    const hipError_t e = mp::launch_hash_rows(a, nullptr, stream);
     return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
   }
   if (p->dtype == MAGICPIG_BF16) {
@@ -280,23 +321,28 @@ int magicpig_hash_keys(const magicpig_params* p, const void* K_cache, const floa
 
 int magicpig_hash_query(const magicpig_params* p, const void* q, const void* W, uint32_t* q_codes,
                         void* workspace, size_t workspace_bytes, void* hip_stream) {
-  int st = check_params(p);
+  const int st = check_hash_query_args(p, q, W, q_codes, workspace, workspace_bytes);
   if (st != MAGICPIG_OK) return st;
-  if (!W || !q_codes || !workspace || (!q && p->batch > 0)) return MAGICPIG_INVALID_ARG;
-  if (!aligned16(q) || !aligned16(W) || !aligned16(q_codes) || !aligned16(workspace)) return MAGICPIG_INVALID_ARG;
-  if (workspace_bytes < magicpig_workspace_bytes(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
-  mp::HashDirectArgs a{};
-  a.X = q; a.W = W; a.mu = nullptr; a.codes = q_codes;
-  a.is_fp32 = p->dtype == MAGICPIG_FP32;
-  a.K = p->K; a.L = p->L; a.NW = mp::code_words(p->K, p->L);
-  a.query_layout = 1;
-  a.total_rows = (int64_t)p->batch * p->n_q_heads;
-  a.n_keys = a.total_rows > 0 ? a.total_rows : 1; a.first_key = 0;   // one unit holding every query row
-  a.n_kv_heads = 1;
-  a.stride_b = 0; a.stride_h = 0; a.stride_n = mp::kHeadDim;
-  a.blocks_cap = 0;
-  a.run_flag = nullptr;
-  const hipError_t e = mp::launch_hash_rows(a, reinterpret_cast<hipStream_t>(hip_stream));
+  const mp::HashDirectArgs a = query_rows(p, q, W, q_codes);
+  const hipError_t e = mp::launch_hash_rows(a, nullptr, reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
+}
+
+int magicpig_hash_decode_step(const magicpig_params* p, const void* q, const void* K_cache, const float* mu,
+                              const void* W, int64_t first_key, int64_t n_keys, uint32_t* key_codes,
+                              uint32_t* q_codes, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int st = check_hash_query_args(p, q, W, q_codes, workspace, workspace_bytes);
+  if (st != MAGICPIG_OK) return st;
+  if ((st = check_hash_keys_args(p, K_cache, mu, W, first_key, n_keys, key_codes, workspace, workspace_bytes)) != MAGICPIG_OK)
+    return st;
+  if ((int64_t)p->batch * p->n_kv_heads * n_keys > kFewRows) {   // many keys: the two calls one after the other
+    st = magicpig_hash_keys(p, K_cache, mu, W, first_key, n_keys, key_codes, workspace, workspace_bytes, hip_stream);
+    if (st != MAGICPIG_OK) return st;
+    return magicpig_hash_query(p, q, W, q_codes, workspace, workspace_bytes, hip_stream);
+  }
+  const mp::HashDirectArgs aq = query_rows(p, q, W, q_codes);
+  const mp::HashDirectArgs ak = key_rows(p, K_cache, mu, W, first_key, n_keys, key_codes);
+  const hipError_t e = mp::launch_hash_rows(aq, &ak, reinterpret_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
 }
 

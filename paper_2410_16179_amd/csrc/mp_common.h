@@ -94,7 +94,7 @@ constexpr int kStaticPerRange = 32;   // static (sink / local) keys per gather w
 
 // host-side launchers (defined next to their kernels)
 hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s);
-hipError_t launch_hash_rows(const HashDirectArgs& a, hipStream_t s);
+hipError_t launch_hash_rows(const HashDirectArgs& a, const HashDirectArgs* b, hipStream_t s);
 hipError_t launch_hash_keys_mfma(const HashMfmaArgs& a, hipStream_t s);
 hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s);
 hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, hipStream_t s, hipEvent_t const* stage_events);

@@ -213,7 +213,13 @@ def test_decode_steps_append_keys_behind_the_tables(oracle):
     s.hash_keys(0, n0)
     s.build_tables(n0)
     for i in range(n0, w.n_ctx):
-        s.hash_keys(i, 1)
+        if i % 2:
+            s.hash_keys(i, 1)
+        else:                                            # key and queries coded by one launch
+            mp.magicpig_hash_decode_step(s.params, s.q, s.Kc, s.mu, s.W, i, 1, s.key_codes, s.q_codes, s.ws)
+    qref = np.stack([oracle.hash_query(data["q"][b], data["W"], w.K, w.L) for b in range(w.batch)])
+    np.testing.assert_array_equal(s.query_table_codes(), qref)
+    s.q_codes.zero_()
     s.hash_query()
     ref = oracle.decode_step(data["q"], data["K"], data["V"], data["W"], w.K, w.L, mu=mu,
                              min_hits=w.min_hits, n_sink=w.n_sink, n_local=w.n_local)
