@@ -72,31 +72,39 @@ __device__ inline int64_t static_key(const AttnArgs& a, int64_t j) {
 // q.(k-mu), |k-mu|^2 are reduced over the 16 lanes of a row; the inclusion probability and
 // the logit q.k/sqrt(d) - log u are evaluated once per key (sampled keys only: static keys
 // enter with u = 1); an online max/sum softmax accumulates the weighted V rows.
+// The query row and the centering vector of a wavefront's head, eight elements per lane (the
+// 16 lanes of a quarter wavefront hold a row).  Requested at the start of the kernel, so that
+// they travel together with the ballots instead of after them.
+template <bool FP32>
+struct HeadVectors {
+  Frag q;
+  float4 mu0, mu1;
+};
+template <bool FP32>
+__device__ inline void request_head_vectors(const AttnArgs& a, int unit, int64_t bh, HeadVectors<FP32>& hv) {
+  const int sl = threadIdx.x & 15;
+  frag_load<FP32>(a.q, bh * kHeadDim + sl * 8, hv.q);
+  hv.mu0 = make_float4(0.f, 0.f, 0.f, 0.f);
+  hv.mu1 = hv.mu0;
+  if (a.mu) {
+    const float4* mp4 = reinterpret_cast<const float4*>(a.mu + (int64_t)unit * kHeadDim + sl * 8);
+    hv.mu0 = mp4[0];
+    hv.mu1 = mp4[1];
+  }
+}
+
 template <bool FP32, class KeyOf>
 __device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t bh, int total, bool sampled,
-                                            KeyOf key_of, float* pp) {
+                                            const HeadVectors<FP32>& hv, KeyOf key_of, float* pp) {
   constexpr int kIters = FP32 ? 4 : 8;                    // rows per quarter-wavefront and batch
   const int lane = threadIdx.x & 63;
   const int b = unit / a.Hkv, g = unit % a.Hkv;
   const int qd = lane >> 4, sl = lane & 15;
   const int64_t kbase = (int64_t)b * a.ks_b + (int64_t)g * a.ks_h + sl * 8;
   const int64_t vbase = (int64_t)b * a.vs_b + (int64_t)g * a.vs_h + sl * 8;
-  float muf[8], qf[8], o[8];
+  float o[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { muf[e] = 0.f; o[e] = 0.f; }
-  if (a.mu) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) muf[e] = a.mu[(int64_t)unit * kHeadDim + sl * 8 + e];
-  }
-  {
-    Frag f;
-    frag_load<FP32>(a.q, bh * kHeadDim + sl * 8, f);
-    frag_to_float<FP32>(f, qf);
-  }
-  float qq = 0.f;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) qq += qf[e] * qf[e];
-  const float qnorm = sqrtf(row_sum16(qq));
+  for (int e = 0; e < 8; ++e) o[e] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
   for (int base = 0; base < total; base += 4 * kIters) {
@@ -115,6 +123,14 @@ __device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t
         frag_zero<FP32>(vf[it]);
       }
     }
+    // (first use of the query and the centering vector: after the rows have been requested)
+    const float muf[8] = {hv.mu0.x, hv.mu0.y, hv.mu0.z, hv.mu0.w, hv.mu1.x, hv.mu1.y, hv.mu1.z, hv.mu1.w};
+    float qf[8];
+    frag_to_float<FP32>(hv.q, qf);
+    float qq = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) qq += qf[e] * qf[e];
+    const float qnorm = sqrtf(row_sum16(qq));
     // lane sl == it of quarter qd keeps candidate base + 4*it + qd
     float my_dq = 0.f, my_dc = 0.f, my_nn = 0.f;
     bool my_ok = false;

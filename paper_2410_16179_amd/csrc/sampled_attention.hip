@@ -121,6 +121,8 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
   const int64_t nblk = key_blocks(a.n);
   const int64_t blk0 = (int64_t)range * kRangeBlocks;
   uint16_t* list = lists[wave];
+  HeadVectors<FP32> hv;
+  request_head_vectors<FP32>(a, unit, bh, hv);
 
   // Ranges below nscan cover 16 key blocks of sampled keys; the ranges after them cover the
   // static set T (sink + local window), kStaticPerRange keys each, taken exactly (u = 1).
@@ -154,10 +156,10 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
   }
   float* pp = a.partial + (bh * a.nranges + range) * kPartialStride;
   if (!is_static) {
-    gather_estimate_wave<FP32>(a, unit, bh, total, true,
+    gather_estimate_wave<FP32>(a, unit, bh, total, true, hv,
                                [&](int c) { return blk0 * kBlockKeys + (int64_t)list[c]; }, pp);
   } else {
-    gather_estimate_wave<FP32>(a, unit, bh, total, false,
+    gather_estimate_wave<FP32>(a, unit, bh, total, false, hv,
                                [&](int c) { return static_key(a, static_first + c); }, pp);
   }
 }

@@ -128,6 +128,12 @@ def test_c5_shape_group_of_eight(oracle):
     run_case(oracle, wl.scaled(wl.CONFIGS["C5"], batch=2, n_ctx=2500))
 
 
+def test_full_batches_many_query_vectors(oracle):
+    # 512 query vectors per step: the few-vectors kernel walks several pairs per workgroup
+    run_case(oracle, wl.scaled(wl.CONFIGS["C4"], n_ctx=200), oracle_codes_too=False)
+    run_case(oracle, wl.scaled(wl.CONFIGS["C5"], n_ctx=150), oracle_codes_too=False)
+
+
 @pytest.mark.parametrize("K,L,Hq,Hkv,dtype", [(7, 65, 4, 2, "bf16"), (3, 33, 2, 2, "fp32"),
                                               (16, 40, 8, 1, "bf16"), (1, 1, 1, 1, "fp32"),
                                               (5, 512, 2, 1, "bf16")])
