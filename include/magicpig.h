@@ -66,9 +66,15 @@ typedef struct magicpig_params {
 } magicpig_params;
 
 /* ---- packed code layout (part of the contract: the caller stores codes between calls) ----
- * A key's code is NW = K * ceil(L/32) 32-bit words.  Word x = w*K + b holds, in bit beta,
- * the sign bit b (SimHash, Sec. 2.2: 1 iff the projection is >= 0) of table t = 32*w + beta;
- * bits of tables t >= L are 0 in key codes and 1 in query codes, so they never collide.
+ * Codes are bit planes over groups of 32 tables: plane word w*K + b holds, in bit beta, the
+ * sign bit b (SimHash, Sec. 2.2: 1 iff the projection is >= 0) of table t = 32*w + beta.
+ * A query's code is its NQ = K * ceil(L/32) plane words, [batch, n_q_heads, NQ] row-major,
+ * with the bits of tables t >= L set to 1.
+ * A key's code is NW words: the K*(ceil(L/32) - 1) plane words of the complete table groups
+ * as they are, then the last group (Lt = L - 32*(ceil(L/32) - 1) tables) as one bit string:
+ * bit b*Lt + beta of the string, counted from bit 0 of word K*(ceil(L/32) - 1), is bit b of
+ * table 32*(ceil(L/32) - 1) + beta; the string ends with zeros, NW = K*(ceil(L/32) - 1) +
+ * ceil(K*Lt/32).  At (K, L) = (10, 150) that is 47 words = 188 bytes for 1500 sign bits.
  * Key codes are stored in blocks of 64 consecutive keys of one (batch, KV head):
  * word x of key i lives at u32 index
  *     ((b*n_kv_heads + g)*ceil(n_cap/64) + i/64) * 64*NW + slot(x, i%64),
@@ -76,9 +82,10 @@ typedef struct magicpig_params {
  *                = (NW/4)*256 + r*(NW%4) + x%4        otherwise,
  * i.e. each lane of a 64-wide wavefront reads its key's words as 16-byte vectors and a
  * wavefront reads a contiguous 256*NW-byte block.  magicpig_key_code_index() evaluates
- * this formula.  Query codes are [batch, n_q_heads, NW] row-major.
+ * this formula.
  */
-size_t magicpig_code_words_per_key(const magicpig_params* params);
+size_t magicpig_code_words_per_key(const magicpig_params* params);     /* NW */
+size_t magicpig_code_words_per_query(const magicpig_params* params);   /* NQ */
 size_t magicpig_key_code_bytes(const magicpig_params* params);    /* whole key-code buffer  */
 size_t magicpig_query_code_bytes(const magicpig_params* params);
 /* u32 index of word x of key i of (b, g) in the key-code buffer; (size_t)-1 if out of range */

@@ -36,7 +36,8 @@ class magicpig_params(ctypes.Structure):
 
 
 EXPORTS = (
-    "magicpig_code_words_per_key", "magicpig_key_code_bytes", "magicpig_query_code_bytes",
+    "magicpig_code_words_per_key", "magicpig_code_words_per_query", "magicpig_key_code_bytes",
+    "magicpig_query_code_bytes",
     "magicpig_key_code_index", "magicpig_workspace_bytes", "magicpig_key_mean",
     "magicpig_hash_keys", "magicpig_hash_query", "magicpig_sampled_attention",
     "magicpig_status_string", "magicpig_last_hip_error", "magicpig_profile_stage_events",
@@ -57,7 +58,7 @@ def lib() -> ctypes.CDLL:
     L = ctypes.CDLL(LIB_PATH)
     P = ctypes.POINTER(magicpig_params)
     vp, sz, i32, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int64
-    for name in ("magicpig_code_words_per_key", "magicpig_key_code_bytes",
+    for name in ("magicpig_code_words_per_key", "magicpig_code_words_per_query", "magicpig_key_code_bytes",
                  "magicpig_query_code_bytes", "magicpig_workspace_bytes",
                  "magicpig_hash_keys_stats_offset", "magicpig_table_bytes"):
         getattr(L, name).restype, getattr(L, name).argtypes = sz, [P]
@@ -116,6 +117,10 @@ def make_params(*, batch, n_q_heads, n_kv_heads, K, L, n_ctx, dtype, n_cap=None,
 
 def magicpig_code_words_per_key(params) -> int:
     return lib().magicpig_code_words_per_key(ctypes.byref(params))
+
+
+def magicpig_code_words_per_query(params) -> int:
+    return lib().magicpig_code_words_per_query(ctypes.byref(params))
 
 
 def magicpig_key_code_bytes(params) -> int:
@@ -240,9 +245,47 @@ def key_code_gather_index(params) -> np.ndarray:
     return idx.reshape(params.batch, params.n_kv_heads, n_cap, NW)
 
 
+def key_plane_words(words: np.ndarray, K: int, L: int) -> np.ndarray:
+    """[..., NW] words of key codes -> [..., K*ceil(L/32)] plane words: the last table group,
+    stored as one bit string of K planes, is spread out again (tables >= L read 0)."""
+    words = np.asarray(words).astype(np.uint32)
+    Wd = (L + 31) // 32
+    Lt, xs = L - 32 * (Wd - 1), K * (Wd - 1)
+    out = np.zeros(words.shape[:-1] + (K * Wd,), np.uint32)
+    out[..., :xs] = words[..., :xs]
+    tail = words[..., xs:].astype(np.uint64)
+    for b in range(K):
+        pos = b * Lt
+        wi, sh = pos // 32, pos % 32
+        v = tail[..., wi] >> np.uint64(sh)
+        if sh + Lt > 32:
+            v = v | (tail[..., wi + 1] << np.uint64(32 - sh))
+        out[..., xs + b] = (v & np.uint64((1 << Lt) - 1)).astype(np.uint32)
+    return out
+
+
+def key_words_from_planes(planes: np.ndarray, K: int, L: int) -> np.ndarray:
+    """Inverse of key_plane_words: [..., K*ceil(L/32)] plane words -> [..., NW] key-code words."""
+    planes = np.asarray(planes).astype(np.uint32)
+    Wd = (L + 31) // 32
+    Lt, xs = L - 32 * (Wd - 1), K * (Wd - 1)
+    nt = (K * Lt + 31) // 32
+    out = np.zeros(planes.shape[:-1] + (xs + nt,), np.uint32)
+    out[..., :xs] = planes[..., :xs]
+    acc = np.zeros(planes.shape[:-1] + (nt + 1,), np.uint64)
+    for b in range(K):
+        pos = b * Lt
+        wi, sh = pos // 32, pos % 32
+        v = (planes[..., xs + b].astype(np.uint64) & np.uint64((1 << Lt) - 1)) << np.uint64(sh)
+        acc[..., wi] |= v & np.uint64(0xffffffff)
+        acc[..., wi + 1] |= v >> np.uint64(32)
+    out[..., xs:] = acc[..., :nt].astype(np.uint32)
+    return out
+
+
 def table_codes_from_words(words: np.ndarray, K: int, L: int) -> np.ndarray:
-    """[..., NW] packed words (word w*K+b, bit beta <-> table 32w+beta) -> [..., L] integers
-    sum_b bit_b 2^b, the canonical per-table form."""
+    """[..., K*ceil(L/32)] plane words (word w*K+b, bit beta <-> table 32w+beta) -> [..., L]
+    integers sum_b bit_b 2^b, the canonical per-table form."""
     words = np.asarray(words).astype(np.uint32)
     Wd = (L + 31) // 32
     w = words.reshape(*words.shape[:-1], Wd, K)

@@ -47,15 +47,15 @@ __device__ inline void load_code_block(const uint32_t* blkp, int lane, uint32_t 
     kw[4 * g4] = v.x; kw[4 * g4 + 1] = v.y; kw[4 * g4 + 2] = v.z; kw[4 * g4 + 3] = v.w;
   }
   if constexpr (rem == 1) {
-    kw[4 * full] = blkp[full * 256 + lane];
+    kw[4 * full] = __builtin_nontemporal_load(blkp + full * 256 + lane);
   } else if constexpr (rem == 2) {
     typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
     const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(blkp + full * 256 + lane * 2));
     kw[4 * full] = v.x; kw[4 * full + 1] = v.y;
   } else if constexpr (rem == 3) {
-    kw[4 * full] = blkp[full * 256 + lane * 3];
-    kw[4 * full + 1] = blkp[full * 256 + lane * 3 + 1];
-    kw[4 * full + 2] = blkp[full * 256 + lane * 3 + 2];
+    kw[4 * full] = __builtin_nontemporal_load(blkp + full * 256 + lane * 3);
+    kw[4 * full + 1] = __builtin_nontemporal_load(blkp + full * 256 + lane * 3 + 1);
+    kw[4 * full + 2] = __builtin_nontemporal_load(blkp + full * 256 + lane * 3 + 2);
   }
 }
 

@@ -46,9 +46,8 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
   const int ncol = a.K * a.L;
   const int Wd = table_words(a.L);
 
-  // blockIdx.y walks the code words: all words of a vector are coded by different
-  // workgroups, which keeps the few query vectors of a decode step spread over the chip.
-  for (int x = blockIdx.y; x < a.NW; x += gridDim.y) {
+  // plane word x of this lane half's vector (tables 32w .. 32w+31, bit b)
+  auto plane = [&](int x) -> uint32_t {
     const int w = x / a.K, b = x % a.K;
     const int t = 32 * w + beta;
     const bool col_ok = t < a.L;
@@ -110,13 +109,33 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
     const uint64_t m = __ballot(bit && col_ok);
     uint32_t word = half ? (uint32_t)(m >> 32) : (uint32_t)m;
     if (a.query_layout && (w == Wd - 1) && (a.L & 31)) word |= ~0u << (a.L & 31);
-    if (beta == 0 && row_ok) {
+    return word;
+  };
+  uint32_t* kdst = a.codes + (unit * a.blocks_cap + key / kBlockKeys) * (kBlockKeys * (int64_t)a.NW);
+  auto store_key_word = [&](int x, uint32_t word) {
+    if (beta == 0 && row_ok) kdst[slot_in_block(a.NW, x, (int)(key % kBlockKeys))] = word;
+  };
+  // blockIdx.y walks the items of a vector - its plane words, and for keys the densely packed
+  // last table group as one item - so that the few vectors of a small call are spread over
+  // the chip.
+  const int xs = a.query_layout ? a.NQ : tail_begin(a.K, a.L);
+  const int nitems = a.query_layout ? a.NQ : xs + 1;
+  for (int it = blockIdx.y; it < nitems; it += gridDim.y) {
+    if (it < xs) {
+      const uint32_t word = plane(it);
       if (a.query_layout) {
-        a.codes[row * a.NW + x] = word;
+        if (beta == 0 && row_ok) a.codes[row * a.NQ + it] = word;
       } else {
-        const int64_t blk = unit * a.blocks_cap + key / kBlockKeys;
-        a.codes[blk * (kBlockKeys * (int64_t)a.NW) + slot_in_block(a.NW, x, (int)(key % kBlockKeys))] = word;
+        store_key_word(it, word);
       }
+    } else {                                             // keys: the K planes of the last group, packed
+      BitString bs;
+      int xo = xs;
+      for (int b = 0; b < a.K; ++b) {
+        uint32_t full;
+        if (bs.append(plane(xs + b), tail_tables(a.L), &full)) store_key_word(xo++, full);
+      }
+      if (bs.nbits > 0) store_key_word(xo, (uint32_t)bs.acc);
     }
   }
   }
@@ -234,10 +253,30 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
       const int x = w * a.K + pb;
       if (a.query_layout) {
         if (w == Wd - 1 && (a.L & 31)) word |= ~0u << (a.L & 31);  // padding tables never collide
-        a.codes[(r0 + row) * a.NW + x] = word;
-      } else {
+        a.codes[(r0 + row) * a.NQ + x] = word;
+      } else if (w < Wd - 1) {
         const int64_t blk = unit[row] * a.blocks_cap + key[row] / kBlockKeys;
         a.codes[blk * (kBlockKeys * (int64_t)a.NW) + slot_in_block(a.NW, x, (int)(key[row] % kBlockKeys))] = word;
+      }
+    }
+  }
+  if (!a.query_layout && w == Wd - 1) {
+    // keys, last table group: the K planes are stored as one bit string of tail_tables bits
+    // each; item (row, packed word e, bit) reads the sign bit at string position 32 e + bit
+    const int Lt = tail_tables(a.L), xs = tail_begin(a.K, a.L), nt = a.NW - xs;
+    const int titems = nrow * nt * 32;
+    for (int p0 = 0; p0 < titems; p0 += 512) {
+      const int p = p0 + tid;
+      const bool on = p < titems;
+      const int row = on ? p / (nt * 32) : 0;
+      const int pos = on ? p % (nt * 32) : 0;
+      const int pb = pos / Lt, tb = pos % Lt;            // plane, table inside the group
+      const bool v = on && pb < a.K && sbit[row][tb * a.K + pb];
+      const uint64_t m = __ballot(v);
+      const uint32_t word = (lane >> 5) ? (uint32_t)(m >> 32) : (uint32_t)m;
+      if (on && (pos & 31) == 0) {
+        const int64_t blk = unit[row] * a.blocks_cap + key[row] / kBlockKeys;
+        a.codes[blk * (kBlockKeys * (int64_t)a.NW) + slot_in_block(a.NW, xs + (pos >> 5), (int)(key[row] % kBlockKeys))] = word;
       }
     }
   }
@@ -259,7 +298,7 @@ hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s) {
   if (a.total_rows <= 0) return hipSuccess;
   const int64_t groups = (a.total_rows + 7) / 8;
   // few vectors (queries): one workgroup per (8 vectors, word); many (keys): words looped
-  const unsigned ny = groups >= 4096 ? 1u : (unsigned)a.NW;
+  const unsigned ny = groups >= 4096 ? 1u : (unsigned)(a.query_layout ? a.NQ : tail_begin(a.K, a.L) + 1);
   // behind the matrix-core path the kernel normally only reads its flag and leaves: a capped
   // grid keeps that cheap, and the groups are walked in a loop if it does have to run
   const unsigned nx = (unsigned)(a.run_flag && groups > 2048 ? 2048 : groups);

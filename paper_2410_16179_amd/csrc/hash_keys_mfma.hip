@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void prep_projector_kernel(HashMfmaArgs a) {
   int x, beta;
   tile_row_to_bit(T, rho, &x, &beta);
   const int t = 32 * (x / a.K) + beta;
-  const bool real = x < a.NW && t < a.L;
+  const bool real = x < a.NQ && t < a.L;
   const int j = real ? t * a.K + x % a.K : 0;
   const int ncol = a.K * a.L;
   const uint16_t* W = reinterpret_cast<const uint16_t*>(a.W);
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void prep_threshold_kernel(HashMfmaArgs a) {
   int x, beta;
   tile_row_to_bit(T, rho, &x, &beta);
   const int t = 32 * (x / a.K) + beta;
-  const bool real = x < a.NW && t < a.L;
+  const bool real = x < a.NQ && t < a.L;
   float c = -INFINITY;                                 // pad rows: never >= 0, never flagged
   if (real) {
     const int j = t * a.K + x % a.K;
@@ -185,9 +185,11 @@ __device__ inline void recheck_pairs(const HashMfmaArgs& a, long long* limb, uin
       pending &= pending - 1;
     }
     if (on && sl == 0) {
-      const uint32_t mask = 1u << tbit;
+      int kword, kbit;
+      key_bit_position(a.K, a.L, x, tbit, &kword, &kbit);
+      const uint32_t mask = 1u << kbit;
       uint32_t* word = a.codes + (unit * a.blocks_cap + k / kBlockKeys) * (kBlockKeys * (int64_t)a.NW) +
-                       slot_in_block(a.NW, x, (int)(k % kBlockKeys));
+                       slot_in_block(a.NW, kword, (int)(k % kBlockKeys));
       if (bit) atomicOr(word, mask);
       else atomicAnd(word, ~mask);
     }
@@ -287,16 +289,33 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
   uint4 pend = make_uint4(0, 0, 0, 0);
   const int64_t mykey = cb * kBlockKeys + lane;
   const bool store_on = wave_on && mykey >= first && mykey < last;
+  // Plane words below the last table group are stored as they are (whole quads as 16 bytes);
+  // the planes of the last group go through a bit string that keeps only the real tables.
+  const int xs = tail_begin(a.K, a.L), Lt = tail_tables(a.L), NQ = a.NQ;
+  BitString tail;
+  int tail_x = xs;                                       // next key word the bit string fills
+  auto store_word = [&](int x, uint32_t wv) {
+    if (store_on) blk_codes[slot_in_block(NW, x, lane)] = wv;
+  };
   auto store_quad = [&](int q) {
-    if (!store_on) return;
     const int x0 = q * 4;
-    if (x0 + 4 <= NW) {
-      *reinterpret_cast<uint4*>(blk_codes + q * 256 + lane * 4) = pend;
-    } else {
-      const int rem = NW - x0;                           // 1..3 words in the last group
-      const uint32_t w4[4] = {pend.x, pend.y, pend.z, pend.w};
-      for (int i = 0; i < rem; ++i) blk_codes[q * 256 + lane * rem + i] = w4[i];
+    if (x0 + 4 <= xs) {
+      if (store_on) *reinterpret_cast<uint4*>(blk_codes + q * 256 + lane * 4) = pend;
+      return;
     }
+    const uint32_t w4[4] = {pend.x, pend.y, pend.z, pend.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int x = x0 + i;
+      if (x >= NQ) break;
+      if (x < xs) {
+        store_word(x, w4[i]);
+      } else {
+        uint32_t full;
+        if (tail.append(w4[i], Lt, &full)) store_word(tail_x++, full);
+      }
+    }
+    if (x0 + 4 >= NQ && tail.nbits > 0) store_word(tail_x, (uint32_t)tail.acc);   // last quad: the rest
   };
   // One quad: 4 MFMA tiles (2 pairs = 4 code words) against the 64 keys of this wavefront.
   auto do_quad = [&](int q, const uint4* sCur, uint4* sNext) {

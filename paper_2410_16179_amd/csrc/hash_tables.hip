@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) void ht_build_kernel(TableArgs a) {
     const uint32_t* blkp = ucodes + blk * (kBlockKeys * (int64_t)a.NW);
     uint32_t kw[16];
 #pragma unroll
-    for (int b = 0; b < 16; ++b) kw[b] = b < a.K ? blkp[slot_in_block(a.NW, w * a.K + b, lane)] : 0u;
+    for (int b = 0; b < 16; ++b) kw[b] = b < a.K ? load_plane_word(blkp, a.NW, a.K, a.L, w * a.K + b, lane) : 0u;
     if (key < a.n) {
       for (int bb = 0; bb < tpp; ++bb) {
         const int beta = beta0 + bb;
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(1024) void table_lookup_kernel(AttnArgs a, TableArg
 
   __shared__ uint32_t qs[256];
   for (int i = tid; i < kLookupRunKeys / 4; i += 1024) counters[i] = 0u;
-  if (tid < a.NW) qs[tid] = a.qcodes[bh * a.NW + tid];   // one round trip for the query's words
+  if (tid < a.NQ) qs[tid] = a.qcodes[bh * a.NQ + tid];   // one round trip for the query's words
   __syncthreads();
   // bucket of every table: the query's K-bit code of table t selects offsets[t][code..code+1]
   for (int t = tid; t < a.L; t += 1024) {

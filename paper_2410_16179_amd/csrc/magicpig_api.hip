@@ -56,9 +56,9 @@ size_t ws_mean(const magicpig_params* p) {
 struct HashWs { size_t afrag_off, wt_off, thr_off, munorm_off, rownorm_off, scalar_off, list_off, total; int ntiles; uint64_t list_cap; };
 HashWs ws_hash_layout(const magicpig_params* p) {
   HashWs w{};
-  const int NW = mp::code_words(p->K, p->L);
+  const int NQ = mp::plane_words(p->K, p->L);
   const size_t units = (size_t)p->batch * p->n_kv_heads;
-  const size_t nquads = (NW + 3) / 4;                    // one tile pair makes two code words
+  const size_t nquads = (NQ + 3) / 4;                    // one tile pair makes two plane words
   w.ntiles = (int)(4 * nquads);                          // whole quads, padded with empty rows
   w.afrag_off = 0;
   w.wt_off = align256(nquads * 4 * 8 * 64 * 16);
@@ -138,7 +138,7 @@ mp::HashDirectArgs key_rows(const magicpig_params* p, const void* K_cache, const
   mp::HashDirectArgs a{};
   a.X = K_cache; a.W = W; a.mu = mu; a.codes = key_codes;
   a.is_fp32 = p->dtype == MAGICPIG_FP32;
-  a.K = p->K; a.L = p->L; a.NW = mp::code_words(p->K, p->L);
+  a.K = p->K; a.L = p->L; a.NW = mp::code_words(p->K, p->L); a.NQ = mp::plane_words(p->K, p->L);
   a.query_layout = 0;
   a.n_keys = n_keys > 0 ? n_keys : 1; a.first_key = first_key;
   a.n_kv_heads = p->n_kv_heads;
@@ -154,7 +154,7 @@ mp::HashDirectArgs query_rows(const magicpig_params* p, const void* q, const voi
   mp::HashDirectArgs a{};
   a.X = q; a.W = W; a.mu = nullptr; a.codes = q_codes;
   a.is_fp32 = p->dtype == MAGICPIG_FP32;
-  a.K = p->K; a.L = p->L; a.NW = mp::code_words(p->K, p->L);
+  a.K = p->K; a.L = p->L; a.NW = mp::code_words(p->K, p->L); a.NQ = mp::plane_words(p->K, p->L);
   a.query_layout = 1;
   a.total_rows = (int64_t)p->batch * p->n_q_heads;
   a.n_keys = a.total_rows > 0 ? a.total_rows : 1; a.first_key = 0;
@@ -203,7 +203,7 @@ int run_attention_impl(const magicpig_params* p, const void* q, const void* K_ca
   a.dbg_counts = dbg_counts; a.dbg_cand = dbg_cand; a.dbg_ncand = dbg_ncand; a.dbg_cand_cap = dbg_cand_cap;
   a.is_fp32 = p->dtype == MAGICPIG_FP32;
   a.B = p->batch; a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.K = p->K; a.L = p->L;
-  a.Wd = mp::table_words(p->L); a.NW = mp::code_words(p->K, p->L);
+  a.Wd = mp::table_words(p->L); a.NW = mp::code_words(p->K, p->L); a.NQ = mp::plane_words(p->K, p->L);
   a.tau = p->min_hits; a.n_sink = p->n_sink; a.n_local = p->n_local;
   a.n = p->n_ctx; a.blocks_cap = mp::key_blocks(p->n_cap);
   a.ks_b = p->k_stride_b; a.ks_h = p->k_stride_h; a.ks_n = p->k_stride_n;
@@ -226,6 +226,11 @@ size_t magicpig_code_words_per_key(const magicpig_params* p) {
   return (size_t)mp::code_words(p->K, p->L);
 }
 
+size_t magicpig_code_words_per_query(const magicpig_params* p) {
+  if (check_params(p) != MAGICPIG_OK) return 0;
+  return (size_t)mp::plane_words(p->K, p->L);
+}
+
 size_t magicpig_key_code_bytes(const magicpig_params* p) {
   if (check_params(p) != MAGICPIG_OK) return 0;
   return (size_t)p->batch * p->n_kv_heads * (size_t)mp::key_blocks(p->n_cap) * mp::kBlockKeys *
@@ -234,7 +239,7 @@ size_t magicpig_key_code_bytes(const magicpig_params* p) {
 
 size_t magicpig_query_code_bytes(const magicpig_params* p) {
   if (check_params(p) != MAGICPIG_OK) return 0;
-  return (size_t)p->batch * p->n_q_heads * mp::code_words(p->K, p->L) * sizeof(uint32_t);
+  return (size_t)p->batch * p->n_q_heads * mp::plane_words(p->K, p->L) * sizeof(uint32_t);
 }
 
 size_t magicpig_key_code_index(const magicpig_params* p, int32_t b, int32_t g, int64_t key, int32_t word) {
@@ -298,7 +303,7 @@ int magicpig_hash_keys(const magicpig_params* p, const void* K_cache, const floa
     char* wsb = reinterpret_cast<char*>(workspace);
     mp::HashMfmaArgs m{};
     m.Kc = K_cache; m.W = W; m.mu = mu; m.codes = key_codes;
-    m.K = p->K; m.L = p->L; m.NW = a.NW; m.ntiles = wl.ntiles;
+    m.K = p->K; m.L = p->L; m.NW = a.NW; m.NQ = a.NQ; m.ntiles = wl.ntiles;
     m.units = p->batch * p->n_kv_heads; m.n_kv_heads = p->n_kv_heads;
     m.n_keys = n_keys; m.first_key = first_key; m.n_cap = p->n_cap; m.blocks_cap = a.blocks_cap;
     m.stride_b = p->k_stride_b; m.stride_h = p->k_stride_h; m.stride_n = p->k_stride_n;

@@ -12,14 +12,59 @@ constexpr int kBlockKeys = 64;   // keys per code block = lanes per wavefront
 constexpr int kNumCU = 256;      // MI355X
 
 // ---- packed code layout (documented in magicpig.h) ----
+// Plane word w*K + b holds sign bit b of tables 32w .. 32w+31.  Query codes are stored as
+// plane words.  Key codes store the plane words of the first Wd-1 table groups as they are
+// and the last group densely: its K planes, tail_tables(L) bits each, as one bit string.
 __host__ __device__ inline int table_words(int L) { return (L + 31) >> 5; }
-__host__ __device__ inline int code_words(int K, int L) { return K * table_words(L); }
+__host__ __device__ inline int plane_words(int K, int L) { return K * table_words(L); }
+__host__ __device__ inline int tail_tables(int L) { return L - 32 * (table_words(L) - 1); }      // 1..32
+__host__ __device__ inline int tail_begin(int K, int L) { return K * (table_words(L) - 1); }
+__host__ __device__ inline int code_words(int K, int L) {
+  return tail_begin(K, L) + (K * tail_tables(L) + 31) / 32;
+}
 __host__ __device__ inline int64_t key_blocks(int64_t n) { return (n + kBlockKeys - 1) / kBlockKeys; }
 __host__ __device__ inline int slot_in_block(int NW, int x, int r) {
   const int full = NW >> 2, rem = NW & 3;
   const int gq = x >> 2;
   return gq < full ? gq * 256 + r * 4 + (x & 3) : full * 256 + r * rem + (x & 3);
 }
+// Key word and bit inside it that hold bit `beta` of plane word x.
+__host__ __device__ inline void key_bit_position(int K, int L, int x, int beta, int* word, int* bit) {
+  const int xs = tail_begin(K, L);
+  if (x < xs) { *word = x; *bit = beta; return; }
+  const int pos = (x - xs) * tail_tables(L) + beta;
+  *word = xs + (pos >> 5);
+  *bit = pos & 31;
+}
+// Plane word x of key r of a code block, read from memory (bits of tables >= L may be set in
+// the last group: they belong to the next plane; callers mask or ignore them).
+__device__ inline uint32_t load_plane_word(const uint32_t* blkp, int NW, int K, int L, int x, int r) {
+  const int xs = tail_begin(K, L);
+  if (x < xs) return blkp[slot_in_block(NW, x, r)];
+  const int pos = (x - xs) * tail_tables(L);
+  const int wi = xs + (pos >> 5), sh = pos & 31;
+  const uint32_t lo = blkp[slot_in_block(NW, wi, r)];
+  if (sh + tail_tables(L) <= 32) return lo >> sh;
+  const uint32_t hi = blkp[slot_in_block(NW, wi + 1, r)];
+  return (lo >> sh) | (hi << (32 - sh));
+}
+// Appends bit fields to a string of 32-bit words (every lane of a wavefront carries its own
+// string; lengths and counts are wave-uniform).
+struct BitString {
+  uint64_t acc = 0;
+  int nbits = 0;
+  // returns true when a word was completed: it is in *out and must be stored by the caller
+  __host__ __device__ inline bool append(uint32_t field, int len, uint32_t* out) {
+    const uint32_t f = len >= 32 ? field : field & ((1u << len) - 1u);
+    acc |= (uint64_t)f << nbits;
+    nbits += len;
+    if (nbits < 32) return false;
+    *out = (uint32_t)acc;
+    acc >>= 32;
+    nbits -= 32;
+    return true;
+  }
+};
 
 // Launch description of the direct (float64 + exact fallback) SimHash kernel.
 struct HashDirectArgs {
@@ -28,8 +73,8 @@ struct HashDirectArgs {
   const float* mu;      // per (b,g) [128] or nullptr
   uint32_t* codes;
   int is_fp32;          // element type of X and W
-  int K, L, NW;
-  int query_layout;     // 1: codes[row][NW], pad bits 1;  0: blocked key layout, pad bits 0
+  int K, L, NW, NQ;     // NW: words per key code, NQ: plane words (= words per query code)
+  int query_layout;     // 1: codes[row][NQ] plane words, pad bits 1;  0: blocked key layout, pad bits 0
   // key addressing: row r in [0, units*n_keys): unit = r / n_keys, i = first_key + r % n_keys
   int64_t n_keys, first_key;
   int n_kv_heads;       // unit = b*n_kv_heads + g
@@ -42,7 +87,7 @@ struct HashDirectArgs {
 // Launch description of the matrix-core key hashing (bf16 keys).
 struct HashMfmaArgs {
   const void* Kc; const void* W; const float* mu; uint32_t* codes;
-  int K, L, NW, ntiles, units, n_kv_heads;
+  int K, L, NW, NQ, ntiles, units, n_kv_heads;
   int64_t n_keys, first_key, n_cap, blocks_cap;
   int64_t stride_b, stride_h, stride_n;
   // workspace pieces
@@ -69,7 +114,7 @@ struct AttnArgs {
   uint64_t* masks;        // [B*Hq][key blocks] ballots of sampled + static keys
   uint16_t* dbg_counts; int32_t* dbg_cand; int32_t* dbg_ncand; int64_t dbg_cand_cap;
   int is_fp32;
-  int B, Hq, Hkv, K, L, Wd, NW, tau, n_sink, n_local;
+  int B, Hq, Hkv, K, L, Wd, NW, NQ, tau, n_sink, n_local;
   int64_t n, blocks_cap;
   int64_t blk_begin;         // first key block the collision scan covers (blocks before it: table lookup)
   int64_t ks_b, ks_h, ks_n, vs_b, vs_h, vs_n;

@@ -28,10 +28,11 @@
 
 namespace mp {
 
-// KT, WDT: compile-time K and ceil(L/32) for the tuned instantiations, 0 for the generic one.
+// KT, WDT, LT: compile-time K, ceil(L/32) and tables in the last group for the tuned
+// instantiations, 0 for the generic one.
 // BPW: consecutive 64-key blocks per wavefront; all their code words are requested before the
 // first comparison, and each scalar-loaded query word serves BPW keys per lane.
-template <int KT, int WDT, int BPW>
+template <int KT, int WDT, int LT, int BPW>
 __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
   constexpr bool kGeneric = (KT == 0);
   // readfirstlane tells the compiler that the wavefront index (and everything derived from
@@ -44,36 +45,57 @@ __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
   const int G = a.Hq / a.Hkv;
   const int K = kGeneric ? a.K : KT;
   const int Wd = kGeneric ? a.Wd : WDT;
-  const int NW = K * Wd;
+  const int NQ = K * Wd;                                 // plane words of a query code
+  constexpr int kTailWords = kGeneric ? 0 : (KT * LT + 31) / 32;
+  constexpr int kNWT = kGeneric ? 1 : KT * (WDT - 1) + kTailWords;   // words of a key code
+  const int NW = kGeneric ? a.NW : kNWT;
   const int64_t head0 = (int64_t)(unit / a.Hkv) * a.Hq + (int64_t)(unit % a.Hkv) * G;
   // Query codes are wave-uniform and constant during the kernel: read through the constant
   // address space they are scalar loads into SGPRs and feed the bit operations directly.
-  const const_u32_ptr qc = (const_u32_ptr)(a.qcodes + head0 * NW);
+  const const_u32_ptr qc = (const_u32_ptr)(a.qcodes + head0 * NQ);
   const uint32_t* blkp = a.kcodes + ((int64_t)unit * a.blocks_cap + blk0) * (kBlockKeys * (int64_t)NW);
 
-  [[maybe_unused]] uint32_t kw[BPW][kGeneric ? 1 : KT * WDT];
+  [[maybe_unused]] uint32_t kw[BPW][kNWT];
+  // the planes of the last table group, taken out of their bit string once per key
+  [[maybe_unused]] uint32_t kt[BPW][kGeneric ? 1 : KT];
   if constexpr (!kGeneric) {
 #pragma unroll
-    for (int j = 0; j < BPW; ++j)
-      if (blk0 + j < nblk) load_code_block<KT * WDT>(blkp + j * (kBlockKeys * (int64_t)NW), lane, kw[j]);
+    for (int j = 0; j < BPW; ++j) {
+      if (blk0 + j < nblk) load_code_block<kNWT>(blkp + j * (kBlockKeys * (int64_t)NW), lane, kw[j]);
+#pragma unroll
+      for (int p = 0; p < KT; ++p) {
+        constexpr int xs = KT * (WDT - 1);
+        const int off = p * LT, wi = xs + off / 32, sh = off % 32;
+        if (sh == 0) kt[j][p] = kw[j][wi];
+        else if (sh + LT <= 32) kt[j][p] = kw[j][wi] >> sh;
+        else kt[j][p] = __builtin_amdgcn_alignbit(kw[j][wi + 1], kw[j][wi], sh);
+      }
+    }
   }
 
 #pragma unroll 1
   for (int h = 0; h < G; ++h) {
-    const const_u32_ptr qh = qc + h * NW;
+    const const_u32_ptr qh = qc + h * NQ;
     uint32_t cnt[BPW];
 #pragma unroll
     for (int j = 0; j < BPW; ++j) cnt[j] = 0;
     if constexpr (!kGeneric) {
 #pragma unroll
       for (int w = 0; w < WDT; ++w) {
+        const bool tail = w == WDT - 1;
         uint32_t same[BPW];
 #pragma unroll
-        for (int j = 0; j < BPW; ++j) same[j] = ~(kw[j][w * KT] ^ qh[w * KT]);
+        for (int j = 0; j < BPW; ++j) same[j] = ~((tail ? kt[j][0] : kw[j][w * KT]) ^ qh[w * KT]);
 #pragma unroll
         for (int p = 1; p < KT; ++p) {
 #pragma unroll
-          for (int j = 0; j < BPW; ++j) same[j] &= ~(kw[j][w * KT + p] ^ qh[w * KT + p]);   // one 3-input op
+          for (int j = 0; j < BPW; ++j)
+            same[j] &= ~((tail ? kt[j][p] : kw[j][w * KT + p]) ^ qh[w * KT + p]);   // one 3-input op
+        }
+        // beyond the real tables of the last group the key planes hold bits of the next plane
+        if (tail && LT < 32) {
+#pragma unroll
+          for (int j = 0; j < BPW; ++j) same[j] &= (1u << (LT & 31)) - 1u;
         }
 #pragma unroll
         for (int j = 0; j < BPW; ++j) cnt[j] += __popc(same[j]);
@@ -83,8 +105,9 @@ __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
         uint32_t same = ~0u;
         for (int p = 0; p < K; ++p) {
           const int x = w * K + p;
-          same &= ~(blkp[slot_in_block(NW, x, lane)] ^ qh[x]);
+          same &= ~(load_plane_word(blkp, NW, K, a.L, x, lane) ^ qh[x]);
         }
+        if (w == Wd - 1 && (a.L & 31)) same &= (1u << (a.L & 31)) - 1u;
         cnt[0] += __popc(same);
       }
     }
@@ -241,15 +264,16 @@ static hipError_t launch_scan(const AttnArgs& a, hipStream_t s, hipEvent_t start
   const dim3 block(256);
   const int64_t nscanned = key_blocks(a.n) - a.blk_begin;   // > 0
   const dim3 grid_t((unsigned)((nscanned + 4 * kBPW - 1) / (4 * kBPW)), (unsigned)(a.B * a.Hkv));
-#define MP_TUNED(KT, WDT)                                                                  \
-  if (a.K == KT && a.Wd == WDT) {                                                          \
-    launch_timed(collision_scan_kernel<KT, WDT, kBPW>, grid_t, block, s, start, stop, a);  \
-    return hipGetLastError();                                                              \
+#define MP_TUNED(KT, LL)                                                                            \
+  if (a.K == KT && a.L == LL) {                                                                     \
+    launch_timed(collision_scan_kernel<KT, (LL + 31) / 32, LL - 32 * ((LL + 31) / 32 - 1), kBPW>,  \
+                 grid_t, block, s, start, stop, a);                                                 \
+    return hipGetLastError();                                                                       \
   }
-  MP_TUNED(10, 5) MP_TUNED(9, 4) MP_TUNED(10, 6) MP_TUNED(8, 3)
+  MP_TUNED(10, 150) MP_TUNED(9, 120) MP_TUNED(10, 170) MP_TUNED(8, 75)
 #undef MP_TUNED
   const dim3 grid((unsigned)((nscanned + 3) / 4), (unsigned)(a.B * a.Hkv));
-  launch_timed(collision_scan_kernel<0, 0, 1>, grid, block, s, start, stop, a);
+  launch_timed(collision_scan_kernel<0, 0, 0, 1>, grid, block, s, start, stop, a);
   return hipGetLastError();
 }
 

@@ -20,7 +20,7 @@ def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
 
 
 def pack_table_codes(codes: np.ndarray, K: int, L: int, pad_bit: int) -> np.ndarray:
-    """[..., L] canonical integers -> [..., NW] packed words (inverse of table_codes_from_words)."""
+    """[..., L] canonical integers -> [..., K*ceil(L/32)] plane words (inverse of table_codes_from_words)."""
     Wd = (L + 31) // 32
     codes = np.asarray(codes).astype(np.uint32)
     full = np.zeros(codes.shape[:-1] + (Wd * 32,), np.uint32)
@@ -53,6 +53,7 @@ class Session:
         self.ws = mp.alloc_workspace(self.params)
         self.mu = None
         self.NW = mp.magicpig_code_words_per_key(self.params)
+        self.NQ = mp.magicpig_code_words_per_query(self.params)
 
     def set_mu(self, mu: np.ndarray | None):
         self.mu = None if mu is None else torch.from_numpy(np.ascontiguousarray(mu, np.float32)).cuda()
@@ -75,18 +76,19 @@ class Session:
         torch.cuda.synchronize()
         raw = self.key_codes.cpu().numpy().view(np.uint32)
         words = raw[mp.key_code_gather_index(self.params)]
-        return mp.table_codes_from_words(words, self.K, self.L)
+        return mp.table_codes_from_words(mp.key_plane_words(words, self.K, self.L), self.K, self.L)
 
     def query_table_codes(self) -> np.ndarray:
         torch.cuda.synchronize()
-        raw = self.q_codes.cpu().numpy().view(np.uint32)[: self.B * self.Hq * self.NW]
-        return mp.table_codes_from_words(raw.reshape(self.B, self.Hq, self.NW), self.K, self.L)
+        raw = self.q_codes.cpu().numpy().view(np.uint32)[: self.B * self.Hq * self.NQ]
+        return mp.table_codes_from_words(raw.reshape(self.B, self.Hq, self.NQ), self.K, self.L)
 
     def upload_codes(self, key_codes: np.ndarray, q_codes: np.ndarray):
         """Install oracle codes ([B,Hkv,n_cap,L], [B,Hq,L]) in the packed device layout."""
         idx = mp.key_code_gather_index(self.params)
         raw = np.zeros(self.key_codes.numel(), np.uint32)
-        raw[idx.ravel()] = pack_table_codes(key_codes, self.K, self.L, 0).ravel()
+        raw[idx.ravel()] = mp.key_words_from_planes(pack_table_codes(key_codes, self.K, self.L, 0),
+                                                    self.K, self.L).ravel()
         self.key_codes.copy_(torch.from_numpy(raw.view(np.int32)))
         qw = pack_table_codes(q_codes, self.K, self.L, 1).ravel()
         self.q_codes[: qw.size].copy_(torch.from_numpy(qw.view(np.int32)))

@@ -34,9 +34,15 @@ def test_struct_layout_matches_header():
 
 def test_sizes_and_paper_projector_size():
     p = params()
-    assert mp.magicpig_code_words_per_key(p) == 10 * 5
+    # 1500 sign bits: 4 complete groups of 32 tables (40 plane words) + 10 planes x 22 tables = 220 bits
+    assert mp.magicpig_code_words_per_key(p) == 40 + 7
+    assert mp.magicpig_code_words_per_query(p) == 10 * 5
     assert mp.magicpig_query_code_bytes(p) == 32 * 50 * 4
-    assert mp.magicpig_key_code_bytes(p) == 8 * 1024 * 50 * 4     # capacity rounded to 64 keys
+    assert mp.magicpig_key_code_bytes(p) == 8 * 1024 * 47 * 4     # capacity rounded to 64 keys
+    assert mp.magicpig_code_words_per_key(params(K=9, L=120)) == 27 + 7
+    assert mp.magicpig_code_words_per_key(params(K=10, L=170)) == 50 + 4
+    assert mp.magicpig_code_words_per_key(params(K=8, L=75)) == 16 + 3
+    assert mp.magicpig_code_words_per_key(params(K=6, L=64)) == 12     # whole groups: nothing to pack
     assert mp.magicpig_workspace_bytes(p) >= 256
     # Table "overhead of LSH": the (10,150) projector for d = 128 in bf16 is 384 KB
     assert 128 * p.K * p.L * 2 == 384000
@@ -57,6 +63,25 @@ def test_code_layout_is_a_bijection_inside_the_buffer(K, L, n_cap):
         assert idx[b, g, k, x] == mp.magicpig_key_code_index(p, int(b), int(g), int(k), int(x))
     assert mp.magicpig_key_code_index(p, 0, 0, n_cap, 0) == ctypes.c_size_t(-1).value
     assert mp.magicpig_key_code_index(p, 0, 0, 0, NW) == ctypes.c_size_t(-1).value
+
+
+@pytest.mark.parametrize("K,L", [(10, 150), (9, 120), (10, 170), (8, 75), (5, 70), (16, 33), (3, 64), (1, 1)])
+def test_key_words_pack_and_unpack(K, L):
+    rng = np.random.default_rng(2)
+    Wd = (L + 31) // 32
+    Lt = L - 32 * (Wd - 1)
+    planes = rng.integers(0, 2 ** 32, size=(5, 3, K * Wd), dtype=np.uint64).astype(np.uint32)
+    planes[..., K * (Wd - 1):] &= np.uint32((1 << Lt) - 1)       # tables >= L are 0 in key codes
+    words = mp.key_words_from_planes(planes, K, L)
+    assert words.shape[-1] == mp.magicpig_code_words_per_key(params(K=K, L=L))
+    np.testing.assert_array_equal(mp.key_plane_words(words, K, L), planes)
+    # bit b*Lt + beta of the tail string is bit b of table 32*(Wd-1) + beta
+    xs = K * (Wd - 1)
+    for b in range(K):
+        for beta in (0, Lt - 1):
+            pos = b * Lt + beta
+            got = (words[..., xs + pos // 32] >> np.uint32(pos % 32)) & np.uint32(1)
+            np.testing.assert_array_equal(got, (planes[..., xs + b] >> np.uint32(beta)) & np.uint32(1))
 
 
 def test_table_codes_from_words_roundtrip():
