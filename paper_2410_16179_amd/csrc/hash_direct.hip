@@ -5,6 +5,7 @@
 // projection is accumulated in float64 from exact products; results inside the float64
 // error bound are re-summed exactly (exact_dot.h), so the bits do not depend on
 // summation order.
+#include <type_traits>
 #include "mp_common.h"
 #include "exact_dot.h"
 #include "device_utils.h"
@@ -191,32 +192,34 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   const const_u32_ptr xs0 = (const_u32_ptr)(reinterpret_cast<const char*>(a.X) + xb[0] * (FP32 ? 4 : 2));
   const const_u32_ptr xs1 = (const_u32_ptr)(reinterpret_cast<const char*>(a.X) + xb[1] * (FP32 ? 4 : 2));
   double s[2] = {0.0, 0.0}, mag[2] = {0.0, 0.0};
-#pragma unroll
-  for (int i = 0; i < kHeadDim; ++i) {
-    float x0, x1;
-    if constexpr (FP32) {
-      x0 = __uint_as_float(xs0[i]);
-      x1 = __uint_as_float(xs1[i]);
-    } else {
-      x0 = __uint_as_float((i & 1) ? (xs0[i >> 1] & 0xffff0000u) : (xs0[i >> 1] << 16));
-      x1 = __uint_as_float((i & 1) ? (xs1[i >> 1] & 0xffff0000u) : (xs1[i >> 1] << 16));
-    }
-    const double wv = (double)wf[i];
-    const double p0 = (double)x0 * wv, p1 = (double)x1 * wv;
-    s[0] += p0; mag[0] += fabs(p0);
-    s[1] += p1; mag[1] += fabs(p1);
-  }
-  if (a.mu) {                                            // keys: subtract the centering term mu.w
+  // one pass per element: the projector value is converted once and serves the vector terms
+  // and (keys) the centering terms mu.w, which are subtracted
+  auto accumulate = [&](auto with_mu) {
     const const_u32_ptr ms0 = (const_u32_ptr)(a.mu + unit[0] * kHeadDim);
     const const_u32_ptr ms1 = (const_u32_ptr)(a.mu + unit[1] * kHeadDim);
 #pragma unroll
     for (int i = 0; i < kHeadDim; ++i) {
+      float x0, x1;
+      if constexpr (FP32) {
+        x0 = __uint_as_float(xs0[i]);
+        x1 = __uint_as_float(xs1[i]);
+      } else {
+        x0 = __uint_as_float((i & 1) ? (xs0[i >> 1] & 0xffff0000u) : (xs0[i >> 1] << 16));
+        x1 = __uint_as_float((i & 1) ? (xs1[i >> 1] & 0xffff0000u) : (xs1[i >> 1] << 16));
+      }
       const double wv = (double)wf[i];
-      const double p0 = (double)__uint_as_float(ms0[i]) * wv, p1 = (double)__uint_as_float(ms1[i]) * wv;
-      s[0] -= p0; mag[0] += fabs(p0);
-      s[1] -= p1; mag[1] += fabs(p1);
+      const double p0 = (double)x0 * wv, p1 = (double)x1 * wv;
+      s[0] += p0; mag[0] += fabs(p0);
+      s[1] += p1; mag[1] += fabs(p1);
+      if constexpr (decltype(with_mu)::value) {
+        const double m0 = (double)__uint_as_float(ms0[i]) * wv, m1 = (double)__uint_as_float(ms1[i]) * wv;
+        s[0] -= m0; mag[0] += fabs(m0);
+        s[1] -= m1; mag[1] += fabs(m1);
+      }
     }
-  }
+  };
+  if (a.mu) accumulate(std::true_type{});
+  else accumulate(std::false_type{});
   for (int rr = 0; rr < nrow; ++rr) {
     bool bit = s[rr] >= 0.0;
     const bool unsure = col_ok && mag[rr] > 0.0 && fabs(s[rr]) <= kF64Slack * mag[rr];
