@@ -160,8 +160,10 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   const int w = blockIdx.x;
   const bool second = (int)blockIdx.y >= pairs0;
   const HashDirectArgs& a = second ? a1 : a0;
-  const int64_t r0 = (int64_t)((int)blockIdx.y - (second ? pairs0 : 0)) * 2;
-  const int nrow = a.total_rows - r0 >= 2 ? 2 : 1;
+  // vectors with a centering term cost twice the arithmetic: they are taken one per workgroup
+  const int per_wg = a.mu ? 1 : 2;
+  const int64_t r0 = (int64_t)((int)blockIdx.y - (second ? pairs0 : 0)) * per_wg;
+  const int nrow = a.total_rows - r0 >= per_wg ? per_wg : 1;
   const int ncol = a.K * a.L;
   const int t = 32 * w + tid / a.K, b = tid % a.K;
   const bool col_ok = tid < 32 * a.K && t < a.L;
@@ -192,11 +194,10 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   const const_u32_ptr xs0 = (const_u32_ptr)(reinterpret_cast<const char*>(a.X) + xb[0] * (FP32 ? 4 : 2));
   const const_u32_ptr xs1 = (const_u32_ptr)(reinterpret_cast<const char*>(a.X) + xb[1] * (FP32 ? 4 : 2));
   double s[2] = {0.0, 0.0}, mag[2] = {0.0, 0.0};
-  // one pass per element: the projector value is converted once and serves the vector terms
-  // and (keys) the centering terms mu.w, which are subtracted
+  // one pass per element: the projector value is converted once and serves either two vectors
+  // or one vector and its centering term mu.w, which is subtracted
   auto accumulate = [&](auto with_mu) {
     const const_u32_ptr ms0 = (const_u32_ptr)(a.mu + unit[0] * kHeadDim);
-    const const_u32_ptr ms1 = (const_u32_ptr)(a.mu + unit[1] * kHeadDim);
 #pragma unroll
     for (int i = 0; i < kHeadDim; ++i) {
       float x0, x1;
@@ -208,13 +209,14 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
         x1 = __uint_as_float((i & 1) ? (xs1[i >> 1] & 0xffff0000u) : (xs1[i >> 1] << 16));
       }
       const double wv = (double)wf[i];
-      const double p0 = (double)x0 * wv, p1 = (double)x1 * wv;
+      const double p0 = (double)x0 * wv;
       s[0] += p0; mag[0] += fabs(p0);
-      s[1] += p1; mag[1] += fabs(p1);
       if constexpr (decltype(with_mu)::value) {
-        const double m0 = (double)__uint_as_float(ms0[i]) * wv, m1 = (double)__uint_as_float(ms1[i]) * wv;
+        const double m0 = (double)__uint_as_float(ms0[i]) * wv;
         s[0] -= m0; mag[0] += fabs(m0);
-        s[1] -= m1; mag[1] += fabs(m1);
+      } else {
+        const double p1 = (double)x1 * wv;
+        s[1] += p1; mag[1] += fabs(p1);
       }
     }
   };
@@ -289,7 +291,8 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
 hipError_t launch_hash_rows(const HashDirectArgs& a, const HashDirectArgs* b, hipStream_t s) {
   const int64_t rows0 = a.total_rows > 0 ? a.total_rows : 0, rows1 = b && b->total_rows > 0 ? b->total_rows : 0;
   if (rows0 + rows1 <= 0) return hipSuccess;
-  const int pairs0 = (int)((rows0 + 1) / 2), pairs1 = (int)((rows1 + 1) / 2);
+  const int pairs0 = (int)(a.mu ? rows0 : (rows0 + 1) / 2);           // workgroups of the first set
+  const int pairs1 = (int)(b && b->mu ? rows1 : (rows1 + 1) / 2);
   const dim3 grid((unsigned)table_words(a.L), (unsigned)(pairs0 + pairs1)), block(512);
   const HashDirectArgs& a1 = b ? *b : a;
   if (a.is_fp32) hipLaunchKernelGGL(hash_rows_kernel<true>, grid, block, 0, s, a, a1, pairs0);

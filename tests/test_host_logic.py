@@ -139,6 +139,17 @@ def test_argument_validation_without_a_gpu():
                                           None, None, None, 0, fake, 16, None) == -3
     assert lib.magicpig_key_mean(ctypes.byref(p), fake, None, fake, big, None) == -1
 
+    def decode_hash(pp, q=fake, first=0, count=1, kcodes=fake, qcodes=fake, wbytes=big):
+        return lib.magicpig_hash_decode_step(ctypes.byref(pp), q, fake, None, fake, first, count, kcodes,
+                                             qcodes, fake, wbytes, None)
+
+    assert decode_hash(p, first=1000, count=1) == -1               # beyond the capacity
+    assert decode_hash(p, qcodes=None) == -1
+    assert decode_hash(p, kcodes=None) == -1
+    assert decode_hash(p, q=None) == -1
+    assert decode_hash(p, wbytes=8) == -3
+    assert decode_hash(params(K=17)) == -2
+
     def attend_tables(pp, n_indexed, codes=fake, tables=fake):
         return lib.magicpig_sampled_attention_tables(ctypes.byref(pp), fake, fake, fake, None, tables, n_indexed,
                                                      codes, fake, fake, None, None, None, 0, fake, 16, None)
