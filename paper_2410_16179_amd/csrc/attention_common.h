@@ -127,30 +127,41 @@ __device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t
     const float muf[8] = {hv.mu0.x, hv.mu0.y, hv.mu0.z, hv.mu0.w, hv.mu1.x, hv.mu1.y, hv.mu1.z, hv.mu1.w};
     float qf[8];
     frag_to_float<FP32>(hv.q, qf);
-    float qq = 0.f;
+    float qq = 0.f, qm = 0.f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) qq += qf[e] * qf[e];
+    for (int e = 0; e < 8; ++e) { qq += qf[e] * qf[e]; qm += qf[e] * muf[e]; }
     const float qnorm = sqrtf(row_sum16(qq));
+    const float qmu = row_sum16(qm);                       // q.(k - mu) = q.k - q.mu
     // lane sl == it of quarter qd keeps candidate base + 4*it + qd
-    float my_dq = 0.f, my_dc = 0.f, my_nn = 0.f;
+    float my_dq = 0.f, my_nn = 0.f;
     bool my_ok = false;
 #pragma unroll
     for (int it = 0; it < kIters; ++it) {
       float kv[8];
       frag_to_float<FP32>(kf[it], kv);
-      float dq = 0.f, dc = 0.f, nn = 0.f;
+      float dq = 0.f, nn = 0.f;
+      if constexpr (FP32) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dq += qf[e] * kv[e];
+      } else {
+        // q.k straight from the stored bf16 pairs (v_dot2c_f32_bf16: two products per instruction)
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+        const uint32_t kr[4] = {kf[it].a.x, kf[it].a.y, kf[it].a.z, kf[it].a.w};
+        const uint32_t qr[4] = {hv.q.a.x, hv.q.a.y, hv.q.a.z, hv.q.a.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          dq = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kr[e]), __builtin_bit_cast(bf16x2, qr[e]), dq, false);
+      }
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const float kc = kv[e] - muf[e];
-        dq += qf[e] * kv[e];
-        dc += qf[e] * kc;
         nn += kc * kc;
       }
       dq = row_sum16(dq);
-      dc = row_sum16(dc);
       nn = row_sum16(nn);
-      if (sl == it) { my_dq = dq; my_dc = dc; my_nn = nn; my_ok = ok[it]; }
+      if (sl == it) { my_dq = dq; my_nn = nn; my_ok = ok[it]; }
     }
+    const float my_dc = my_dq - qmu;
     float logit = -INFINITY;
     if (sl < kIters && my_ok) {
       logit = my_dq * a.scale;
