@@ -246,10 +246,12 @@ def main():
         for s_ in sets:
             s_["tables"] = mp.alloc_tables(params)
         b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        bws = mp.alloc_table_build_workspace(params)          # room for the two-pass build
+        mp.magicpig_build_tables(params, sets[0]["codes"], sets[0]["tables"], bws)     # warm-up
         torch.cuda.synchronize()
         b0.record()
         for s_ in sets:
-            mp.magicpig_build_tables(params, s_["codes"], s_["tables"], ws)
+            mp.magicpig_build_tables(params, s_["codes"], s_["tables"], bws)
         b1.record()
         torch.cuda.synchronize()
 
@@ -279,6 +281,7 @@ def main():
         tables_info = {"value": heads / (t_ms * 1e-3), "unit": "query-heads/s", "ms_per_step": t_ms,
                        "build_ms": b0.elapsed_time(b1) / len(sets),
                        "table_bytes": mp.magicpig_table_bytes(params),
+                       "build_workspace_bytes": mp.magicpig_table_build_workspace_bytes(params),
                        "what": "magicpig_hash_query + magicpig_sampled_attention_tables, HIP graph; "
                                "build = magicpig_build_tables per cache copy (one-time)"}
 
@@ -331,7 +334,7 @@ def main():
                                    n_ctx=n_idx, n_cap=w.n_ctx, dtype=w.dtype, min_hits=w.min_hits,
                                    n_sink=w.n_sink, n_local=w.n_local)
             for s_ in sets:
-                mp.magicpig_build_tables(p_idx, s_["codes"], s_["tables"], ws)
+                mp.magicpig_build_tables(p_idx, s_["codes"], s_["tables"], bws)
             loop_info["tables_ms_per_token"] = time_token("tables")
             loop_info["keys_appended_since_table_build"] = w.n_ctx - n_idx
             loop_info["max_abs_diff_tables_vs_scan_output"] = float(np.abs(out.cpu().numpy() - out0).max())

@@ -164,6 +164,12 @@ int magicpig_sampled_attention(const magicpig_params* params, const void* q, con
  * key codes; they are not extended incrementally: keys appended after a build are found by
  * scanning their packed codes (see n_indexed below) until the next build. */
 size_t magicpig_table_bytes(const magicpig_params* params);
+/* magicpig_build_tables works with any workspace (NULL included).  Given one of at least
+ * magicpig_table_build_workspace_bytes(params) bytes (2 bytes per key and table plus the bucket
+ * fill levels per window of 16384 keys; 0 if tables are unsupported) it first writes every key's
+ * code per table there and then places the keys window by window, which is several times faster
+ * than scattering them in one pass.  The resulting tables hold the same buckets either way. */
+size_t magicpig_table_build_workspace_bytes(const magicpig_params* params);
 int magicpig_build_tables(const magicpig_params* params, const uint32_t* key_codes, void* tables,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 /* magicpig_sampled_attention with the collision scan replaced by the table lookup for the keys

@@ -42,7 +42,7 @@ EXPORTS = (
     "magicpig_hash_keys", "magicpig_hash_query", "magicpig_sampled_attention",
     "magicpig_status_string", "magicpig_last_hip_error", "magicpig_profile_stage_events",
     "magicpig_hash_keys_stats_offset", "magicpig_table_bytes", "magicpig_build_tables",
-    "magicpig_sampled_attention_tables", "magicpig_hash_decode_step",
+    "magicpig_sampled_attention_tables", "magicpig_hash_decode_step", "magicpig_table_build_workspace_bytes",
 )
 
 _lib = None
@@ -60,7 +60,7 @@ def lib() -> ctypes.CDLL:
     vp, sz, i32, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int64
     for name in ("magicpig_code_words_per_key", "magicpig_code_words_per_query", "magicpig_key_code_bytes",
                  "magicpig_query_code_bytes", "magicpig_workspace_bytes",
-                 "magicpig_hash_keys_stats_offset", "magicpig_table_bytes"):
+                 "magicpig_hash_keys_stats_offset", "magicpig_table_bytes", "magicpig_table_build_workspace_bytes"):
         getattr(L, name).restype, getattr(L, name).argtypes = sz, [P]
     L.magicpig_key_code_index.restype = sz
     L.magicpig_key_code_index.argtypes = [P, i32, i32, i64, i32]
@@ -187,9 +187,10 @@ def magicpig_table_bytes(params) -> int:
     return lib().magicpig_table_bytes(ctypes.byref(params))
 
 
-def magicpig_build_tables(params, key_codes, tables, workspace) -> None:
+def magicpig_build_tables(params, key_codes, tables, workspace=None) -> None:
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().magicpig_build_tables(ctypes.byref(params), _ptr(key_codes), _ptr(tables), _ptr(workspace),
-                                       workspace.numel() * workspace.element_size(), _stream()))
+                                       nbytes, _stream()))
 
 
 def magicpig_sampled_attention_tables(params, q, K_cache, V_cache, mu, tables, n_indexed, key_codes, q_codes,
@@ -224,6 +225,14 @@ def alloc_tables(params, device="cuda") -> torch.Tensor:
     if nbytes == 0:
         raise MagicpigError("hash tables are not supported for these parameters")
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def magicpig_table_build_workspace_bytes(params) -> int:
+    return lib().magicpig_table_build_workspace_bytes(ctypes.byref(params))
+
+
+def alloc_table_build_workspace(params, device="cuda") -> torch.Tensor:
+    return torch.empty(max(magicpig_table_build_workspace_bytes(params), 256), dtype=torch.uint8, device=device)
 
 
 def alloc_workspace(params, device="cuda") -> torch.Tensor:

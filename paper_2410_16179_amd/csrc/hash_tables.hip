@@ -8,6 +8,12 @@
 // scan at a small fraction of its bytes.
 //   ht_build_kernel<false>: histogram of the codes of 32 (or fewer) tables in LDS -> offsets.
 //   ht_build_kernel<true> : second pass, scatters key indices to their buckets.
+//   With a large workspace the first pass also writes every key's code per table (16 bits,
+//   table-major) and the bucket fill levels at the start of every window of 16384 keys, and
+//   ht_place_kernel replaces the second pass: one workgroup places one window of one table, so
+//   the 4-byte stores to a bucket come close together in time and combine into whole lines in
+//   L2 (the one-pass scatter keeps thousands of lines half written per workgroup and writes
+//   each store to HBM on its own).
 //   table_lookup_kernel   : one workgroup per (query head, run of 32768 keys): reads the L
 //       buckets, counts hits per key in LDS byte counters, and emits the same 64-bit ballots
 //       (count >= min_hits, key not static) that collision_scan_kernel emits, so the gather
@@ -47,7 +53,22 @@ __global__ __launch_bounds__(256) void ht_build_kernel(TableArgs a) {
 
   const int64_t nblk = key_blocks(a.n);
   const uint32_t* ucodes = a.kcodes + (int64_t)unit * a.blocks_cap * (kBlockKeys * (int64_t)a.NW);
-  for (int64_t blk = wave; blk < nblk; blk += 4) {
+  const bool windowed = !SCATTER && a.codes16 != nullptr;
+  constexpr int64_t kWinBlocks = kBuildWindow / kBlockKeys;
+  const int64_t nwin = windowed ? a.windows : 1;
+  for (int64_t win = 0; win < nwin; ++win) {
+  if (windowed) {
+    // fill levels of the buckets before this window (cumulative histogram so far)
+    __syncthreads();
+    for (int i = tid; i < tpp * nb; i += 256) {
+      const int t = 32 * w + beta0 + i / nb;
+      if (t < a.L) a.wincum[(((int64_t)unit * a.L + t) * a.windows + win) * nb + i % nb] = hist[i];
+    }
+    __syncthreads();
+  }
+  const int64_t blk_lo = windowed ? win * kWinBlocks : 0;
+  const int64_t blk_hi = windowed ? (nblk < blk_lo + kWinBlocks ? nblk : blk_lo + kWinBlocks) : nblk;
+  for (int64_t blk = blk_lo + wave; blk < blk_hi; blk += 4) {
     const int64_t key = blk * kBlockKeys + lane;
     const uint32_t* blkp = ucodes + blk * (kBlockKeys * (int64_t)a.NW);
     uint32_t kw[16];
@@ -62,8 +83,10 @@ __global__ __launch_bounds__(256) void ht_build_kernel(TableArgs a) {
         for (int b = 0; b < 16; ++b) code |= ((kw[b] >> beta) & 1u) << b;
         const uint32_t pos = atomicAdd(&hist[bb * nb + code], 1u);
         if (SCATTER) idxs[(int64_t)(32 * w + beta) * a.n_cap + pos] = (uint32_t)key;
+        if (windowed) a.codes16[((int64_t)unit * a.L + 32 * w + beta) * (a.blocks_cap * kBlockKeys) + key] = (uint16_t)code;
       }
     }
+  }
   }
   if (SCATTER) return;
   __syncthreads();
@@ -92,6 +115,85 @@ __global__ __launch_bounds__(256) void ht_build_kernel(TableArgs a) {
       }
     }
     if (lane == 63) offs[(int64_t)t * (nb + 1) + nb] = incl;
+  }
+}
+
+// Places the keys of one window into the buckets of one table.  The window is counting-sorted
+// by bucket in LDS (its bucket sizes are the differences of the fill levels the first pass
+// left), then every bucket's piece is copied to its place - offsets[c] + keys of bucket c in
+// earlier windows - by one wavefront with consecutive lanes on consecutive entries, so the
+// index array is written in whole contiguous pieces.
+__global__ __launch_bounds__(256) void ht_place_kernel(TableArgs a) {
+  extern __shared__ uint32_t lds[];
+  const int nb = 1 << a.K;
+  uint32_t* cursor = lds;                                              // [2^K] next free slot of the bucket's piece
+  uint16_t* cnt = reinterpret_cast<uint16_t*>(lds + nb);               // [2^K] keys of the bucket in this window
+  uint16_t* sorted = cnt + nb;                                         // [kBuildWindow] key offsets, bucket-major
+  __shared__ uint32_t wsum[4];
+  const int win = blockIdx.x, t = blockIdx.y, unit = blockIdx.z;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const uint32_t* offs = a.offsets + ((int64_t)unit * a.L + t) * (nb + 1);
+  const uint32_t* cum = a.wincum + (((int64_t)unit * a.L + t) * a.windows + win) * nb;
+  const bool last = win == a.windows - 1;
+  // bucket sizes of the window and their exclusive prefix sums (thread = run of consecutive buckets)
+  const int per = nb / 256 > 0 ? nb / 256 : 1;                         // nb is a power of two
+  uint32_t run = 0;
+  for (int j = 0; j < per; ++j) {
+    const int c = tid * per + j;
+    if (c < nb) {
+      const uint32_t after = last ? offs[c + 1] - offs[c] : cum[nb + c];
+      const uint32_t n_c = after - cum[c];
+      cnt[c] = (uint16_t)n_c;
+      run += n_c;
+    }
+  }
+  uint32_t incl = run;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t v = __shfl_up(incl, o);
+    if (lane >= o) incl += v;
+  }
+  if (lane == 63) wsum[wave] = incl;
+  __syncthreads();
+  uint32_t base = incl - run;
+  for (int v = 0; v < wave; ++v) base += wsum[v];
+  for (int j = 0; j < per; ++j) {
+    const int c = tid * per + j;
+    if (c < nb) {
+      cursor[c] = base;
+      base += cnt[c];
+    }
+  }
+  __syncthreads();
+  // counting sort of the window's keys
+  const uint16_t* codes = a.codes16 + ((int64_t)unit * a.L + t) * (a.blocks_cap * kBlockKeys);   // rows of whole blocks
+  const int64_t k0 = (int64_t)win * kBuildWindow;
+  const int64_t k1 = k0 + kBuildWindow < a.n ? k0 + kBuildWindow : a.n;
+  for (int64_t kb = k0 + (int64_t)tid * 8; kb < k1; kb += 256 * 8) {
+    const uint4 raw = *reinterpret_cast<const uint4*>(codes + kb);
+    const uint32_t u[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t code = (u[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+      if (kb + e < k1) sorted[atomicAdd(&cursor[code], 1u)] = (uint16_t)(kb + e - k0);
+    }
+  }
+  __syncthreads();
+  // copy out: wavefront v takes the buckets of every fourth group of 64; cursor[c] now marks
+  // the end of bucket c's piece
+  uint32_t* idxs = a.indices + ((int64_t)unit * a.L + t) * a.n_cap;
+  for (int c0 = wave * 64; c0 < nb; c0 += 256) {
+    const int c = c0 + lane;
+    uint32_t gb = 0, le = 0, n_c = 0;
+    if (c < nb) {
+      gb = offs[c] + cum[c];
+      le = cursor[c];
+      n_c = cnt[c];
+    }
+    for (int j = 0; j < 64 && c0 + j < nb; ++j) {
+      const uint32_t g = __shfl(gb, j), e = __shfl(le, j), m = __shfl(n_c, j);
+      for (uint32_t i = lane; i < m; i += 64) idxs[g + i] = (uint32_t)k0 + sorted[e - m + i];
+    }
   }
 }
 
@@ -205,7 +307,13 @@ hipError_t launch_build_tables(const TableArgs& t, hipStream_t s) {
   hipLaunchKernelGGL(ht_build_kernel<false>, grid, dim3(256), lds, s, t);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(ht_build_kernel<true>, grid, dim3(256), lds, s, t);
+  if (t.codes16 && t.n > 0) {
+    const size_t place_lds = ((size_t)6 << t.K) + (size_t)kBuildWindow * sizeof(uint16_t);   // <= 56 KB at K = 12
+    hipLaunchKernelGGL(ht_place_kernel, dim3((unsigned)t.windows, (unsigned)t.L, (unsigned)t.units), dim3(256),
+                       place_lds, s, t);
+  } else {
+    hipLaunchKernelGGL(ht_build_kernel<true>, grid, dim3(256), lds, s, t);
+  }
   return hipGetLastError();
 }
 

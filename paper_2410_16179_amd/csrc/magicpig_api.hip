@@ -97,6 +97,19 @@ bool tables_supported(const magicpig_params* p) {
   return p->K <= 12 && p->L <= 255 && (int64_t)p->batch * p->n_q_heads <= 65535;
 }
 
+// workspace of the two-pass table build: [codes per table and key | bucket fill levels per window]
+struct BuildWs { size_t codes_off, cum_off, total; int windows; };
+BuildWs ws_build_layout(const magicpig_params* p) {
+  BuildWs w{};
+  const size_t units = (size_t)p->batch * p->n_kv_heads;
+  const int64_t n = p->n_ctx > 0 ? p->n_ctx : 1;
+  w.windows = (int)((n + mp::kBuildWindow - 1) / mp::kBuildWindow);
+  w.codes_off = 0;
+  w.cum_off = align256(units * p->L * (size_t)mp::key_blocks(p->n_cap) * mp::kBlockKeys * sizeof(uint16_t));
+  w.total = w.cum_off + align256(units * p->L * (size_t)w.windows * ((size_t)1 << p->K) * sizeof(uint32_t));
+  return w;
+}
+
 void fill_table_args(const magicpig_params* p, const void* tables, mp::TableArgs* t) {
   const size_t units = (size_t)p->batch * p->n_kv_heads;
   char* base = reinterpret_cast<char*>(const_cast<void*>(tables));
@@ -105,6 +118,7 @@ void fill_table_args(const magicpig_params* p, const void* tables, mp::TableArgs
   t->indices = reinterpret_cast<uint32_t*>(base + align256(units * p->L * (((size_t)1 << p->K) + 1) * 4));
   t->K = p->K; t->L = p->L; t->NW = mp::code_words(p->K, p->L); t->units = (int)units;
   t->n = p->n_ctx; t->n_cap = p->n_cap; t->blocks_cap = mp::key_blocks(p->n_cap);
+  t->codes16 = nullptr; t->wincum = nullptr; t->windows = 1;
 }
 
 int check_hash_keys_args(const magicpig_params* p, const void* K_cache, const float* mu, const void* W,
@@ -367,16 +381,28 @@ size_t magicpig_table_bytes(const magicpig_params* p) {
   return align256(units * p->L * (((size_t)1 << p->K) + 1) * 4) + align256(units * p->L * (size_t)p->n_cap * 4);
 }
 
+size_t magicpig_table_build_workspace_bytes(const magicpig_params* p) {
+  if (check_params(p) != MAGICPIG_OK || !tables_supported(p)) return 0;
+  return ws_build_layout(p).total;
+}
+
 int magicpig_build_tables(const magicpig_params* p, const uint32_t* key_codes, void* tables,
                           void* workspace, size_t workspace_bytes, void* hip_stream) {
   int st = check_params(p);
   if (st != MAGICPIG_OK) return st;
   if (!tables_supported(p)) return MAGICPIG_UNSUPPORTED;
   if (!key_codes || !tables || !aligned16(key_codes) || !aligned16(tables)) return MAGICPIG_INVALID_ARG;
-  (void)workspace; (void)workspace_bytes;
   mp::TableArgs t{};
   fill_table_args(p, tables, &t);
   t.kcodes = key_codes;
+  // with room for the per-table codes the keys are placed window by window (several times faster)
+  const BuildWs bw = ws_build_layout(p);
+  if (workspace && aligned16(workspace) && workspace_bytes >= bw.total) {
+    char* wsb = reinterpret_cast<char*>(workspace);
+    t.codes16 = reinterpret_cast<uint16_t*>(wsb + bw.codes_off);
+    t.wincum = reinterpret_cast<uint32_t*>(wsb + bw.cum_off);
+    t.windows = bw.windows;
+  }
   const hipError_t e = mp::launch_build_tables(t, reinterpret_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
 }

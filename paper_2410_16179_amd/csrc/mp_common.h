@@ -131,7 +131,13 @@ struct TableArgs {
   uint32_t* indices;           // [units][L][n_cap]
   int K, L, NW, units;
   int64_t n, n_cap, blocks_cap;   // n: keys [0, n) are in the tables
+  // build with a large workspace: per-table codes of every key and, for every window of
+  // kBuildWindow keys, the number of keys of each bucket in the windows before it
+  uint16_t* codes16;           // [units][L][n_cap], or null (one-pass scatter)
+  uint32_t* wincum;            // [units][L][windows][2^K]
+  int windows;
 };
+constexpr int kBuildWindow = 16384;   // keys one workgroup places into the buckets of one table
 
 constexpr int kPartialStride = 132;   // 128 output elements, running max, running sum, pad
 constexpr int kRangeBlocks = 16;      // key blocks per gather wavefront (1024 keys)

@@ -93,12 +93,25 @@ class Session:
         qw = pack_table_codes(q_codes, self.K, self.L, 1).ravel()
         self.q_codes[: qw.size].copy_(torch.from_numpy(qw.view(np.int32)))
 
-    def build_tables(self, n_indexed=None):
-        """Tables over the keys [0, n_indexed) (default: all); later keys are left to the scan."""
+    def build_tables(self, n_indexed=None, big_workspace=True):
+        """Tables over the keys [0, n_indexed) (default: all); later keys are left to the scan.
+        big_workspace: the two-pass build (codes per table in the workspace) or the one-pass scatter."""
         self.n_indexed = self.n if n_indexed is None else n_indexed
         self.tables = mp.alloc_tables(self.params)
-        mp.magicpig_build_tables(mp.make_params(n_ctx=self.n_indexed, **self._pkw), self.key_codes, self.tables,
-                                 self.ws)
+        pb = mp.make_params(n_ctx=self.n_indexed, **self._pkw)
+        ws = mp.alloc_table_build_workspace(pb) if big_workspace else None
+        mp.magicpig_build_tables(pb, self.key_codes, self.tables, ws)
+        torch.cuda.synchronize()
+
+    def table_buckets(self):
+        """offsets [units, L, 2^K + 1] and indices [units, L, n_cap] of the built tables (host copies)."""
+        units, L, nb = self.B * self.Hkv, self.L, 1 << self.K
+        raw = self.tables.cpu().numpy().view(np.uint32)
+        noff = units * L * (nb + 1)
+        off = raw[:noff].reshape(units, L, nb + 1)
+        start = (noff * 4 + 255) // 256 * 256 // 4
+        idx = raw[start:start + units * L * self.n_cap].reshape(units, L, self.n_cap)
+        return off, idx
 
     def attend(self, debug=True, cand_cap=None, tables=False):
         B, Hq, n = self.B, self.Hq, self.n

@@ -199,6 +199,34 @@ def test_append_keys_with_frozen_mean(oracle):
     np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
 
 
+def test_both_table_builds_give_the_same_buckets(oracle):
+    # 40000 keys: three windows of the two-pass build, the last one partial; (9,120) has 32 tables per pass
+    for cfg, n in (("C2", 40000), ("C4", 20011)):
+        w = wl.scaled(wl.CONFIGS[cfg], batch=1, n_ctx=n, n_q_heads=8, n_kv_heads=2)
+        data = wl.generate(w)
+        s = Session(K=w.K, L=w.L, dtype=w.dtype, Kc=data["K"], Vc=data["V"], q=data["q"], W=data["W"])
+        s.set_mu(oracle_mu(oracle, data["K"], n))
+        s.hash_keys()
+        codes = s.key_table_codes()                              # [B, Hkv, n, L]
+        s.build_tables(big_workspace=False)
+        off1, idx1 = s.table_buckets()
+        s.build_tables(big_workspace=True)
+        off2, idx2 = s.table_buckets()
+        np.testing.assert_array_equal(off1, off2)
+        nb = 1 << w.K
+        for unit in range(2):
+            # offsets are the exclusive prefix sums of the code histogram of every table
+            for t in (0, 31, 32, w.L - 1):
+                hist = np.bincount(codes[0, unit, :, t], minlength=nb)
+                np.testing.assert_array_equal(np.diff(off1[unit, t]), hist)
+            for t in (0, 33, w.L - 1):
+                for c in (0, 1, 77, nb - 1):
+                    lo, hi = off1[unit, t, c], off1[unit, t, c + 1]
+                    ref = np.flatnonzero(codes[0, unit, :, t] == c)
+                    np.testing.assert_array_equal(np.sort(idx1[unit, t, lo:hi]), ref)
+                    np.testing.assert_array_equal(np.sort(idx2[unit, t, lo:hi]), ref)
+
+
 def test_tables_over_a_prefix_and_scan_of_the_appended_keys(oracle):
     # 0: nothing indexed; 64: one block; 1984: most; 2944: what is left lies inside the local window
     w = wl.scaled(wl.CONFIGS["C2"], n_ctx=3000, n_q_heads=8, n_kv_heads=2)
