@@ -294,8 +294,22 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
   const int xs = tail_begin(a.K, a.L), Lt = tail_tables(a.L), NQ = a.NQ;
   BitString tail;
   int tail_x = xs;                                       // next key word the bit string fills
-  auto store_word = [&](int x, uint32_t wv) {
-    if (store_on) blk_codes[slot_in_block(NW, x, lane)] = wv;
+  uint4 tbuf = make_uint4(0, 0, 0, 0);                   // words of the 16-byte group being filled
+  // Words leave in increasing order, starting at a group boundary: whole groups of four are
+  // stored as 16 bytes, the words of the final 1-3 word group one by one.
+  auto emit = [&](int x, uint32_t wv) {
+    if ((x >> 2) < (NW >> 2)) {
+      switch (x & 3) {
+        case 0: tbuf.x = wv; break;
+        case 1: tbuf.y = wv; break;
+        case 2: tbuf.z = wv; break;
+        default:
+          tbuf.w = wv;
+          if (store_on) *reinterpret_cast<uint4*>(blk_codes + (x >> 2) * 256 + lane * 4) = tbuf;
+      }
+    } else if (store_on) {
+      blk_codes[slot_in_block(NW, x, lane)] = wv;
+    }
   };
   auto store_quad = [&](int q) {
     const int x0 = q * 4;
@@ -309,13 +323,13 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
       const int x = x0 + i;
       if (x >= NQ) break;
       if (x < xs) {
-        store_word(x, w4[i]);
+        emit(x, w4[i]);
       } else {
         uint32_t full;
-        if (tail.append(w4[i], Lt, &full)) store_word(tail_x++, full);
+        if (tail.append(w4[i], Lt, &full)) emit(tail_x++, full);
       }
     }
-    if (x0 + 4 >= NQ && tail.nbits > 0) store_word(tail_x, (uint32_t)tail.acc);   // last quad: the rest
+    if (x0 + 4 >= NQ && tail.nbits > 0) emit(tail_x, (uint32_t)tail.acc);   // last quad: the rest
   };
   // One quad: 4 MFMA tiles (2 pairs = 4 code words) against the 64 keys of this wavefront.
   auto do_quad = [&](int q, const uint4* sCur, uint4* sNext) {
