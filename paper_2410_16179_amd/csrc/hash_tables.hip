@@ -298,6 +298,94 @@ __global__ __launch_bounds__(1024) void table_lookup_kernel(AttnArgs a, TableArg
   }
 }
 
+// Production form of the lookup for min_hits 1 or 2 (no count output): one workgroup per query
+// head marks every key it meets in a "seen" bitmap of the whole indexed range and, when it was
+// already marked, in a "seen twice" bitmap (both in LDS, a bit per key); the ballots are those
+// bitmaps.  No bucket is read more than once per head, whatever the context length.
+__global__ __launch_bounds__(1024) void table_lookup_bitmap_kernel(AttnArgs a, TableArgs tb) {
+  extern __shared__ uint32_t bitmap[];                  // seen[nw], twice[nw]
+  __shared__ uint32_t bstart[512], blen[512];
+  __shared__ uint32_t qs[256];
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int64_t bh = blockIdx.x;
+  const int G = a.Hq / a.Hkv;
+  const int64_t unit = (bh / a.Hq) * a.Hkv + (bh % a.Hq) / G;
+  const int nb = 1 << a.K;
+  const uint32_t* offs = tb.offsets + unit * a.L * (nb + 1);
+  const uint32_t* idxs = tb.indices + unit * a.L * tb.n_cap;
+  const int nw = (int)key_blocks(tb.n) * 2;             // 32-key words of the indexed range
+  uint32_t* seen = bitmap;
+  uint32_t* twice = bitmap + nw;
+  for (int i = tid; i < 2 * nw; i += 1024) bitmap[i] = 0u;
+  if (tid < a.NQ) qs[tid] = a.qcodes[bh * a.NQ + tid];
+  __syncthreads();
+  for (int t = tid; t < a.L; t += 1024) {
+    const uint32_t* qw = qs + (t >> 5) * a.K;
+    uint32_t code = 0;
+    for (int b = 0; b < a.K; ++b) code |= ((qw[b] >> (t & 31)) & 1u) << b;
+    const uint32_t s0 = offs[(int64_t)t * (nb + 1) + code], s1 = offs[(int64_t)t * (nb + 1) + code + 1];
+    bstart[t] = s0;
+    blen[t] = s1 - s0;
+  }
+  __syncthreads();
+  // wavefront v reads tables v, v+16, ...: up to 128 entries of each bucket are requested before
+  // any is used; longer buckets are finished in a loop
+  constexpr int kMaxB = 32;                             // L <= 512 tables over 16 wavefronts
+  uint32_t e0[kMaxB], e1[kMaxB];
+  const int nbk = (a.L - wave + 15) >> 4;
+#pragma unroll
+  for (int k = 0; k < kMaxB; ++k) {
+    e0[k] = 0xffffffffu; e1[k] = 0xffffffffu;
+    if (k < nbk) {
+      const int t = wave + 16 * k;
+      const uint32_t len = blen[t];
+      const uint32_t* p = idxs + (int64_t)t * tb.n_cap + bstart[t];
+      if ((uint32_t)lane < len) e0[k] = p[lane];
+      if ((uint32_t)lane + 64 < len) e1[k] = p[lane + 64];
+    }
+  }
+  auto mark = [&](uint32_t key) {
+    if (key != 0xffffffffu) {
+      const uint32_t bit = 1u << (key & 31);
+      if (atomicOr(&seen[key >> 5], bit) & bit) atomicOr(&twice[key >> 5], bit);
+    }
+  };
+#pragma unroll
+  for (int k = 0; k < kMaxB; ++k) {
+    if (k < nbk) {
+      mark(e0[k]);
+      mark(e1[k]);
+      const int t = wave + 16 * k;
+      if (blen[t] > 128) {
+        const uint32_t* p = idxs + (int64_t)t * tb.n_cap + bstart[t];
+        for (uint32_t j = 128 + lane; j < blen[t]; j += 64) mark(p[j]);
+      }
+    }
+  }
+  __syncthreads();
+  // ballots of the indexed range, 32 keys per word, static keys and keys beyond n masked out
+  const int64_t nblk = key_blocks(a.n);
+  const uint32_t* hit = a.tau >= 2 ? twice : seen;
+  uint32_t* mout = reinterpret_cast<uint32_t*>(a.masks) + bh * nblk * 2;
+  const int64_t hi_key = a.n - a.n_local < a.n ? a.n - a.n_local : a.n;
+  for (int i = tid; i < nw; i += 1024) {
+    const int64_t kfirst = (int64_t)i * 32;
+    const int64_t lo = (a.n_sink > kfirst ? a.n_sink : kfirst) - kfirst;
+    const int64_t hi = (hi_key < kfirst + 32 ? hi_key : kfirst + 32) - kfirst;
+    uint32_t elig = 0;
+    if (hi > lo) elig = (hi - lo >= 32 ? 0xffffffffu : ((1u << (hi - lo)) - 1u)) << lo;
+    const uint32_t bits = hit[i] & elig;
+    mout[i] = bits;
+    if (a.dbg_cand) {                                    // debug output only
+      for (uint32_t f = bits; f; f &= f - 1) {
+        const int pos = atomicAdd(&a.dbg_ncand[bh], 1);
+        if (pos < a.dbg_cand_cap) a.dbg_cand[bh * a.dbg_cand_cap + pos] = (int32_t)(kfirst + __ffs(f) - 1);
+      }
+    }
+  }
+}
+
 hipError_t launch_build_tables(const TableArgs& t, hipStream_t s) {
   if (t.units <= 0 || t.L <= 0) return hipSuccess;
   const int tpp = ht_tables_per_pass(t.K);
@@ -319,6 +407,14 @@ hipError_t launch_build_tables(const TableArgs& t, hipStream_t s) {
 
 hipError_t launch_table_lookup(const AttnArgs& a, const TableArgs& t, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
   const int64_t nblk = key_blocks(t.n);
+  // two bits per key in LDS: up to 196608 indexed keys in 48 KB (5 KB more are static)
+  const size_t bitmap_bytes = (size_t)nblk * 2 * 2 * sizeof(uint32_t);
+  if (!a.dbg_counts && (a.tau == 1 || a.tau == 2) && bitmap_bytes <= 48 * 1024) {
+    const dim3 grid((unsigned)((int64_t)a.B * a.Hq));
+    if (start || stop) hipExtLaunchKernelGGL(table_lookup_bitmap_kernel, grid, dim3(1024), bitmap_bytes, s, start, stop, 0, a, t);
+    else hipLaunchKernelGGL(table_lookup_bitmap_kernel, grid, dim3(1024), bitmap_bytes, s, a, t);
+    return hipGetLastError();
+  }
   const dim3 grid((unsigned)((nblk + kLookupRunBlocks - 1) / kLookupRunBlocks), (unsigned)((int64_t)a.B * a.Hq));
   if (start || stop) hipExtLaunchKernelGGL(table_lookup_kernel, grid, dim3(1024), 0, s, start, stop, 0, a, t);
   else hipLaunchKernelGGL(table_lookup_kernel, grid, dim3(1024), 0, s, a, t);

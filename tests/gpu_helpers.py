@@ -113,7 +113,7 @@ class Session:
         idx = raw[start:start + units * L * self.n_cap].reshape(units, L, self.n_cap)
         return off, idx
 
-    def attend(self, debug=True, cand_cap=None, tables=False):
+    def attend(self, debug=True, cand_cap=None, tables=False, with_counts=True):
         B, Hq, n = self.B, self.Hq, self.n
         out = torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device="cuda")
         if debug:
@@ -121,6 +121,8 @@ class Session:
             counts = torch.full((B, Hq, max(n, 1)), -1 if not tables else 0, dtype=torch.int16, device="cuda")
             cand = torch.full((B, Hq, cap), -1, dtype=torch.int32, device="cuda")
             ncand = torch.zeros((B, Hq), dtype=torch.int32, device="cuda")
+            if not with_counts:
+                counts = None
         else:
             counts = cand = ncand = None
         if tables:
@@ -133,7 +135,8 @@ class Session:
         torch.cuda.synchronize()
         res = {"out": out.cpu().numpy()}
         if debug:
-            res["counts"] = counts.cpu().numpy()[:, :, :n].astype(np.int32)
+            if counts is not None:
+                res["counts"] = counts.cpu().numpy()[:, :, :n].astype(np.int32)
             nc = ncand.cpu().numpy()
             cd = cand.cpu().numpy()
             res["ncand"] = nc
