@@ -187,41 +187,81 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
     key[rr] = a.first_key + r % a.n_keys;
     xb[rr] = (unit[rr] / a.n_kv_heads) * a.stride_b + (unit[rr] % a.n_kv_heads) * a.stride_h + key[rr] * a.stride_n;
   }
-  // both vectors in one pass over the column, so that each projector element is converted to
-  // float64 once and nothing but the four accumulators stays live; the vectors are
-  // wave-uniform: read through the constant address space they arrive in SGPRs
-  typedef const uint32_t __attribute__((address_space(4))) * const_u32_ptr;
-  const const_u32_ptr xs0 = (const_u32_ptr)(reinterpret_cast<const char*>(a.X) + xb[0] * (FP32 ? 4 : 2));
-  const const_u32_ptr xs1 = (const_u32_ptr)(reinterpret_cast<const char*>(a.X) + xb[1] * (FP32 ? 4 : 2));
-  double s[2] = {0.0, 0.0}, mag[2] = {0.0, 0.0};
-  // one pass per element: the projector value is converted once and serves either two vectors
-  // or one vector and its centering term mu.w, which is subtracted
-  auto accumulate = [&](auto with_mu) {
-    const const_u32_ptr ms0 = (const_u32_ptr)(a.mu + unit[0] * kHeadDim);
-#pragma unroll
-    for (int i = 0; i < kHeadDim; ++i) {
-      float x0, x1;
-      if constexpr (FP32) {
-        x0 = __uint_as_float(xs0[i]);
-        x1 = __uint_as_float(xs1[i]);
+  // The two vectors (or the vector and its centering vector) are staged once in LDS as float32
+  // and read back as broadcasts: every thread needs all 128 elements of both.
+  __shared__ float4 sx[2][kHeadDim / 4];
+  {
+    const int rr = (tid >> 5) & 1, i4 = tid & 31;         // threads 0..63: four elements each
+    if (tid < 64) {
+      float4 v;
+      if (a.mu && rr == 1) {                             // second "vector": minus the centering vector
+        const float4 m = *reinterpret_cast<const float4*>(a.mu + unit[0] * kHeadDim + i4 * 4);
+        v = make_float4(-m.x, -m.y, -m.z, -m.w);
+      } else if constexpr (FP32) {
+        v = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.X) + xb[rr] + i4 * 4);
       } else {
-        x0 = __uint_as_float((i & 1) ? (xs0[i >> 1] & 0xffff0000u) : (xs0[i >> 1] << 16));
-        x1 = __uint_as_float((i & 1) ? (xs1[i >> 1] & 0xffff0000u) : (xs1[i >> 1] << 16));
+        const uint2 r = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a.X) + xb[rr] + i4 * 4);
+        v = make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u),
+                        __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xffff0000u));
       }
-      const double wv = (double)wf[i];
-      const double p0 = (double)x0 * wv;
-      s[0] += p0; mag[0] += fabs(p0);
-      if constexpr (decltype(with_mu)::value) {
-        const double m0 = (double)__uint_as_float(ms0[i]) * wv;
-        s[0] -= m0; mag[0] += fabs(m0);
-      } else {
-        const double p1 = (double)x1 * wv;
-        s[1] += p1; mag[1] += fabs(p1);
-      }
+      sx[rr][i4] = v;
     }
-  };
-  if (a.mu) accumulate(std::true_type{});
-  else accumulate(std::false_type{});
+  }
+  __syncthreads();
+  const bool with_mu = a.mu != nullptr;                  // then there is one vector: x.w - mu.w
+  // First a float32 pass: sum and sum of magnitudes by one fused multiply-add each per term.
+  // n roundings of relative size 2^-24 at most (n = 128 terms, 257 with a centering vector) give
+  // |sum32 - exact| <= n 2^-24 (1 + small) * sum|terms|, plus what underflowing products lose,
+  // far below the absolute floor: a result beyond kClose32 times the float32 magnitude sum
+  // (itself low by at most the same relative amount) has the exact sign.  Only wavefronts with
+  // a closer result in some column (about one in a thousand) repeat their columns in float64,
+  // where every product of two float32 values is exact.
+  const float kClose32 = with_mu ? 1.6e-5f : 8.0e-6f;
+  float s32[2] = {0.f, 0.f}, m32[2] = {0.f, 0.f};
+#pragma unroll
+  for (int i4 = 0; i4 < kHeadDim / 4; ++i4) {
+    const float4 x0 = sx[0][i4], x1 = sx[1][i4];
+    const float xa[4] = {x0.x, x0.y, x0.z, x0.w}, xc[4] = {x1.x, x1.y, x1.z, x1.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float wv = wf[i4 * 4 + e];
+      s32[0] = fmaf(xa[e], wv, s32[0]);
+      m32[0] = fmaf(fabsf(xa[e]), fabsf(wv), m32[0]);
+      s32[1] = fmaf(xc[e], wv, s32[1]);
+      m32[1] = fmaf(fabsf(xc[e]), fabsf(wv), m32[1]);
+    }
+  }
+  if (with_mu) {
+    s32[0] += s32[1];                                    // one more rounding, inside the factor
+    m32[0] += m32[1];
+  }
+  const bool close0 = !(fabsf(s32[0]) > kClose32 * m32[0] + 1e-30f);
+  const bool close1 = !with_mu && nrow > 1 && !(fabsf(s32[1]) > kClose32 * m32[1] + 1e-30f);
+  double s[2] = {(double)s32[0], (double)s32[1]}, mag[2] = {0.0, 0.0};
+  if (__ballot(col_ok && (close0 || close1))) {
+    // (a wavefront pays for the repeat whether one lane or all need it, so it is kept short:
+    // sixteen elements at a time, nothing hoisted, few registers)
+    s[0] = 0.0; s[1] = 0.0;
+#pragma unroll
+    for (int i4 = 0; i4 < kHeadDim / 4; ++i4) {
+      const float4 x0 = sx[0][i4], x1 = sx[1][i4];
+      const double xa[4] = {(double)x0.x, (double)x0.y, (double)x0.z, (double)x0.w};
+      const double xc[4] = {(double)x1.x, (double)x1.y, (double)x1.z, (double)x1.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const double wv = (double)wf[i4 * 4 + e];
+        s[0] = fma(xa[e], wv, s[0]);                     // exact product, one rounding per term
+        mag[0] = fma(fabs(xa[e]), fabs(wv), mag[0]);
+        s[1] = fma(xc[e], wv, s[1]);
+        mag[1] = fma(fabs(xc[e]), fabs(wv), mag[1]);
+      }
+      if ((i4 & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+    }
+    if (with_mu) {
+      s[0] += s[1];
+      mag[0] += mag[1];
+    }
+  }
   for (int rr = 0; rr < nrow; ++rr) {
     bool bit = s[rr] >= 0.0;
     const bool unsure = col_ok && mag[rr] > 0.0 && fabs(s[rr]) <= kF64Slack * mag[rr];
