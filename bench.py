@@ -105,7 +105,7 @@ def cpu_baseline(w, data, seed):
 def stored_traffic(workload: str):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
     (FETCH_SIZE and WRITE_SIZE, calibrated on a copy of known size); None if absent."""
-    path = os.path.join(ROOT, "profiles", f"collision_scan_{workload}_pmc.txt")
+    path = os.path.join(ROOT, "profiles", f"scan_gather_{workload}_pmc.txt")
     try:
         with open(path) as f:
             for line in f:
@@ -228,16 +228,17 @@ def main():
         ms = ctypes.c_float()
         assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
         return ms.value
+    # (magicpig_sampled_attention scans and gathers in one kernel: events 0 / 1 are its begin /
+    # end timestamps, event 3 the end of the merge kernel)
     stage_ms = {
         "hash_query": float(np.mean([span(q[4], q[0]) for q in evs])),
-        "collision_scan": float(np.mean([span(q[0], q[1]) for q in evs])),
-        "gather_estimate": float(np.mean([span(q[1], q[2]) for q in evs])),
-        "merge": float(np.mean([span(q[2], q[3]) for q in evs])),
+        "scan_gather": float(np.mean([span(q[0], q[1]) for q in evs])),
+        "merge": float(np.mean([span(q[1], q[3]) for q in evs])),
     }
     for quad in evs:
         for e in quad:
             hip.hipEventDestroy(e)
-    scan_ms = stage_ms["collision_scan"]
+    scan_ms = stage_ms["scan_gather"]
 
     # ---- the same decode step with the bucketed hash tables (the paper's Query(HT, q_code))
     # in place of the collision scan: same sample, same output, far fewer bytes
@@ -344,8 +345,11 @@ def main():
     gather_bytes = float((n_sampled + n_static).sum()) * 2 * 128 * (2 if w.dtype == "bf16" else 4)
     out_bytes = heads * 128 * 4
     alg_bytes = scan_bytes + gather_bytes + out_bytes
-    achieved = scan_bytes / (scan_ms * 1e-3) / 1e9
-    path_gbs = alg_bytes / ((scan_ms + stage_ms['gather_estimate'] + stage_ms['merge']) * 1e-3) / 1e9
+    # the dominant kernel streams the codes of the eligible keys and gathers the K and V rows
+    # of the attended ones: both are its algorithmic bytes
+    kernel_bytes = scan_bytes + gather_bytes
+    achieved = kernel_bytes / (scan_ms * 1e-3) / 1e9
+    path_gbs = alg_bytes / ((scan_ms + stage_ms['merge']) * 1e-3) / 1e9
 
     hash_flops = 2.0 * w.batch * w.n_kv_heads * w.n_ctx * 128 * w.K * w.L
     result = {
@@ -359,11 +363,12 @@ def main():
                    "step": "magicpig_hash_query + magicpig_sampled_attention"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": stored_traffic(w.name),
-                     "kernel": "collision_scan_kernel (dominant kernel of magicpig_sampled_attention)",
-                     "avg_launch_ms": scan_ms, "algorithmic_bytes": scan_bytes,
-                     "scan_plus_gather": {"algorithmic_bytes": alg_bytes, "gather_bytes": gather_bytes,
-                                          "achieved": path_gbs, "frac": path_gbs / HBM_PEAK_GBS,
-                                          "what": "scan + gather + merge kernels, bytes / summed durations"},
+                     "kernel": "scan_gather_kernel (dominant kernel of magicpig_sampled_attention)",
+                     "avg_launch_ms": scan_ms, "algorithmic_bytes": kernel_bytes,
+                     "code_bytes": scan_bytes, "row_bytes": gather_bytes,
+                     "with_merge": {"algorithmic_bytes": alg_bytes, "achieved": path_gbs,
+                                    "frac": path_gbs / HBM_PEAK_GBS,
+                                    "what": "scan_gather + merge kernels, bytes / summed durations"},
                      "mean_sampled_per_head": float(n_sampled.mean())},
         "stage_ms": stage_ms, "launch": launch_mode, "gpu_ms_per_step": gpu_ms_per_step,
         "prefill_hash": {"ms": prefill_ms, "keys": w.batch * w.n_kv_heads * w.n_ctx,

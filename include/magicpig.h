@@ -62,7 +62,8 @@ typedef struct magicpig_params {
   int64_t n_ctx;      /* keys per sequence seen by the decode step (all sequences alike)    */
   int64_t n_cap;      /* key capacity of the code buffer per (batch, KV head), >= n_ctx     */
   int64_t k_stride_b, k_stride_h, k_stride_n;   /* element strides of the K cache */
-  int64_t v_stride_b, v_stride_h, v_stride_n;   /* element strides of the V cache */
+  int64_t v_stride_b, v_stride_h, v_stride_n;   /* element strides of the V cache; the decode
+                         step needs row strides (*_stride_n) below 2^31 elements */
 } magicpig_params;
 
 /* ---- packed code layout (part of the contract: the caller stores codes between calls) ----
@@ -190,7 +191,9 @@ int magicpig_sampled_attention_tables(const magicpig_params* params, const void*
  * points to four hipEvent_t handles which later magicpig_sampled_attention[_tables] calls on
  * this host thread attach to their kernels: events[0] / events[1] receive the begin / end
  * timestamp of the retrieval kernel (collision scan or table lookup), events[2] the end of the
- * gather / estimator kernel, events[3] the end of the merge kernel.  NULL switches it off. */
+ * gather / estimator kernel, events[3] the end of the merge kernel.  magicpig_sampled_attention
+ * scans and gathers in one kernel: events[0] / events[1] are its begin / end and events[2] is
+ * recorded on the stream right behind it.  NULL switches it off. */
 void magicpig_profile_stage_events(void* const* events);
 
 const char* magicpig_status_string(int status);

@@ -7,20 +7,66 @@ namespace mp {
 
 typedef const uint32_t __attribute__((address_space(4))) * const_u32_ptr;
 
-// u = P[Binomial(L, x) >= tau], x = p^K, in float32 without cancellation: the complement
-// 1 - P[< tau] when that is below one half, otherwise the positive upper-tail terms.  The
-// hardware exp2/log2/rcp based intrinsics are accurate to about 1e-6 relative here, which
-// moves log u by about 1e-5: two orders below the output tolerance.
-__device__ inline float inclusion_probability(float cosv, int K, int L, int tau) {
+// acos(c), |c| <= 1, by the seven-degree polynomial of Abramowitz & Stegun 4.4.46:
+// acos(x) = sqrt(1 - x) * poly(x) on [0, 1] with |error| <= 2e-8, reflected for negative x.
+__device__ inline float acos_poly(float c) {
+  const float x = fabsf(c);
+  float p = -0.0012624911f;
+  p = fmaf(p, x, 0.0066700901f);
+  p = fmaf(p, x, -0.0170881256f);
+  p = fmaf(p, x, 0.0308918810f);
+  p = fmaf(p, x, -0.0501743046f);
+  p = fmaf(p, x, 0.0889789874f);
+  p = fmaf(p, x, -0.2145988016f);
+  p = fmaf(p, x, 1.5707963050f);
+  const float r = __builtin_sqrtf(1.f - x) * p;
+  return c < 0.f ? 3.14159265358979f - r : r;
+}
+
+// u = P[Binomial(L, x) >= tau], x = p^K, p = 1 - acos(cos)/pi (Eq. "lsh sampling probability",
+// Eq. "close form"), in float32 without cancellation: the complement 1 - P[< tau] when that
+// is below one half, otherwise the positive upper-tail terms.  With term_j = C(L,j) x^j
+// (1-x)^(L-j): term_0 = exp(L log(1-x)), term_{j+1} = term_j * (L-j)/(j+1) * x/(1-x).  The
+// ratios (L-j)/(j+1) come from the host (AttnArgs::head_ratio / tail_ratio, scalar operands).
+// For min_hits <= kFastTau the upper tail is the nested product term_tau * (1 + rho_tau * (1 +
+// rho_tau+1 * ( ... ))) over kTailTerms terms, branch-free: it is only used when
+// P[< tau] >= 1/2, i.e. L x is below about tau, where the neglected terms are below 1e-8 of
+// the sum.  Larger min_hits sum the tail term by term until it no longer changes the sum.
+// log(1-x) is its series below x = 1/8 (8 terms, truncation 7e-9 relative) and the hardware
+// logarithm above, where 150 log errors of 1e-7 no longer matter (P[< tau] is tiny there).
+// Overall u is accurate to a few 1e-6 relative, which moves log u by as much: three orders
+// below the output tolerance.
+__device__ inline float inclusion_probability(float cosv, const AttnArgs& a) {
+  const int K = a.K, L = a.L, tau = a.tau;
   const float c = fminf(fmaxf(cosv, -1.f), 1.f);
-  const float p = 1.f - acosf(c) * 0.31830988618379067f;
+  const float p = 1.f - acos_poly(c) * 0.31830988618379067f;
   float x = 1.f;
   for (int i = 0; i < K; ++i) x *= p;
   if (x >= 1.f) return L >= tau ? 1.f : 0.f;
   if (!(x > 0.f)) return 0.f;
   const float r = __fdividef(x, 1.f - x);
-  float t = __expf((float)L * log1pf(-x));   // term j = 0
+  float lg = 1.f / 9.f;
+  lg = fmaf(lg, x, 1.f / 8.f);
+  lg = fmaf(lg, x, 1.f / 7.f);
+  lg = fmaf(lg, x, 1.f / 6.f);
+  lg = fmaf(lg, x, 1.f / 5.f);
+  lg = fmaf(lg, x, 1.f / 4.f);
+  lg = fmaf(lg, x, 1.f / 3.f);
+  lg = fmaf(lg, x, 1.f / 2.f);
+  lg = fmaf(lg, x, 1.f);
+  lg = x < 0.125f ? -x * lg : __logf(1.f - x);
+  float t = __expf((float)L * lg);           // term j = 0
   float head = 0.f;
+  if (tau <= kFastTau) {
+    for (int j = 0; j < tau; ++j) {
+      head += t;
+      t *= a.head_ratio[j] * r;
+    }
+    float s = 1.f;
+#pragma unroll
+    for (int i = kTailTerms - 1; i >= 0; --i) s = fmaf(a.tail_ratio[i] * r, s, 1.f);
+    return head < 0.5f ? 1.f - head : t * s;
+  }
   for (int j = 0; j < tau; ++j) {
     head += t;
     t *= (float)(L - j) * __frcp_rn((float)(j + 1)) * r;
@@ -66,12 +112,6 @@ __device__ inline int64_t static_key(const AttnArgs& a, int64_t j) {
   return j < sink_keys ? j : j + (a.n - a.n_local - a.n_sink);
 }
 
-// One wavefront attends the keys key_of(0) .. key_of(total - 1) of query head bh (KV unit
-// `unit`) and stores one (output[128], max, sum) partial at `pp`.  A quarter wavefront holds
-// one 128-element row; all K and V rows of a batch are requested before any is used; q.k,
-// q.(k-mu), |k-mu|^2 are reduced over the 16 lanes of a row; the inclusion probability and
-// the logit q.k/sqrt(d) - log u are evaluated once per key (sampled keys only: static keys
-// enter with u = 1); an online max/sum softmax accumulates the weighted V rows.
 // The query row and the centering vector of a wavefront's head, eight elements per lane (the
 // 16 lanes of a quarter wavefront hold a row).  Requested at the start of the kernel, so that
 // they travel together with the ballots instead of after them.
@@ -93,10 +133,17 @@ __device__ inline void request_head_vectors(const AttnArgs& a, int unit, int64_t
   }
 }
 
-template <bool FP32, class KeyOf>
+// One wavefront attends the keys key_of(0) .. key_of(total - 1) of query head bh (KV unit
+// `unit`) and stores one (output[128], max, sum) partial at `pp`.  A quarter wavefront holds
+// one 128-element row; all K and V rows of a batch (kIters rows per quarter wavefront) are
+// requested before any is used; q.k, q.(k-mu), |k-mu|^2 are reduced over the 16 lanes of a
+// row; the inclusion probability and the logit q.k/sqrt(d) - log u are evaluated once per key
+// (sampled keys only: static keys enter with u = 1); an online max/sum softmax accumulates the
+// weighted V rows.
+template <bool FP32, int kIters, class KeyOf>
 __device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t bh, int total, bool sampled,
                                             const HeadVectors<FP32>& hv, KeyOf key_of, float* pp) {
-  constexpr int kIters = FP32 ? 4 : 8;                    // rows per quarter-wavefront and batch
+  static_assert(kIters >= 1 && kIters <= 16, "one lane of a quarter wavefront per row of a batch");
   const int lane = threadIdx.x & 63;
   const int b = unit / a.Hkv, g = unit % a.Hkv;
   const int qd = lane >> 4, sl = lane & 15;
@@ -107,17 +154,28 @@ __device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t
   for (int e = 0; e < 8; ++e) o[e] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
+  // row strides are below 2^31 elements (checked by the host): one 32 x 32 -> 64-bit
+  // multiply-add per address
+  const uint32_t ksn = (uint32_t)a.ks_n, vsn = (uint32_t)a.vs_n;
   for (int base = 0; base < total; base += 4 * kIters) {
     Frag kf[kIters], vf[kIters];
     bool ok[kIters];
+    // quarter-wavefront rounds of this batch that hold at least one row (wave-uniform): the
+    // work of the others is skipped
+    const int rounds = (total - base + 3) >> 2;
 #pragma unroll
     for (int it = 0; it < kIters; ++it) {
       const int cc = base + it * 4 + qd;
       ok[it] = cc < total;
-      const int64_t idx = key_of(ok[it] ? cc : base);
-      if (ok[it]) {
-        frag_load<FP32>(a.Kc, kbase + idx * a.ks_n, kf[it]);
-        frag_load<FP32>(a.Vc, vbase + idx * a.vs_n, vf[it]);
+      if (it < rounds) {
+        const uint32_t idx = (uint32_t)key_of(ok[it] ? cc : base);
+        if (ok[it]) {
+          frag_load<FP32>(a.Kc, kbase + (int64_t)((uint64_t)idx * ksn), kf[it]);
+          frag_load<FP32>(a.Vc, vbase + (int64_t)((uint64_t)idx * vsn), vf[it]);
+        } else {
+          frag_zero<FP32>(kf[it]);
+          frag_zero<FP32>(vf[it]);
+        }
       } else {
         frag_zero<FP32>(kf[it]);
         frag_zero<FP32>(vf[it]);
@@ -137,6 +195,7 @@ __device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t
     bool my_ok = false;
 #pragma unroll
     for (int it = 0; it < kIters; ++it) {
+      if (it >= rounds) break;
       float kv[8];
       frag_to_float<FP32>(kf[it], kv);
       float dq = 0.f, nn = 0.f;
@@ -168,7 +227,7 @@ __device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t
       if (sampled && a.tau > 0) {
         const float den = qnorm * sqrtf(my_nn);
         const float cosv = den > 0.f ? my_dc / den : 0.f;
-        const float u = fmaxf(inclusion_probability(cosv, a.K, a.L, a.tau), 1.17549435e-38f);
+        const float u = fmaxf(inclusion_probability(cosv, a), 1.17549435e-38f);
         logit -= __logf(u);
       }
     }
@@ -181,6 +240,7 @@ __device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t
     for (int e = 0; e < 8; ++e) o[e] *= alpha;
 #pragma unroll
     for (int it = 0; it < kIters; ++it) {
+      if (it >= rounds) break;
       const float wv = __shfl(wgt, (lane & 48) | it);
       float vv[8];
       frag_to_float<FP32>(vf[it], vv);

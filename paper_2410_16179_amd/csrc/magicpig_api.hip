@@ -76,7 +76,7 @@ HashWs ws_hash_layout(const magicpig_params* p) {
 size_t ws_hash(const magicpig_params* p) { return p->dtype == MAGICPIG_BF16 ? ws_hash_layout(p).total : 256; }
 
 // decode workspace: [partials | ballots]
-struct AttnWs { size_t partial_off, masks_off, total; int nranges, nscan; int64_t n_static; };
+struct AttnWs { size_t partial_off, masks_off, total; int nranges, nscan, f_nranges, f_nstatic; int64_t n_static; };
 AttnWs ws_attention_layout(const magicpig_params* p) {
   AttnWs w{};
   const int64_t nblk = mp::key_blocks(p->n_ctx);
@@ -85,8 +85,12 @@ AttnWs ws_attention_layout(const magicpig_params* p) {
   const int64_t st = (int64_t)p->n_sink + p->n_local;
   w.n_static = st < p->n_ctx ? st : p->n_ctx;
   w.nranges = w.nscan + (int)((w.n_static + mp::kStaticPerRange - 1) / mp::kStaticPerRange);
+  // the one-launch scan + gather has shorter runs, hence more partials per head
+  w.f_nstatic = (int)((w.n_static + mp::kFusedStatic - 1) / mp::kFusedStatic);
+  w.f_nranges = w.f_nstatic + (int)((nblk + mp::kFusedBlocks - 1) / mp::kFusedBlocks);
+  const size_t most = (size_t)(w.f_nranges > w.nranges ? w.f_nranges : w.nranges);
   w.partial_off = 0;
-  w.masks_off = align256(heads * w.nranges * mp::kPartialStride * sizeof(float));
+  w.masks_off = align256(heads * most * mp::kPartialStride * sizeof(float));
   w.total = w.masks_off + align256(heads * (size_t)nblk * sizeof(uint64_t));
   return w;
 }
@@ -192,6 +196,8 @@ int run_attention_impl(const magicpig_params* p, const void* q, const void* K_ca
   if (st != MAGICPIG_OK) return st;
   if ((st = check_strides(p->k_stride_b, p->k_stride_h, p->k_stride_n)) != MAGICPIG_OK) return st;
   if ((st = check_strides(p->v_stride_b, p->v_stride_h, p->v_stride_n)) != MAGICPIG_OK) return st;
+  // the gather forms row addresses from 32-bit row strides
+  if (p->k_stride_n > INT32_MAX || p->v_stride_n > INT32_MAX) return MAGICPIG_UNSUPPORTED;
   const bool has_keys = p->n_ctx > 0 && p->batch > 0;
   if (!out || !workspace || (!q && p->batch > 0)) return MAGICPIG_INVALID_ARG;
   if (has_keys && (!K_cache || !V_cache || (!key_codes && !tables) || !q_codes)) return MAGICPIG_INVALID_ARG;
@@ -214,6 +220,7 @@ int run_attention_impl(const magicpig_params* p, const void* q, const void* K_ca
   a.partial = reinterpret_cast<float*>(wsb + wl.partial_off); a.out = out;
   a.masks = reinterpret_cast<uint64_t*>(wsb + wl.masks_off);
   a.nranges = wl.nranges; a.nscan = wl.nscan; a.n_static = wl.n_static;
+  a.f_nranges = wl.f_nranges; a.f_nstatic = wl.f_nstatic;
   a.dbg_counts = dbg_counts; a.dbg_cand = dbg_cand; a.dbg_ncand = dbg_ncand; a.dbg_cand_cap = dbg_cand_cap;
   a.is_fp32 = p->dtype == MAGICPIG_FP32;
   a.B = p->batch; a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.K = p->K; a.L = p->L;
@@ -223,6 +230,11 @@ int run_attention_impl(const magicpig_params* p, const void* q, const void* K_ca
   a.ks_b = p->k_stride_b; a.ks_h = p->k_stride_h; a.ks_n = p->k_stride_n;
   a.vs_b = p->v_stride_b; a.vs_h = p->v_stride_h; a.vs_n = p->v_stride_n;
   a.scale = 0.08838834764831845f;   // 1/sqrt(128)
+  {
+    auto ratio = [&](int j) { return j < p->L ? (float)((double)(p->L - j) / (double)(j + 1)) : 0.f; };
+    for (int j = 0; j < mp::kFastTau; ++j) a.head_ratio[j] = ratio(j);
+    for (int i = 0; i < mp::kTailTerms; ++i) a.tail_ratio[i] = ratio(p->min_hits + i);
+  }
   mp::TableArgs t{};
   if (tables) {
     fill_table_args(p, tables, &t);

@@ -107,6 +107,9 @@ struct MeanArgs {
   int64_t stride_b, stride_h, stride_n;
 };
 
+constexpr int kFastTau = 4;      // largest min_hits whose inclusion probability takes the branch-free form
+constexpr int kTailTerms = 16;   // terms of its upper-tail series
+
 struct AttnArgs {
   const void* q; const void* Kc; const void* Vc; const float* mu;
   const uint32_t* kcodes; const uint32_t* qcodes;
@@ -121,6 +124,12 @@ struct AttnArgs {
   int nranges;               // partials per head: nscan runs of kRangeBlocks key blocks + static runs
   int nscan;                 // runs of kRangeBlocks key blocks per head
   int64_t n_static;          // keys in the static set T
+  // scan and gather in one launch (0 partials: not used): f_nstatic workgroups per KV head for
+  // the static set, then one per kFusedBlocks key blocks; one partial per head and workgroup
+  int f_nranges, f_nstatic;
+  // ratios of consecutive binomial terms, (L-j)/(j+1) (0 from j = L on): j = 0 .. kFastTau-1,
+  // and j = tau .. tau+kTailTerms-1 (filled when tau <= kFastTau)
+  float head_ratio[kFastTau], tail_ratio[kTailTerms];
   float scale;
 };
 
@@ -142,6 +151,11 @@ constexpr int kBuildWindow = 16384;   // keys one workgroup places into the buck
 constexpr int kPartialStride = 132;   // 128 output elements, running max, running sum, pad
 constexpr int kRangeBlocks = 16;      // key blocks per gather wavefront (1024 keys)
 constexpr int kStaticPerRange = 32;   // static (sink / local) keys per gather wavefront
+// the one-launch scan + gather: four wavefronts per workgroup
+constexpr int kFusedWaveBlocks = 4;           // key blocks a wavefront scans, one after the other
+constexpr int kFusedBlocks = 4 * kFusedWaveBlocks;        // key blocks per workgroup
+constexpr int kFusedIters = 8;             // its gather batch: rows per quarter wavefront
+constexpr int kFusedStatic = 4 * kFusedIters;             // static keys per workgroup and head there
 
 // host-side launchers (defined next to their kernels)
 hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s);

@@ -1,22 +1,31 @@
 // One decode step of LSH-sampled attention (Algorithm 1 "MagicPIG Decoding"; Eq. "lsh
-// sampling probability"; Eq. "close form"), HBM-bound, in two launches.
+// sampling probability"; Eq. "close form"), HBM-bound.
 //
-// collision_scan_kernel  (streams the packed key codes once)
+// Retrieval by scanning the packed codes of every key (magicpig_sampled_attention):
+//   scan_gather_kernel, then merge_partials_kernel.
+// Retrieval through the hash tables (magicpig_sampled_attention_tables):
+//   table lookup [+ collision_scan_kernel over the keys appended since the build],
+//   gather_estimate_kernel, merge_partials_kernel.
+//
+// collision scan (scan_blocks)
 //   One wavefront per 64-key code block, lane = key: the block is a contiguous 256*NW-byte
 //   read, 16 bytes per lane and load.  For each of the G query heads of the KV head the K
 //   bit planes of every table word are XNOR-ed with the query's (scalar operands) and
 //   AND-ed together; a popcount adds the number of colliding tables.  Keys outside the
-//   static set with count >= min_hits are reported as one 64-bit ballot per (head, block).  No LDS, no barrier, about 60 VGPRs: eight wavefronts per SIMD keep
-//   enough loads in flight to saturate HBM.
-// gather_estimate_kernel  (random 256-byte K and V rows)
+//   static set with count >= min_hits are reported as one 64-bit ballot per (head, block).
+//   No LDS, no barrier, about 60 VGPRs.
+// gather and estimate (gather_estimate_wave)
 //   One wavefront per (query head, run of 16 key blocks): the ballots are expanded into an
 //   index list in LDS by a wavefront prefix sum (further wavefronts take the static sink and
-//   local-window keys, 32 each, so that no wavefront needs a second batch in the usual case); rows are gathered four at a time (a
-//   quarter wavefront holds one 128-element row) with up to 32 K rows and 32 V rows in
-//   flight; q.k, q.(k-mu), |k-mu|^2 are reduced over the 16 lanes of a row, the inclusion
-//   probability u_i and the logit q.k/sqrt(d) - log u_i are evaluated once per candidate,
-//   and an online max/sum softmax accumulates the weighted V rows.  The wavefront stores a
-//   (max, sum, output) partial.
+//   local-window keys, 32 each, so that no wavefront needs a second batch in the usual
+//   case); rows are gathered four at a time (a quarter wavefront holds one 128-element row)
+//   with up to 32 K rows and 32 V rows in flight; q.k, q.(k-mu), |k-mu|^2 are reduced over
+//   the 16 lanes of a row, the inclusion probability u_i and the logit q.k/sqrt(d) - log u_i
+//   are evaluated once per candidate, and an online max/sum softmax accumulates the weighted
+//   V rows.  The wavefront stores a (max, sum, output) partial.
+// scan_gather_kernel does both for a run of 16 key blocks in one workgroup;
+// collision_scan_kernel / gather_estimate_kernel are the two as separate launches, joined by
+// the ballots in HBM.
 // merge_partials_kernel combines a head's partials (the "recursive attention" merge of
 //   Sec. 4.4) and writes the output row.
 #include "attention_common.h"
@@ -28,20 +37,33 @@
 
 namespace mp {
 
+// Reports the keys of block `blk` that query head `head` samples (lane = key, cnt = its number
+// of colliding tables): the ballot of the sampled keys, plus the optional debug outputs.
+__device__ inline uint64_t report_block(const AttnArgs& a, int64_t head, int64_t blk, int lane, uint32_t cnt) {
+  const int64_t i = blk * kBlockKeys + lane;
+  const bool valid = i < a.n;
+  const bool in_T = i < a.n_sink || i >= a.n - a.n_local;
+  const bool hit = valid && !in_T && (a.tau <= 0 || (int)cnt >= a.tau);
+  const uint64_t m = __ballot(hit);
+  if (a.dbg_counts && valid) a.dbg_counts[head * a.n + i] = (uint16_t)cnt;
+  if (a.dbg_cand && hit) {
+    const int pos = atomicAdd(&a.dbg_ncand[head], 1);
+    if (pos < a.dbg_cand_cap) a.dbg_cand[head * a.dbg_cand_cap + pos] = (int32_t)i;
+  }
+  return m;
+}
+
+// One wavefront compares BPW consecutive 64-key code blocks (lane = key) of KV unit `unit`,
+// starting at block blk0 < key_blocks(n), with the codes of the unit's G query heads, and hands
+// emit(h, blk, ballot) the sampled keys of every (head, block).
 // KT, WDT, LT: compile-time K, ceil(L/32) and tables in the last group for the tuned
 // instantiations, 0 for the generic one.
-// BPW: consecutive 64-key blocks per wavefront; all their code words are requested before the
-// first comparison, and each scalar-loaded query word serves BPW keys per lane.
-template <int KT, int WDT, int LT, int BPW>
-__global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
+// BPW: all code words of the blocks are requested before the first comparison, and each
+// scalar-loaded query word serves BPW keys per lane.
+template <int KT, int WDT, int LT, int BPW, class Emit>
+__device__ inline void scan_blocks(const AttnArgs& a, int unit, int64_t blk0, int lane, Emit emit) {
   constexpr bool kGeneric = (KT == 0);
-  // readfirstlane tells the compiler that the wavefront index (and everything derived from
-  // it: KV head, query-code address) is uniform, so those loads become scalar
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int64_t nblk = key_blocks(a.n);
-  const int unit = blockIdx.y;
-  const int64_t blk0 = a.blk_begin + ((int64_t)blockIdx.x * 4 + wave) * BPW;
-  if (blk0 >= nblk) return;
   const int G = a.Hq / a.Hkv;
   const int K = kGeneric ? a.K : KT;
   const int Wd = kGeneric ? a.Wd : WDT;
@@ -114,22 +136,29 @@ __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
 #pragma unroll
     for (int j = 0; j < BPW; ++j) {
       const int64_t blk = blk0 + j;
-      if (blk < nblk) {
-        const int64_t i = blk * kBlockKeys + lane;
-        const bool valid = i < a.n;
-        const bool in_T = i < a.n_sink || i >= a.n - a.n_local;
-        const bool hit = valid && !in_T && (a.tau <= 0 || (int)cnt[j] >= a.tau);
-        const uint64_t m = __ballot(hit);
-        if (lane == 0) a.masks[(head0 + h) * nblk + blk] = m;
-        if (a.dbg_counts && valid) a.dbg_counts[(head0 + h) * a.n + i] = (uint16_t)cnt[j];
-        if (a.dbg_cand && hit) {
-          const int pos = atomicAdd(&a.dbg_ncand[head0 + h], 1);
-          if (pos < a.dbg_cand_cap) a.dbg_cand[(head0 + h) * a.dbg_cand_cap + pos] = (int32_t)i;
-        }
-      }
+      if (blk < nblk) emit(h, blk, report_block(a, head0 + h, blk, lane, cnt[j]));
     }
   }
 }
+
+template <int KT, int WDT, int LT, int BPW>
+__global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
+  // readfirstlane tells the compiler that the wavefront index (and everything derived from
+  // it: KV head, query-code address) is uniform, so those loads become scalar
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int64_t nblk = key_blocks(a.n);
+  const int unit = blockIdx.y;
+  const int64_t blk0 = a.blk_begin + ((int64_t)blockIdx.x * 4 + wave) * BPW;
+  if (blk0 >= nblk) return;
+  const int G = a.Hq / a.Hkv;
+  const int64_t head0 = (int64_t)(unit / a.Hkv) * a.Hq + (int64_t)(unit % a.Hkv) * G;
+  scan_blocks<KT, WDT, LT, BPW>(a, unit, blk0, lane, [&](int h, int64_t blk, uint64_t m) {
+    if (lane == 0) a.masks[(head0 + h) * nblk + blk] = m;
+  });
+}
+
+// rows per quarter wavefront and batch of the stand-alone gather: 32 K and 32 V rows in flight
+template <bool FP32> constexpr int kGatherIters = FP32 ? 4 : 8;
 
 // One wavefront = one (query head, run of kRangeBlocks key blocks).  blockDim = 64 * G:
 // the G wavefronts of a workgroup serve the G heads of one KV head on the same run.
@@ -179,26 +208,106 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
   }
   float* pp = a.partial + (bh * a.nranges + range) * kPartialStride;
   if (!is_static) {
-    gather_estimate_wave<FP32>(a, unit, bh, total, true, hv,
+    gather_estimate_wave<FP32, kGatherIters<FP32>>(a, unit, bh, total, true, hv,
                                [&](int c) { return blk0 * kBlockKeys + (int64_t)list[c]; }, pp);
   } else {
-    gather_estimate_wave<FP32>(a, unit, bh, total, false, hv,
+    gather_estimate_wave<FP32, kGatherIters<FP32>>(a, unit, bh, total, false, hv,
                                [&](int c) { return static_key(a, static_first + c); }, pp);
   }
 }
 
-// Merges the (max, sum, output) partials of one query head (256 threads: wavefront w takes
-// every fourth group of partials, lane = two output elements).  Every load of a pass is
+// Scan and gather in one launch (the whole context is scanned, no hash tables): a workgroup of
+// four wavefronts compares kFusedBlocks = 16 consecutive code blocks with the G heads' codes
+// (scan_blocks, four blocks per wavefront one after the other), leaves the ballots in LDS, and
+// wavefront h then gathers and weighs the keys that head h samples from these 1024 keys (about
+// 17 at a sampling rate of 1.6 %: one batch of the 32-row gather).  As separate launches the
+// gather follows the scan with two dependent round trips of its own (ballots, then rows) on an
+// idle memory system; here the rows of one workgroup travel while the others still stream
+// codes, and only the gather of the last workgroups is exposed (measured at 32 heads x 98304
+// keys: 35 us against 25.6 + 13.7 us).  Shorter runs (4 or 8 blocks per workgroup) measured the
+// same kernel time but cost more partials and gather batches; the 141 registers of this form
+// (three wavefronts per SIMD) measured faster than the same kernel held to 128.
+// The first f_nstatic workgroups of a KV head take the static set T, kFusedStatic keys each.
+// One partial per (head, workgroup).
+template <int KT, int WDT, int LT, bool FP32>
+__global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
+  constexpr int kIt = FP32 ? (kFusedIters + 1) / 2 : kFusedIters;   // the same registers per batch
+  __shared__ uint64_t smask[8][kFusedBlocks];
+  __shared__ uint16_t lists[4][kFusedBlocks * kBlockKeys];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int unit = blockIdx.y, run = blockIdx.x;
+  const int G = a.Hq / a.Hkv;
+  const int64_t head0 = (int64_t)(unit / a.Hkv) * a.Hq + (int64_t)(unit % a.Hkv) * G;
+  if (run < a.f_nstatic) {
+    const int64_t first = (int64_t)run * kFusedStatic;
+    const int64_t left = a.n_static - first;
+    const int total = (int)(left < kFusedStatic ? left : kFusedStatic);
+    for (int h = wave; h < G; h += 4) {
+      HeadVectors<FP32> hv;
+      request_head_vectors<FP32>(a, unit, head0 + h, hv);
+      gather_estimate_wave<FP32, kIt>(a, unit, head0 + h, total, false, hv,
+                                              [&](int c) { return static_key(a, first + c); },
+                                              a.partial + ((head0 + h) * a.f_nranges + run) * kPartialStride);
+    }
+    return;
+  }
+  const int64_t nblk = key_blocks(a.n);
+  const int64_t blk0 = (int64_t)(run - a.f_nstatic) * kFusedBlocks;
+#pragma unroll 1
+  for (int j = 0; j < kFusedWaveBlocks; ++j) {
+    const int bi = wave * kFusedWaveBlocks + j;
+    if (blk0 + bi < nblk) {
+      scan_blocks<KT, WDT, LT, 1>(a, unit, blk0 + bi, lane, [&](int h, int64_t, uint64_t m) {
+        if (lane == 0) smask[h][bi] = m;
+      });
+    } else if (lane < G) {
+      smask[lane][bi] = 0;
+    }
+  }
+  __syncthreads();
+  uint16_t* list = lists[wave];
+  for (int h = wave; h < G; h += 4) {
+    HeadVectors<FP32> hv;
+    request_head_vectors<FP32>(a, unit, head0 + h, hv);
+    // ---- the ballots of head h as an index list (wavefront prefix sum) ----
+    uint64_t m = lane < kFusedBlocks ? smask[h][lane] : 0;
+    const int c = __popcll(m);
+    int incl = c;
+#pragma unroll
+    for (int o = 1; o < kFusedBlocks; o <<= 1) {
+      const int v = __shfl_up(incl, o);
+      if (lane >= o) incl += v;
+    }
+    const int total = __shfl(incl, kFusedBlocks - 1);
+    int pos = incl - c;
+    while (m) {
+      const int bit = __ffsll((unsigned long long)m) - 1;
+      list[pos++] = (uint16_t)(lane * kBlockKeys + bit);
+      m &= m - 1;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    gather_estimate_wave<FP32, kIt>(a, unit, head0 + h, total, true, hv,
+                                            [&](int cc) { return blk0 * kBlockKeys + (int64_t)list[cc]; },
+                                            a.partial + ((head0 + h) * a.f_nranges + run) * kPartialStride);
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+// Merges the (max, sum, output) partials of one query head (NWAVES wavefronts: wavefront w takes
+// every NWAVES-th group of partials, lane = two output elements).  Every load of a pass is
 // issued before any is used - their addresses do not depend on the data - so a pass costs
-// one memory round trip; LDS joins the four wavefronts.
-__global__ __launch_bounds__(256) void merge_partials_kernel(AttnArgs a) {
+// one memory round trip; LDS joins the wavefronts.
+template <int NWAVES>
+__global__ __launch_bounds__(64 * NWAVES) void merge_partials_kernel(AttnArgs a) {
   constexpr int kPer = 16;                    // partials per wavefront and pass
-  __shared__ float sm[4], sl_[4], so[4][kHeadDim];
+  __shared__ float sm[NWAVES], sl_[NWAVES], so[NWAVES][kHeadDim];
   const int64_t bh = blockIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const float* hp = a.partial + bh * a.nranges * kPartialStride;
   float m = -INFINITY, l = 0.f, ox = 0.f, oy = 0.f;
-  for (int r0 = wave * kPer; r0 < a.nranges; r0 += 4 * kPer) {
+  for (int r0 = wave * kPer; r0 < a.nranges; r0 += NWAVES * kPer) {
     float2 oc[kPer];
     float mr[kPer], lr[kPer];
 #pragma unroll
@@ -230,11 +339,13 @@ __global__ __launch_bounds__(256) void merge_partials_kernel(AttnArgs a) {
   so[wave][2 * lane + 1] = oy;
   __syncthreads();
   if (threadIdx.x < kHeadDim) {
-    const float M = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
+    float M = sm[0];
+#pragma unroll
+    for (int w = 1; w < NWAVES; ++w) M = fmaxf(M, sm[w]);
     float acc = 0.f, lt = 0.f;
     if (M > -INFINITY) {
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
+      for (int w = 0; w < NWAVES; ++w) {
         if (sm[w] > -INFINITY) {
           const float s = expf(sm[w] - M);
           acc += s * so[w][threadIdx.x];
@@ -277,6 +388,25 @@ static hipError_t launch_scan(const AttnArgs& a, hipStream_t s, hipEvent_t start
   return hipGetLastError();
 }
 
+static hipError_t launch_scan_gather(const AttnArgs& a, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
+  const dim3 block(256), grid((unsigned)a.f_nranges, (unsigned)(a.B * a.Hkv));
+#define MP_TUNED(KT, LL)                                                                            \
+  if (a.K == KT && a.L == LL) {                                                                     \
+    if (a.is_fp32)                                                                                  \
+      launch_timed(scan_gather_kernel<KT, (LL + 31) / 32, LL - 32 * ((LL + 31) / 32 - 1), true>,    \
+                   grid, block, s, start, stop, a);                                                 \
+    else                                                                                            \
+      launch_timed(scan_gather_kernel<KT, (LL + 31) / 32, LL - 32 * ((LL + 31) / 32 - 1), false>,   \
+                   grid, block, s, start, stop, a);                                                 \
+    return hipGetLastError();                                                                       \
+  }
+  MP_TUNED(10, 150) MP_TUNED(9, 120) MP_TUNED(10, 170) MP_TUNED(8, 75)
+#undef MP_TUNED
+  if (a.is_fp32) launch_timed(scan_gather_kernel<0, 0, 0, true>, grid, block, s, start, stop, a);
+  else launch_timed(scan_gather_kernel<0, 0, 0, false>, grid, block, s, start, stop, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, hipStream_t s, hipEvent_t const* ev) {
   const int64_t heads = (int64_t)a.B * a.Hq;
   if (heads <= 0) return hipSuccess;
@@ -301,14 +431,22 @@ hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, 
       if (e != hipSuccess) return e;
     }
   } else {
-    e = launch_scan(a, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr);
-    if (e != hipSuccess) return e;
+    // whole-context scan: scan and gather in one launch, then the merge over its partials
+    if ((e = launch_scan_gather(a, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr)) != hipSuccess) return e;
+    if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
+    AttnArgs b = a;
+    b.nranges = a.f_nranges;
+    if (b.nranges > 128)
+      launch_timed(merge_partials_kernel<16>, dim3((unsigned)heads), dim3(1024), s, nullptr, ev ? ev[3] : nullptr, b);
+    else
+      launch_timed(merge_partials_kernel<4>, dim3((unsigned)heads), dim3(256), s, nullptr, ev ? ev[3] : nullptr, b);
+    return hipGetLastError();
   }
   const dim3 grid((unsigned)a.nranges, (unsigned)(a.B * a.Hkv)), block(64 * (a.Hq / a.Hkv));
   if (a.is_fp32) launch_timed(gather_estimate_kernel<true>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);
   else launch_timed(gather_estimate_kernel<false>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  launch_timed(merge_partials_kernel, dim3((unsigned)heads), dim3(256), s, nullptr, ev ? ev[3] : nullptr, a);
+  launch_timed(merge_partials_kernel<4>, dim3((unsigned)heads), dim3(256), s, nullptr, ev ? ev[3] : nullptr, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   return hipSuccess;
 }

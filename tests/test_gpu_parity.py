@@ -147,7 +147,7 @@ def test_generic_table_shapes(oracle, K, L, Hq, Hkv, dtype):
     run_case(oracle, w)
 
 
-@pytest.mark.parametrize("tau", [0, 1, 3])
+@pytest.mark.parametrize("tau", [0, 1, 3, 4, 5, 7])    # 5 and up: the term-by-term tail of the inclusion probability
 def test_other_hit_thresholds(oracle, tau):
     w = wl.scaled(wl.CONFIGS["C2"], n_ctx=2000, n_q_heads=8, n_kv_heads=2, min_hits=tau)
     ref, res, _ = run_case(oracle, w)
