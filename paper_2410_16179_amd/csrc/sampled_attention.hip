@@ -388,6 +388,15 @@ static hipError_t launch_scan(const AttnArgs& a, hipStream_t s, hipEvent_t start
   return hipGetLastError();
 }
 
+// a wavefront merges 16 partials per pass: enough wavefronts for one pass where that fits
+static hipError_t launch_merge(const AttnArgs& a, int64_t heads, hipStream_t s, hipEvent_t stop) {
+  const dim3 grid((unsigned)heads);
+  if (a.nranges <= 64) launch_timed(merge_partials_kernel<4>, grid, dim3(256), s, nullptr, stop, a);
+  else if (a.nranges <= 128) launch_timed(merge_partials_kernel<8>, grid, dim3(512), s, nullptr, stop, a);
+  else launch_timed(merge_partials_kernel<16>, grid, dim3(1024), s, nullptr, stop, a);
+  return hipGetLastError();
+}
+
 static hipError_t launch_scan_gather(const AttnArgs& a, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
   const dim3 block(256), grid((unsigned)a.f_nranges, (unsigned)(a.B * a.Hkv));
 #define MP_TUNED(KT, LL)                                                                            \
@@ -436,19 +445,14 @@ hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, 
     if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
     AttnArgs b = a;
     b.nranges = a.f_nranges;
-    if (b.nranges > 128)
-      launch_timed(merge_partials_kernel<16>, dim3((unsigned)heads), dim3(1024), s, nullptr, ev ? ev[3] : nullptr, b);
-    else
-      launch_timed(merge_partials_kernel<4>, dim3((unsigned)heads), dim3(256), s, nullptr, ev ? ev[3] : nullptr, b);
+    if ((e = launch_merge(b, heads, s, ev ? ev[3] : nullptr)) != hipSuccess) return e;
     return hipGetLastError();
   }
   const dim3 grid((unsigned)a.nranges, (unsigned)(a.B * a.Hkv)), block(64 * (a.Hq / a.Hkv));
   if (a.is_fp32) launch_timed(gather_estimate_kernel<true>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);
   else launch_timed(gather_estimate_kernel<false>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  launch_timed(merge_partials_kernel<4>, dim3((unsigned)heads), dim3(256), s, nullptr, ev ? ev[3] : nullptr, a);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  return hipSuccess;
+  return launch_merge(a, heads, s, ev ? ev[3] : nullptr);
 }
 
 }  // namespace mp
