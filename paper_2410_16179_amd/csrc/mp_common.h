@@ -124,8 +124,8 @@ struct AttnArgs {
   int nranges;               // partials per head: nscan runs of kRangeBlocks key blocks + static runs
   int nscan;                 // runs of kRangeBlocks key blocks per head
   int64_t n_static;          // keys in the static set T
-  // scan and gather in one launch (0 partials: not used): f_nstatic workgroups per KV head for
-  // the static set, then one per kFusedBlocks key blocks; one partial per head and workgroup
+  // scan and gather in one launch: one workgroup and one partial per head for every kFusedBlocks
+  // key blocks, then f_nstatic partials per head for the chunks of the static set
   int f_nranges, f_nstatic;
   // ratios of consecutive binomial terms, (L-j)/(j+1) (0 from j = L on): j = 0 .. kFastTau-1,
   // and j = tau .. tau+kTailTerms-1 (filled when tau <= kFastTau)

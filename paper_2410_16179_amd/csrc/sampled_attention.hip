@@ -227,8 +227,11 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
 // keys: 35 us against 25.6 + 13.7 us).  Shorter runs (4 or 8 blocks per workgroup) measured the
 // same kernel time but cost more partials and gather batches; the 141 registers of this form
 // (three wavefronts per SIMD) measured faster than the same kernel held to 128.
-// The first f_nstatic workgroups of a KV head take the static set T, kFusedStatic keys each.
-// One partial per (head, workgroup).
+// The grid is one workgroup per run (at 8 KV heads x 98304 keys: 768, exactly what is resident
+// at once; workgroups that start late end last).  The static set T is cut into chunks of
+// kFusedStatic keys; chunk c of the launch is taken, after its own run, by the c-th workgroup in
+// dispatch order: those finish their scan first and have the time.
+// One partial per (head, run) and per (head, static chunk).
 template <int KT, int WDT, int LT, bool FP32>
 __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
   constexpr int kIt = FP32 ? (kFusedIters + 1) / 2 : kFusedIters;   // the same registers per batch
@@ -236,23 +239,11 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
   __shared__ uint16_t lists[4][kFusedBlocks * kBlockKeys];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int unit = blockIdx.y, run = blockIdx.x;
+  const int nruns = gridDim.x;                             // = f_nranges - f_nstatic
   const int G = a.Hq / a.Hkv;
   const int64_t head0 = (int64_t)(unit / a.Hkv) * a.Hq + (int64_t)(unit % a.Hkv) * G;
-  if (run < a.f_nstatic) {
-    const int64_t first = (int64_t)run * kFusedStatic;
-    const int64_t left = a.n_static - first;
-    const int total = (int)(left < kFusedStatic ? left : kFusedStatic);
-    for (int h = wave; h < G; h += 4) {
-      HeadVectors<FP32> hv;
-      request_head_vectors<FP32>(a, unit, head0 + h, hv);
-      gather_estimate_wave<FP32, kIt>(a, unit, head0 + h, total, false, hv,
-                                              [&](int c) { return static_key(a, first + c); },
-                                              a.partial + ((head0 + h) * a.f_nranges + run) * kPartialStride);
-    }
-    return;
-  }
   const int64_t nblk = key_blocks(a.n);
-  const int64_t blk0 = (int64_t)(run - a.f_nstatic) * kFusedBlocks;
+  const int64_t blk0 = (int64_t)run * kFusedBlocks;
 #pragma unroll 1
   for (int j = 0; j < kFusedWaveBlocks; ++j) {
     const int bi = wave * kFusedWaveBlocks + j;
@@ -288,10 +279,26 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
     __builtin_amdgcn_wave_barrier();
     gather_estimate_wave<FP32, kIt>(a, unit, head0 + h, total, true, hv,
-                                            [&](int cc) { return blk0 * kBlockKeys + (int64_t)list[cc]; },
-                                            a.partial + ((head0 + h) * a.f_nranges + run) * kPartialStride);
+                                    [&](int cc) { return blk0 * kBlockKeys + (int64_t)list[cc]; },
+                                    a.partial + ((head0 + h) * a.f_nranges + run) * kPartialStride);
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
     __builtin_amdgcn_wave_barrier();
+  }
+  // ---- static chunks of the launch, dealt out in dispatch order ----
+  const int chunks = (int)gridDim.y * a.f_nstatic;
+  for (int c = (int)blockIdx.y * nruns + run; c < chunks; c += nruns * (int)gridDim.y) {
+    const int su = c / a.f_nstatic, sc = c % a.f_nstatic;
+    const int64_t shead0 = (int64_t)(su / a.Hkv) * a.Hq + (int64_t)(su % a.Hkv) * G;
+    const int64_t first = (int64_t)sc * kFusedStatic;
+    const int64_t left = a.n_static - first;
+    const int total = (int)(left < kFusedStatic ? left : kFusedStatic);
+    for (int h = wave; h < G; h += 4) {
+      HeadVectors<FP32> hv;
+      request_head_vectors<FP32>(a, su, shead0 + h, hv);
+      gather_estimate_wave<FP32, kIt>(a, su, shead0 + h, total, false, hv,
+                                      [&](int cc) { return static_key(a, first + cc); },
+                                      a.partial + ((shead0 + h) * a.f_nranges + nruns + sc) * kPartialStride);
+    }
   }
 }
 
@@ -398,7 +405,7 @@ static hipError_t launch_merge(const AttnArgs& a, int64_t heads, hipStream_t s, 
 }
 
 static hipError_t launch_scan_gather(const AttnArgs& a, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
-  const dim3 block(256), grid((unsigned)a.f_nranges, (unsigned)(a.B * a.Hkv));
+  const dim3 block(256), grid((unsigned)(a.f_nranges - a.f_nstatic), (unsigned)(a.B * a.Hkv));
 #define MP_TUNED(KT, LL)                                                                            \
   if (a.K == KT && a.L == LL) {                                                                     \
     if (a.is_fp32)                                                                                  \
