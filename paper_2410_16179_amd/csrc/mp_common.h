@@ -126,7 +126,7 @@ struct AttnArgs {
   int64_t n_static;          // keys in the static set T
   // scan and gather in one launch: one workgroup and one partial per head for every kFusedBlocks
   // key blocks, then f_nstatic partials per head for the chunks of the static set
-  int f_nranges, f_nstatic;
+  int f_nranges, f_nstatic, f_wave_blocks;   // f_wave_blocks: key blocks per wavefront (1, 2, 4)
   // ratios of consecutive binomial terms, (L-j)/(j+1) (0 from j = L on): j = 0 .. kFastTau-1,
   // and j = tau .. tau+kTailTerms-1 (filled when tau <= kFastTau)
   float head_ratio[kFastTau], tail_ratio[kTailTerms];
@@ -152,8 +152,9 @@ constexpr int kPartialStride = 132;   // 128 output elements, running max, runni
 constexpr int kRangeBlocks = 16;      // key blocks per gather wavefront (1024 keys)
 constexpr int kStaticPerRange = 32;   // static (sink / local) keys per gather wavefront
 // the one-launch scan + gather: four wavefronts per workgroup
-constexpr int kFusedWaveBlocks = 4;           // key blocks a wavefront scans, one after the other
-constexpr int kFusedBlocks = 4 * kFusedWaveBlocks;        // key blocks per workgroup
+constexpr int kFusedWaveBlocks = 4;           // most key blocks a wavefront scans, one after the other
+constexpr int kFusedBlocks = 4 * kFusedWaveBlocks;        // most key blocks per workgroup
+constexpr int kFusedFill = 768;               // workgroups of it that are resident at once (3 per compute unit)
 constexpr int kFusedIters = 8;             // its gather batch: rows per quarter wavefront
 constexpr int kFusedStatic = 4 * kFusedIters;             // static keys per workgroup and head there
 

@@ -217,16 +217,18 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
 }
 
 // Scan and gather in one launch (the whole context is scanned, no hash tables): a workgroup of
-// four wavefronts compares kFusedBlocks = 16 consecutive code blocks with the G heads' codes
-// (scan_blocks, four blocks per wavefront one after the other), leaves the ballots in LDS, and
-// wavefront h then gathers and weighs the keys that head h samples from these 1024 keys (about
-// 17 at a sampling rate of 1.6 %: one batch of the 32-row gather).  As separate launches the
-// gather follows the scan with two dependent round trips of its own (ballots, then rows) on an
-// idle memory system; here the rows of one workgroup travel while the others still stream
-// codes, and only the gather of the last workgroups is exposed (measured at 32 heads x 98304
-// keys: 35 us against 25.6 + 13.7 us).  Shorter runs (4 or 8 blocks per workgroup) measured the
-// same kernel time but cost more partials and gather batches; the 141 registers of this form
-// (three wavefronts per SIMD) measured faster than the same kernel held to 128.
+// four wavefronts compares a run of up to kFusedBlocks = 16 consecutive code blocks with the G
+// heads' codes (scan_blocks, f_wave_blocks blocks per wavefront one after the other), leaves the
+// ballots in LDS, and wavefront h then gathers and weighs the keys that head h samples from the
+// run (16 blocks: about 17 at a sampling rate of 1.6 %, one batch of the 32-row gather).  As
+// separate launches the gather follows the scan with two dependent round trips of its own
+// (ballots, then rows) on an idle memory system; here the rows of one workgroup travel while
+// the others still stream codes, and only the gather of the last workgroups is exposed
+// (measured at 32 heads x 98304 keys: 33 us against 25.6 + 13.7 us).  The host picks the run
+// length: 16 blocks when that still gives the chip its 768 workgroups, 8 or 4 for shorter
+// contexts.  At the long-context shapes shorter runs measured the same kernel time but cost
+// more partials and gather batches; the 142 registers of this form (three wavefronts per SIMD)
+// measured faster than the same kernel held to 128.
 // The grid is one workgroup per run (at 8 KV heads x 98304 keys: 768, exactly what is resident
 // at once; workgroups that start late end last).  The static set T is cut into chunks of
 // kFusedStatic keys; chunk c of the launch is taken, after its own run, by the c-th workgroup in
@@ -243,10 +245,12 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
   const int G = a.Hq / a.Hkv;
   const int64_t head0 = (int64_t)(unit / a.Hkv) * a.Hq + (int64_t)(unit % a.Hkv) * G;
   const int64_t nblk = key_blocks(a.n);
-  const int64_t blk0 = (int64_t)run * kFusedBlocks;
+  const int wave_blocks = a.f_wave_blocks;                 // 1, 2 or 4: key blocks per wavefront
+  const int run_blocks = 4 * wave_blocks;
+  const int64_t blk0 = (int64_t)run * run_blocks;
 #pragma unroll 1
-  for (int j = 0; j < kFusedWaveBlocks; ++j) {
-    const int bi = wave * kFusedWaveBlocks + j;
+  for (int j = 0; j < wave_blocks; ++j) {
+    const int bi = wave * wave_blocks + j;
     if (blk0 + bi < nblk) {
       scan_blocks<KT, WDT, LT, 1>(a, unit, blk0 + bi, lane, [&](int h, int64_t, uint64_t m) {
         if (lane == 0) smask[h][bi] = m;
@@ -261,7 +265,7 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
     HeadVectors<FP32> hv;
     request_head_vectors<FP32>(a, unit, head0 + h, hv);
     // ---- the ballots of head h as an index list (wavefront prefix sum) ----
-    uint64_t m = lane < kFusedBlocks ? smask[h][lane] : 0;
+    uint64_t m = lane < run_blocks ? smask[h][lane] : 0;
     const int c = __popcll(m);
     int incl = c;
 #pragma unroll
