@@ -213,9 +213,9 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   // n roundings of relative size 2^-24 at most (n = 128 terms, 257 with a centering vector) give
   // |sum32 - exact| <= n 2^-24 (1 + small) * sum|terms|, plus what underflowing products lose,
   // far below the absolute floor: a result beyond kClose32 times the float32 magnitude sum
-  // (itself low by at most the same relative amount) has the exact sign.  Only wavefronts with
-  // a closer result in some column (about one in a thousand) repeat their columns in float64,
-  // where every product of two float32 values is exact.
+  // (itself low by at most the same relative amount) has the exact sign.  The few columns with
+  // a closer result (about one in ten thousand) are redone in float64, where every product of
+  // two float32 values is exact.
   const float kClose32 = with_mu ? 1.6e-5f : 8.0e-6f;
   float s32[2] = {0.f, 0.f}, m32[2] = {0.f, 0.f};
 #pragma unroll
@@ -238,29 +238,46 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   const bool close0 = !(fabsf(s32[0]) > kClose32 * m32[0] + 1e-30f);
   const bool close1 = !with_mu && nrow > 1 && !(fabsf(s32[1]) > kClose32 * m32[1] + 1e-30f);
   double s[2] = {(double)s32[0], (double)s32[1]}, mag[2] = {0.0, 0.0};
-  if (__ballot(col_ok && (close0 || close1))) {
-    // (a wavefront pays for the repeat whether one lane or all need it, so it is kept short:
-    // sixteen elements at a time, nothing hoisted, few registers)
-    s[0] = 0.0; s[1] = 0.0;
+  // The few close columns of a wavefront are redone one at a time by the whole wavefront: the
+  // owning lane hands its column over through LDS, every lane forms the exact float64 products
+  // of its two (four) terms, and a butterfly adds them up: at most nine roundings of 2^-53
+  // relative to the magnitude sum, far inside the slack the final test allows.
+  __shared__ float4 scol[8][kHeadDim / 4];
+  uint64_t redo = __ballot(col_ok && (close0 || close1));
+  while (redo) {
+    const int src = __ffsll((unsigned long long)redo) - 1;
+    redo &= redo - 1;
+    if (lane == src) {
 #pragma unroll
-    for (int i4 = 0; i4 < kHeadDim / 4; ++i4) {
-      const float4 x0 = sx[0][i4], x1 = sx[1][i4];
-      const double xa[4] = {(double)x0.x, (double)x0.y, (double)x0.z, (double)x0.w};
-      const double xc[4] = {(double)x1.x, (double)x1.y, (double)x1.z, (double)x1.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const double wv = (double)wf[i4 * 4 + e];
-        s[0] = fma(xa[e], wv, s[0]);                     // exact product, one rounding per term
-        mag[0] = fma(fabs(xa[e]), fabs(wv), mag[0]);
-        s[1] = fma(xc[e], wv, s[1]);
-        mag[1] = fma(fabs(xc[e]), fabs(wv), mag[1]);
-      }
-      if ((i4 & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+      for (int i4 = 0; i4 < kHeadDim / 4; ++i4)
+        scol[wave][i4] = make_float4(wf[4 * i4], wf[4 * i4 + 1], wf[4 * i4 + 2], wf[4 * i4 + 3]);
     }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    const float* cf = reinterpret_cast<const float*>(scol[wave]);
+    const float* xf = reinterpret_cast<const float*>(sx);
+    const double w0 = (double)cf[lane], w1 = (double)cf[lane + 64];
+    const double p00 = (double)xf[lane] * w0, p01 = (double)xf[lane + 64] * w1;                        // exact
+    const double p10 = (double)xf[kHeadDim + lane] * w0, p11 = (double)xf[kHeadDim + lane + 64] * w1;  // exact
+    double t0 = p00 + p01, g0 = fabs(p00) + fabs(p01);
+    double t1 = p10 + p11, g1 = fabs(p10) + fabs(p11);
     if (with_mu) {
-      s[0] += s[1];
-      mag[0] += mag[1];
+      t0 += t1;
+      g0 += g1;
     }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      t0 += __shfl_xor(t0, o);
+      g0 += __shfl_xor(g0, o);
+      t1 += __shfl_xor(t1, o);
+      g1 += __shfl_xor(g1, o);
+    }
+    if (lane == src) {
+      s[0] = t0; mag[0] = g0;
+      s[1] = t1; mag[1] = g1;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
   }
   for (int rr = 0; rr < nrow; ++rr) {
     bool bit = s[rr] >= 0.0;
