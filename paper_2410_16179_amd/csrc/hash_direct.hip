@@ -190,6 +190,7 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   // The two vectors (or the vector and its centering vector) are staged once in LDS as float32
   // and read back as broadcasts: every thread needs all 128 elements of both.
   __shared__ float4 sx[2][kHeadDim / 4];
+  __shared__ float sxnorm[2];
   {
     const int rr = (tid >> 5) & 1, i4 = tid & 31;         // threads 0..63: four elements each
     if (tid < 64) {
@@ -205,19 +206,25 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
                         __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xffff0000u));
       }
       sx[rr][i4] = v;
+      // Euclidean norm of the staged vector (32 lanes hold one vector)
+      float q2 = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, v.w * v.w)));
+#pragma unroll
+      for (int o = 16; o >= 1; o >>= 1) q2 += __shfl_xor(q2, o);
+      if (i4 == 0) sxnorm[rr] = __builtin_sqrtf(q2);
     }
   }
   __syncthreads();
   const bool with_mu = a.mu != nullptr;                  // then there is one vector: x.w - mu.w
-  // First a float32 pass: sum and sum of magnitudes by one fused multiply-add each per term.
-  // n roundings of relative size 2^-24 at most (n = 128 terms, 257 with a centering vector) give
-  // |sum32 - exact| <= n 2^-24 (1 + small) * sum|terms|, plus what underflowing products lose,
-  // far below the absolute floor: a result beyond kClose32 times the float32 magnitude sum
-  // (itself low by at most the same relative amount) has the exact sign.  The few columns with
-  // a closer result (about one in ten thousand) are redone in float64, where every product of
-  // two float32 values is exact.
+  // First a float32 pass: one fused multiply-add per term.  n roundings of relative size 2^-24
+  // at most (n = 128 terms, 257 with a centering vector) give |sum32 - exact| <= n 2^-24 (1 +
+  // small) * sum|terms| <= that factor * |x| |w| (Cauchy-Schwarz; with a centering vector
+  // (|x| + |mu|) |w|), plus what underflowing products lose, far below the absolute floor.  The
+  // norms are float32 sums of squares (relative error below 1e-5, inside the margin of kClose32
+  // over the factor): a result beyond kClose32 |x| |w| has the exact sign.  The few columns with
+  // a closer result (a few in ten thousand) are redone in float64, where every product of two
+  // float32 values is exact.
   const float kClose32 = with_mu ? 1.6e-5f : 8.0e-6f;
-  float s32[2] = {0.f, 0.f}, m32[2] = {0.f, 0.f};
+  float s32[2] = {0.f, 0.f}, w2 = 0.f;
 #pragma unroll
   for (int i4 = 0; i4 < kHeadDim / 4; ++i4) {
     const float4 x0 = sx[0][i4], x1 = sx[1][i4];
@@ -226,11 +233,12 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
     for (int e = 0; e < 4; ++e) {
       const float wv = wf[i4 * 4 + e];
       s32[0] = fmaf(xa[e], wv, s32[0]);
-      m32[0] = fmaf(fabsf(xa[e]), fabsf(wv), m32[0]);
       s32[1] = fmaf(xc[e], wv, s32[1]);
-      m32[1] = fmaf(fabsf(xc[e]), fabsf(wv), m32[1]);
+      w2 = fmaf(wv, wv, w2);
     }
   }
+  const float wnorm = __builtin_sqrtf(w2);
+  float m32[2] = {sxnorm[0] * wnorm, sxnorm[1] * wnorm};
   if (with_mu) {
     s32[0] += s32[1];                                    // one more rounding, inside the factor
     m32[0] += m32[1];
@@ -305,8 +313,8 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   for (int p0 = 0; p0 < items; p0 += 512) {
     const int p = p0 + tid;
     const bool on = p < items;
-    const int row = on ? p / (a.K * 32) : 0;
-    const int rem = on ? p % (a.K * 32) : 0;
+    const int row = on && p >= a.K * 32 ? 1 : 0;          // at most two rows
+    const int rem = on ? p - row * (a.K * 32) : 0;
     const int pb = rem >> 5, beta = rem & 31;
     const bool v = on && sbit[row][beta * a.K + pb];
     const uint64_t m = __ballot(v);
