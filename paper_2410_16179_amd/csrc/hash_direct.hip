@@ -1,9 +1,10 @@
-// Direct SimHash coding in float64 with an exact fallback (Sec. 2.2; Algorithm 1 "Encode").
+// Direct SimHash coding with an exact fallback (Sec. 2.2; Algorithm 1 "Encode").
 //
 // Used for the decode queries (a few thousand projections), for float32 inputs, and as the
-// reference-accurate path for bf16 keys when the matrix-core kernel cannot be used.  Every
-// projection is accumulated in float64 from exact products; results inside the float64
-// error bound are re-summed exactly (exact_dot.h), so the bits do not depend on
+// reference-accurate path for bf16 keys when the matrix-core kernel cannot be used.  A
+// projection is accumulated in float64 from exact products (hash_rows_kernel: in float32
+// first, float64 only where the float32 error bound leaves the sign open); results inside
+// the float64 error bound are re-summed exactly (exact_dot.h), so the bits do not depend on
 // summation order.
 #include <type_traits>
 #include "mp_common.h"
@@ -144,9 +145,10 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
 
 // Coding of a few vectors: the queries of a decode step (Algorithm 1 "Encode(q, W)") or the
 // keys appended to the cache since the last call.  One workgroup codes two vectors against the
-// 32*K projector columns of one table word.  Thread = column, so the 128 loads of a column
-// are coalesced across the workgroup and all in flight at once; the two vectors (and the
-// centering vectors of their units) are wave-uniform scalar loads.  Sign bits go through LDS
+// 32*K projector columns of one table word (one vector when it has a centering vector).
+// Thread = column, so the 128 loads of a column are coalesced across the workgroup and all in
+// flight at once; the vectors are staged in LDS and read back as broadcasts.  Sign bits go
+// through LDS
 // to be regrouped from column order (table-major) into the bit-plane words of the code layout.
 // A launch takes two sets of vectors (the first `pairs0` rows of the grid code a0's, the rest
 // a1's), so that a decode step codes its queries and its new keys together.
