@@ -42,3 +42,13 @@ def test_c5_one_sequence_group_of_eight(oracle):
     w = wl.scaled(wl.CONFIGS["C5"], batch=1)
     heads = [(0, h) for h in range(8, 16)]
     run_case(oracle, w, heads=heads, oracle_codes_too=False)
+
+
+def test_c3_ragged_context_in_a_larger_cache(oracle):
+    # the benchmark shape with a context that ends inside a code block and inside a run of 16
+    # blocks (the last workgroup of a KV head scans 11 blocks and a part of the 12th), in a
+    # cache with spare capacity; the last KV head, all four of its query heads
+    w = wl.scaled(wl.CONFIGS["C3"], n_ctx=98304 - 4 * 64 - 37)
+    heads = [(0, h) for h in (28, 29, 30, 31)]
+    ref, res, worst = run_case(oracle, w, heads=heads, n_cap=98304, oracle_codes_too=False)
+    assert np.isfinite(res["out"]).all()
