@@ -105,6 +105,110 @@ __device__ inline void load_code_block(const uint32_t* blkp, int lane, uint32_t 
   }
 }
 
+// Reports the keys of block `blk` that query head `head` samples (lane = key, cnt = its number
+// of colliding tables): the ballot of the sampled keys, plus the optional debug outputs.
+__device__ inline uint64_t report_block(const AttnArgs& a, int64_t head, int64_t blk, int lane, uint32_t cnt) {
+  const int64_t i = blk * kBlockKeys + lane;
+  const bool valid = i < a.n;
+  const bool in_T = i < a.n_sink || i >= a.n - a.n_local;
+  const bool hit = valid && !in_T && (a.tau <= 0 || (int)cnt >= a.tau);
+  const uint64_t m = __ballot(hit);
+  if (a.dbg_counts && valid) a.dbg_counts[head * a.n + i] = (uint16_t)cnt;
+  if (a.dbg_cand && hit) {
+    const int pos = atomicAdd(&a.dbg_ncand[head], 1);
+    if (pos < a.dbg_cand_cap) a.dbg_cand[head * a.dbg_cand_cap + pos] = (int32_t)i;
+  }
+  return m;
+}
+
+// One wavefront compares BPW consecutive 64-key code blocks (lane = key) of KV unit `unit`,
+// starting at block blk0 < key_blocks(n), with the codes of the query heads h_begin .. h_end-1
+// of the unit's G, and hands emit(h, blk, ballot) the sampled keys of every (head, block).
+// KT, WDT, LT: compile-time K, ceil(L/32) and tables in the last group for the tuned
+// instantiations, 0 for the generic one.
+// BPW: all code words of the blocks are requested before the first comparison, and each
+// scalar-loaded query word serves BPW keys per lane.
+template <int KT, int WDT, int LT, int BPW, class Emit>
+__device__ inline void scan_blocks(const AttnArgs& a, int unit, int64_t blk0, int lane, int h_begin, int h_end, Emit emit) {
+  constexpr bool kGeneric = (KT == 0);
+  const int64_t nblk = key_blocks(a.n);
+  const int G = a.Hq / a.Hkv;
+  const int K = kGeneric ? a.K : KT;
+  const int Wd = kGeneric ? a.Wd : WDT;
+  const int NQ = K * Wd;                                 // plane words of a query code
+  constexpr int kTailWords = kGeneric ? 0 : (KT * LT + 31) / 32;
+  constexpr int kNWT = kGeneric ? 1 : KT * (WDT - 1) + kTailWords;   // words of a key code
+  const int NW = kGeneric ? a.NW : kNWT;
+  const int64_t head0 = (int64_t)(unit / a.Hkv) * a.Hq + (int64_t)(unit % a.Hkv) * G;
+  // Query codes are wave-uniform and constant during the kernel: read through the constant
+  // address space they are scalar loads into SGPRs and feed the bit operations directly.
+  const const_u32_ptr qc = (const_u32_ptr)(a.qcodes + head0 * NQ);
+  const uint32_t* blkp = a.kcodes + ((int64_t)unit * a.blocks_cap + blk0) * (kBlockKeys * (int64_t)NW);
+
+  [[maybe_unused]] uint32_t kw[BPW][kNWT];
+  // the planes of the last table group, taken out of their bit string once per key
+  [[maybe_unused]] uint32_t kt[BPW][kGeneric ? 1 : KT];
+  if constexpr (!kGeneric) {
+#pragma unroll
+    for (int j = 0; j < BPW; ++j) {
+      if (blk0 + j < nblk) load_code_block<kNWT>(blkp + j * (kBlockKeys * (int64_t)NW), lane, kw[j]);
+#pragma unroll
+      for (int p = 0; p < KT; ++p) {
+        constexpr int xs = KT * (WDT - 1);
+        const int off = p * LT, wi = xs + off / 32, sh = off % 32;
+        if (sh == 0) kt[j][p] = kw[j][wi];
+        else if (sh + LT <= 32) kt[j][p] = kw[j][wi] >> sh;
+        else kt[j][p] = __builtin_amdgcn_alignbit(kw[j][wi + 1], kw[j][wi], sh);
+      }
+    }
+  }
+
+#pragma unroll 1
+  for (int h = h_begin; h < h_end; ++h) {
+    const const_u32_ptr qh = qc + h * NQ;
+    uint32_t cnt[BPW];
+#pragma unroll
+    for (int j = 0; j < BPW; ++j) cnt[j] = 0;
+    if constexpr (!kGeneric) {
+#pragma unroll
+      for (int w = 0; w < WDT; ++w) {
+        const bool tail = w == WDT - 1;
+        uint32_t same[BPW];
+#pragma unroll
+        for (int j = 0; j < BPW; ++j) same[j] = ~((tail ? kt[j][0] : kw[j][w * KT]) ^ qh[w * KT]);
+#pragma unroll
+        for (int p = 1; p < KT; ++p) {
+#pragma unroll
+          for (int j = 0; j < BPW; ++j)
+            same[j] &= ~((tail ? kt[j][p] : kw[j][w * KT + p]) ^ qh[w * KT + p]);   // one 3-input op
+        }
+        // beyond the real tables of the last group the key planes hold bits of the next plane
+        if (tail && LT < 32) {
+#pragma unroll
+          for (int j = 0; j < BPW; ++j) same[j] &= (1u << (LT & 31)) - 1u;
+        }
+#pragma unroll
+        for (int j = 0; j < BPW; ++j) cnt[j] += __popc(same[j]);
+      }
+    } else {
+      for (int w = 0; w < Wd; ++w) {
+        uint32_t same = ~0u;
+        for (int p = 0; p < K; ++p) {
+          const int x = w * K + p;
+          same &= ~(load_plane_word(blkp, NW, K, a.L, x, lane) ^ qh[x]);
+        }
+        if (w == Wd - 1 && (a.L & 31)) same &= (1u << (a.L & 31)) - 1u;
+        cnt[0] += __popc(same);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < BPW; ++j) {
+      const int64_t blk = blk0 + j;
+      if (blk < nblk) emit(h, blk, report_block(a, head0 + h, blk, lane, cnt[j]));
+    }
+  }
+}
+
 // j-th key of the static set T: the sink keys, then the local window (every key when the
 // context is no longer than n_sink + n_local).
 __device__ inline int64_t static_key(const AttnArgs& a, int64_t j) {

@@ -14,10 +14,15 @@
 //   the 4-byte stores to a bucket come close together in time and combine into whole lines in
 //   L2 (the one-pass scatter keeps thousands of lines half written per workgroup and writes
 //   each store to HBM on its own).
-//   table_lookup_kernel   : one workgroup per (query head, run of 32768 keys): reads the L
-//       buckets, counts hits per key in LDS byte counters, and emits the same 64-bit ballots
-//       (count >= min_hits, key not static) that collision_scan_kernel emits, so the gather
-//       and merge kernels are shared by both retrieval forms.
+//   lookup_gather_kernel  : the decode step's retrieval for min_hits 1 or 2: one workgroup per
+//       (query head, slice of 12288 keys) reads the L buckets, marks the keys of its slice in
+//       LDS bitmaps and gathers and weighs them right away; the few keys appended since the
+//       build are found by the collision scan in the same workgroups.
+//   table_lookup_kernel, table_lookup_bitmap_kernel: the lookup alone (hit counts per key in
+//       LDS byte counters, or seen / seen-twice bitmaps): they emit the same 64-bit ballots
+//       (count >= min_hits, key not static) that collision_scan_kernel emits, for the separate
+//       gather and merge kernels; used for the count output, other min_hits, and when more
+//       keys were appended than the one-launch form takes.
 #include "attention_common.h"
 #include <hip/hip_ext.h>
 
@@ -402,6 +407,177 @@ hipError_t launch_build_tables(const TableArgs& t, hipStream_t s) {
   } else {
     hipLaunchKernelGGL(ht_build_kernel<true>, grid, dim3(256), lds, s, t);
   }
+  return hipGetLastError();
+}
+
+// Lookup and gather in one launch for min_hits 1 or 2: a workgroup of 16 wavefronts per (query
+// head, slice of kLgSliceBlocks key blocks of the indexed range).  It reads the L buckets of the
+// head like table_lookup_bitmap_kernel (every slice of a head reads them all: 58 KB at 96k keys,
+// served by L2 after the first), marks only the keys of its slice in the "seen" / "seen twice"
+// bitmaps in LDS, and wavefront v then expands the bits of its kLgWaveBlocks blocks into an index
+// list and gathers and weighs those keys (gather_estimate_wave) without the ballots ever leaving
+// the compute unit: one partial per (head, slice, wavefront).  The chunks of the static set T
+// (kStaticPerRange keys) are taken by wavefront 0 of slice 0, 1, ... of the same head.  The keys
+// appended since the build, 16 code blocks per slice, are found by the collision scan in the
+// workgroups of slice 0, 1, ... and join the gather batches there.
+// KT, WDT, LT: the collision scan's compile-time K, ceil(L/32) and tables of the last group (0: any).
+template <int KT, int WDT, int LT, bool FP32>
+__global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableArgs tb) {
+  constexpr int kSliceWords = kLgSliceBlocks * 2;       // 32-key words of a slice
+  constexpr int kWaveWords = kLgWaveBlocks * 2;
+  __shared__ uint32_t seen[kSliceWords], twice[kSliceWords];
+  __shared__ uint32_t bstart[512], blen[512];
+  __shared__ uint32_t qs[256];
+  __shared__ uint16_t lists[16][kLgWaveBlocks * kBlockKeys + kBlockKeys];
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int slice = blockIdx.x;
+  const int64_t bh = blockIdx.y;
+  const int G = a.Hq / a.Hkv;
+  const int unit = (int)((bh / a.Hq) * a.Hkv + (bh % a.Hq) / G);
+  // ---- keys appended since the build: run `slice` of 16 of their code blocks, one per
+  // wavefront, compared with this head's code (requested first: the codes travel while the
+  // buckets are looked up); the wavefront gathers what its block samples with its own batch ----
+  uint64_t app_mask = 0;
+  const int64_t app_blk = a.blk_begin + (int64_t)slice * 16 + wave;
+  if (slice < a.lg_app_runs && app_blk < key_blocks(a.n)) {
+    const int hg = (int)(bh % a.Hq) % G;
+    scan_blocks<KT, WDT, LT, 1>(a, unit, app_blk, lane, hg, hg + 1, [&](int, int64_t, uint64_t m) { app_mask = m; });
+  }
+  const int nb = 1 << a.K;
+  const uint32_t* offs = tb.offsets + (int64_t)unit * a.L * (nb + 1);
+  const uint32_t* idxs = tb.indices + (int64_t)unit * a.L * tb.n_cap;
+  const uint32_t key_lo = (uint32_t)slice * (kLgSliceBlocks * kBlockKeys);
+  for (int i = tid; i < kSliceWords; i += 1024) { seen[i] = 0u; twice[i] = 0u; }
+  if (tid < a.NQ) qs[tid] = a.qcodes[bh * a.NQ + tid];
+  __syncthreads();
+  for (int t = tid; t < a.L; t += 1024) {
+    const uint32_t* qw = qs + (t >> 5) * a.K;
+    uint32_t code = 0;
+    for (int b = 0; b < a.K; ++b) code |= ((qw[b] >> (t & 31)) & 1u) << b;
+    const uint32_t s0 = offs[(int64_t)t * (nb + 1) + code], s1 = offs[(int64_t)t * (nb + 1) + code + 1];
+    bstart[t] = s0;
+    blen[t] = s1 - s0;
+  }
+  __syncthreads();
+  // wavefront v reads tables v, v+16, ...: up to 128 entries of each bucket are requested before
+  // any is used; longer buckets are finished in a loop
+  {
+    constexpr int kMaxB = 32;                           // L <= 512 tables over 16 wavefronts
+    uint32_t e0[kMaxB], e1[kMaxB];
+    const int nbk = (a.L - wave + 15) >> 4;
+#pragma unroll
+    for (int k = 0; k < kMaxB; ++k) {
+      e0[k] = 0xffffffffu; e1[k] = 0xffffffffu;
+      if (k < nbk) {
+        const int t = wave + 16 * k;
+        const uint32_t len = blen[t];
+        const uint32_t* p = idxs + (int64_t)t * tb.n_cap + bstart[t];
+        if ((uint32_t)lane < len) e0[k] = p[lane];
+        if ((uint32_t)lane + 64 < len) e1[k] = p[lane + 64];
+      }
+    }
+    auto mark = [&](uint32_t key) {
+      const uint32_t rel = key - key_lo;                // absent entries and other slices: out of range
+      if (rel < (uint32_t)(kLgSliceBlocks * kBlockKeys)) {
+        const uint32_t bit = 1u << (rel & 31);
+        if (atomicOr(&seen[rel >> 5], bit) & bit) atomicOr(&twice[rel >> 5], bit);
+      }
+    };
+#pragma unroll
+    for (int k = 0; k < kMaxB; ++k) {
+      if (k < nbk) {
+        mark(e0[k]);
+        mark(e1[k]);
+        const int t = wave + 16 * k;
+        if (blen[t] > 128) {
+          const uint32_t* p = idxs + (int64_t)t * tb.n_cap + bstart[t];
+          for (uint32_t j = 128 + lane; j < blen[t]; j += 64) mark(p[j]);
+        }
+      }
+    }
+  }
+  __syncthreads();
+  // ---- gather: wavefront v takes blocks v*kLgWaveBlocks .. of the slice ----
+  const uint32_t* hit = a.tau >= 2 ? twice : seen;
+  const int64_t hi_key = a.n - a.n_local < tb.n ? a.n - a.n_local : tb.n;   // indexed, not in the local window
+  const int64_t wave_key0 = (int64_t)key_lo + (int64_t)wave * (kLgWaveBlocks * kBlockKeys);
+  uint16_t* list = lists[wave];
+  HeadVectors<FP32> hv;
+  request_head_vectors<FP32>(a, unit, bh, hv);
+  uint32_t bits = 0;
+  if (lane < kWaveWords) {
+    const int64_t kfirst = wave_key0 + (int64_t)lane * 32;
+    const int64_t lo = (a.n_sink > kfirst ? a.n_sink : kfirst) - kfirst;
+    const int64_t hi = (hi_key < kfirst + 32 ? hi_key : kfirst + 32) - kfirst;
+    uint32_t elig = 0;
+    if (hi > lo) elig = (hi - lo >= 32 ? 0xffffffffu : ((1u << (hi - lo)) - 1u)) << lo;
+    bits = hit[wave * kWaveWords + lane] & elig;
+  }
+  if (a.dbg_cand) {                                      // debug output only
+    for (uint32_t f = bits; f; f &= f - 1) {
+      const int pos = atomicAdd(&a.dbg_ncand[bh], 1);
+      if (pos < a.dbg_cand_cap)
+        a.dbg_cand[bh * a.dbg_cand_cap + pos] = (int32_t)(wave_key0 + lane * 32 + __ffs(f) - 1);
+    }
+  }
+  const int c = __popc(bits);
+  int incl = c;
+#pragma unroll
+  for (int o = 1; o < 32; o <<= 1) {
+    const int v = __shfl_up(incl, o);
+    if (lane >= o) incl += v;
+  }
+  const int in_slice = __shfl(incl, 31);                 // kWaveWords <= 32
+  int pos = incl - c;
+  for (uint32_t f = bits; f; f &= f - 1) list[pos++] = (uint16_t)(lane * 32 + __ffs(f) - 1);
+  // behind them the sampled keys of the wavefront's appended block (lane = key of the block)
+  if ((app_mask >> lane) & 1)
+    list[in_slice + __popcll(app_mask & ((1ull << lane) - 1ull))] = (uint16_t)lane;
+  const int total = in_slice + __popcll(app_mask);
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  gather_estimate_wave<FP32, (FP32 ? 4 : 8)>(a, unit, bh, total, true, hv,
+                                            [&](int cc) {
+                                              return (cc < in_slice ? wave_key0 : app_blk * kBlockKeys) + (int64_t)list[cc];
+                                            },
+                                            a.partial + (bh * a.nranges + slice * 16 + wave) * kPartialStride);
+  // ---- static chunks of this head ----
+  if (wave == 0) {
+    const int chunks = (int)((a.n_static + kStaticPerRange - 1) / kStaticPerRange);
+    for (int sc = slice; sc < chunks; sc += a.lg_nslices) {
+      const int64_t first = (int64_t)sc * kStaticPerRange;
+      const int64_t left = a.n_static - first;
+      const int stotal = (int)(left < kStaticPerRange ? left : kStaticPerRange);
+      gather_estimate_wave<FP32, (FP32 ? 4 : 8)>(a, unit, bh, stotal, false, hv,
+                                                [&](int cc) { return static_key(a, first + cc); },
+                                                a.partial + (bh * a.nranges + a.lg_nslices * 16 + sc) * kPartialStride);
+    }
+  }
+}
+
+template <int KT, int WDT, int LT>
+static void launch_lookup_gather_for(const AttnArgs& a, const TableArgs& t, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
+  if (a.is_fp32) {
+    if (start || stop) hipExtLaunchKernelGGL((lookup_gather_kernel<KT, WDT, LT, true>), grid, dim3(1024), 0, s, start, stop, 0, a, t);
+    else hipLaunchKernelGGL((lookup_gather_kernel<KT, WDT, LT, true>), grid, dim3(1024), 0, s, a, t);
+  } else {
+    if (start || stop) hipExtLaunchKernelGGL((lookup_gather_kernel<KT, WDT, LT, false>), grid, dim3(1024), 0, s, start, stop, 0, a, t);
+    else hipLaunchKernelGGL((lookup_gather_kernel<KT, WDT, LT, false>), grid, dim3(1024), 0, s, a, t);
+  }
+}
+
+hipError_t launch_lookup_gather(const AttnArgs& a0, const TableArgs& t, int nslices, int appended_runs, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
+  AttnArgs a = a0;
+  a.lg_nslices = nslices;
+  a.lg_app_runs = appended_runs;                       // <= nslices
+  const dim3 grid((unsigned)nslices, (unsigned)((int64_t)a.B * a.Hq));
+  // the scan of the appended keys has the same tuned forms as collision_scan_kernel
+  if (a.K == 10 && a.L == 150) launch_lookup_gather_for<10, 5, 22>(a, t, grid, s, start, stop);
+  else if (a.K == 9 && a.L == 120) launch_lookup_gather_for<9, 4, 24>(a, t, grid, s, start, stop);
+  else if (a.K == 10 && a.L == 170) launch_lookup_gather_for<10, 6, 10>(a, t, grid, s, start, stop);
+  else if (a.K == 8 && a.L == 75) launch_lookup_gather_for<8, 3, 11>(a, t, grid, s, start, stop);
+  else launch_lookup_gather_for<0, 0, 0>(a, t, grid, s, start, stop);
   return hipGetLastError();
 }
 

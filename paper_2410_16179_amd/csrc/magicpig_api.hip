@@ -93,7 +93,10 @@ AttnWs ws_attention_layout(const magicpig_params* p) {
   while (w.f_wave_blocks > 1 && units * ((nblk + 4 * w.f_wave_blocks - 1) / (4 * w.f_wave_blocks)) < mp::kFusedFill)
     w.f_wave_blocks /= 2;
   w.f_nranges = w.f_nstatic + (int)((nblk + 4 * w.f_wave_blocks - 1) / (4 * w.f_wave_blocks));
-  const size_t most = (size_t)(w.f_nranges > w.nranges ? w.f_nranges : w.nranges);
+  // lookup + gather in one launch: 16 partials per slice and the static chunks
+  const int lg = (int)((nblk + mp::kLgSliceBlocks - 1) / mp::kLgSliceBlocks) * 16 + (w.nranges - w.nscan);
+  size_t most = (size_t)(w.f_nranges > w.nranges ? w.f_nranges : w.nranges);
+  if ((size_t)lg > most) most = (size_t)lg;
   w.partial_off = 0;
   w.masks_off = align256(heads * most * mp::kPartialStride * sizeof(float));
   w.total = w.masks_off + align256(heads * (size_t)nblk * sizeof(uint64_t));

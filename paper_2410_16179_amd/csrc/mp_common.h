@@ -127,6 +127,9 @@ struct AttnArgs {
   // scan and gather in one launch: one workgroup and one partial per head for every kFusedBlocks
   // key blocks, then f_nstatic partials per head for the chunks of the static set
   int f_nranges, f_nstatic, f_wave_blocks;   // f_wave_blocks: key blocks per wavefront (1, 2, 4)
+  // lookup + gather in one launch: slices of the indexed range; the first lg_app_runs of them
+  // also take a run of 16 appended key blocks each
+  int lg_nslices, lg_app_runs;
   // ratios of consecutive binomial terms, (L-j)/(j+1) (0 from j = L on): j = 0 .. kFastTau-1,
   // and j = tau .. tau+kTailTerms-1 (filled when tau <= kFastTau)
   float head_ratio[kFastTau], tail_ratio[kTailTerms];
@@ -151,6 +154,8 @@ constexpr int kBuildWindow = 16384;   // keys one workgroup places into the buck
 constexpr int kPartialStride = 132;   // 128 output elements, running max, running sum, pad
 constexpr int kRangeBlocks = 16;      // key blocks per gather wavefront (1024 keys)
 constexpr int kStaticPerRange = 32;   // static (sink / local) keys per gather wavefront
+constexpr int kLgWaveBlocks = 12;     // lookup + gather in one launch: key blocks per wavefront,
+constexpr int kLgSliceBlocks = 16 * kLgWaveBlocks;   // and per workgroup (16 wavefronts)
 // the one-launch scan + gather: four wavefronts per workgroup
 constexpr int kFusedWaveBlocks = 4;           // most key blocks a wavefront scans, one after the other
 constexpr int kFusedBlocks = 4 * kFusedWaveBlocks;        // most key blocks per workgroup
@@ -166,6 +171,7 @@ hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s);
 hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, hipStream_t s, hipEvent_t const* stage_events);
 hipError_t launch_build_tables(const TableArgs& t, hipStream_t s);
 hipError_t launch_table_lookup(const AttnArgs& a, const TableArgs& t, hipStream_t s, hipEvent_t start, hipEvent_t stop);
+hipError_t launch_lookup_gather(const AttnArgs& a, const TableArgs& t, int nslices, int appended_runs, hipStream_t s, hipEvent_t start, hipEvent_t stop);
 
 
 }  // namespace mp

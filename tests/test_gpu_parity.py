@@ -88,9 +88,11 @@ def run_case(oracle, w: wl.Workload, seed=0, alpha=0.8, use_mu=True, n_cap=None,
         rt2 = s.attend(debug=False, tables=True)
         rt3 = s.attend(tables=True, with_counts=False)      # candidate lists from the production lookup
         for b, h in pairs:
-            np.testing.assert_array_equal(rt2["out"][b, h], rt["out"][b, h])
+            # (the production form looks up and gathers in one launch: other partial sums)
+            assert rel_err(rt2["out"][b, h][None], rt["out"][b, h][None]) <= 1e-5
+            assert rel_err(rt2["out"][b, h][None], ref["out"][b, h][None]) <= TOL
             np.testing.assert_array_equal(rt3["S"][b][h], ref["S"][b][h])
-            np.testing.assert_array_equal(rt3["out"][b, h], rt["out"][b, h])
+            np.testing.assert_array_equal(rt3["out"][b, h], rt2["out"][b, h])
         # tables over a prefix of the keys, the rest found by the scan of their codes
         for ni in indexed:
             s.build_tables(ni)
@@ -100,7 +102,8 @@ def run_case(oracle, w: wl.Workload, seed=0, alpha=0.8, use_mu=True, n_cap=None,
                 np.testing.assert_array_equal(rh["counts"][b, h], ref["counts"][b, h])
                 np.testing.assert_array_equal(rh["S"][b][h], ref["S"][b][h])
                 assert rel_err(rh["out"][b, h][None], res["out"][b, h][None]) <= 1e-5
-                np.testing.assert_array_equal(rh2["out"][b, h], rh["out"][b, h])
+                assert rel_err(rh2["out"][b, h][None], rh["out"][b, h][None]) <= 1e-5
+                assert rel_err(rh2["out"][b, h][None], ref["out"][b, h][None]) <= TOL
     if oracle_codes_too and heads is None:       # scan fed with the oracle's own codes
         s.upload_codes(np.concatenate([ref["key_codes"], np.zeros((w.batch, w.n_kv_heads, Kc.shape[2] - n, w.L), np.int32)], axis=2),
                        ref["q_codes"])
