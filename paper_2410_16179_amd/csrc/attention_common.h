@@ -216,6 +216,13 @@ __device__ inline int64_t static_key(const AttnArgs& a, int64_t j) {
   return j < sink_keys ? j : j + (a.n - a.n_local - a.n_sink);
 }
 
+// The static set dealt over `slots` gather wavefronts of a head: slot s takes the static keys
+// s, s + slots, s + 2 slots, ... (at long contexts at most one each), which ride along in the
+// batch of its sampled keys instead of costing batches of their own.
+__device__ inline int static_share(const AttnArgs& a, int slot, int slots) {
+  return slot < a.n_static ? (int)((a.n_static - slot + slots - 1) / slots) : 0;
+}
+
 // The query row and the centering vector of a wavefront's head, eight elements per lane (the
 // 16 lanes of a quarter wavefront hold a row).  Requested at the start of the kernel, so that
 // they travel together with the ballots instead of after them.
@@ -242,10 +249,10 @@ __device__ inline void request_head_vectors(const AttnArgs& a, int unit, int64_t
 // one 128-element row; all K and V rows of a batch (kIters rows per quarter wavefront) are
 // requested before any is used; q.k, q.(k-mu), |k-mu|^2 are reduced over the 16 lanes of a
 // row; the inclusion probability and the logit q.k/sqrt(d) - log u are evaluated once per key
-// (sampled keys only: static keys enter with u = 1); an online max/sum softmax accumulates the
-// weighted V rows.
+// (the first n_sampled keys only: the keys behind them, static ones, enter with u = 1); an
+// online max/sum softmax accumulates the weighted V rows.
 template <bool FP32, int kIters, class KeyOf>
-__device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t bh, int total, bool sampled,
+__device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t bh, int total, int n_sampled,
                                             const HeadVectors<FP32>& hv, KeyOf key_of, float* pp) {
   static_assert(kIters >= 1 && kIters <= 16, "one lane of a quarter wavefront per row of a batch");
   const int lane = threadIdx.x & 63;
@@ -328,7 +335,7 @@ __device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t
     float logit = -INFINITY;
     if (sl < kIters && my_ok) {
       logit = my_dq * a.scale;
-      if (sampled && a.tau > 0) {
+      if (base + 4 * sl + qd < n_sampled && a.tau > 0) {   // this lane's key: base + 4*sl + qd
         const float den = qnorm * sqrtf(my_nn);
         const float cosv = den > 0.f ? my_dc / den : 0.f;
         const float u = fmaxf(inclusion_probability(cosv, a), 1.17549435e-38f);

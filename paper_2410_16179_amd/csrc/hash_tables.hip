@@ -416,8 +416,8 @@ hipError_t launch_build_tables(const TableArgs& t, hipStream_t s) {
 // served by L2 after the first), marks only the keys of its slice in the "seen" / "seen twice"
 // bitmaps in LDS, and wavefront v then expands the bits of its kLgWaveBlocks blocks into an index
 // list and gathers and weighs those keys (gather_estimate_wave) without the ballots ever leaving
-// the compute unit: one partial per (head, slice, wavefront).  The chunks of the static set T
-// (kStaticPerRange keys) are taken by wavefront 0 of slice 0, 1, ... of the same head.  The keys
+// the compute unit: one partial per (head, slice, wavefront).  The keys of the static set T are
+// dealt over these wavefronts (key j to wavefront j mod their number) and join the batches.  The keys
 // appended since the build, 16 code blocks per slice, are found by the collision scan in the
 // workgroups of slice 0, 1, ... and join the gather batches there.
 // KT, WDT, LT: the collision scan's compile-time K, ceil(L/32) and tables of the last group (0: any).
@@ -435,21 +435,22 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
   const int64_t bh = blockIdx.y;
   const int G = a.Hq / a.Hkv;
   const int unit = (int)((bh / a.Hq) * a.Hkv + (bh % a.Hq) / G);
+  const int nb = 1 << a.K;
+  const uint32_t* offs = tb.offsets + (int64_t)unit * a.L * (nb + 1);
+  const uint32_t* idxs = tb.indices + (int64_t)unit * a.L * tb.n_cap;
+  const uint32_t key_lo = (uint32_t)slice * (kLgSliceBlocks * kBlockKeys);
+  const uint32_t qword = tid < a.NQ ? a.qcodes[bh * a.NQ + tid] : 0u;      // (requested, not yet used)
+  for (int i = tid; i < kSliceWords; i += 1024) { seen[i] = 0u; twice[i] = 0u; }
   // ---- keys appended since the build: run `slice` of 16 of their code blocks, one per
-  // wavefront, compared with this head's code (requested first: the codes travel while the
-  // buckets are looked up); the wavefront gathers what its block samples with its own batch ----
+  // wavefront, compared with this head's code while the query code is on its way; the
+  // wavefront gathers what its block samples with its own batch ----
   uint64_t app_mask = 0;
   const int64_t app_blk = a.blk_begin + (int64_t)slice * 16 + wave;
   if (slice < a.lg_app_runs && app_blk < key_blocks(a.n)) {
     const int hg = (int)(bh % a.Hq) % G;
     scan_blocks<KT, WDT, LT, 1>(a, unit, app_blk, lane, hg, hg + 1, [&](int, int64_t, uint64_t m) { app_mask = m; });
   }
-  const int nb = 1 << a.K;
-  const uint32_t* offs = tb.offsets + (int64_t)unit * a.L * (nb + 1);
-  const uint32_t* idxs = tb.indices + (int64_t)unit * a.L * tb.n_cap;
-  const uint32_t key_lo = (uint32_t)slice * (kLgSliceBlocks * kBlockKeys);
-  for (int i = tid; i < kSliceWords; i += 1024) { seen[i] = 0u; twice[i] = 0u; }
-  if (tid < a.NQ) qs[tid] = a.qcodes[bh * a.NQ + tid];
+  if (tid < a.NQ) qs[tid] = qword;
   __syncthreads();
   for (int t = tid; t < a.L; t += 1024) {
     const uint32_t* qw = qs + (t >> 5) * a.K;
@@ -534,26 +535,18 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
   // behind them the sampled keys of the wavefront's appended block (lane = key of the block)
   if ((app_mask >> lane) & 1)
     list[in_slice + __popcll(app_mask & ((1ull << lane) - 1ull))] = (uint16_t)lane;
-  const int total = in_slice + __popcll(app_mask);
+  const int n_sampled = in_slice + __popcll(app_mask);
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
   __builtin_amdgcn_wave_barrier();
-  gather_estimate_wave<FP32, (FP32 ? 4 : 8)>(a, unit, bh, total, true, hv,
+  // static keys slot, slot + slots, ... ride along behind the sampled ones
+  const int slots = a.lg_nslices * 16, slot = slice * 16 + wave;
+  const int nst = static_share(a, slot, slots);
+  gather_estimate_wave<FP32, (FP32 ? 4 : 8)>(a, unit, bh, n_sampled + nst, n_sampled, hv,
                                             [&](int cc) {
+                                              if (cc >= n_sampled) return static_key(a, slot + (int64_t)(cc - n_sampled) * slots);
                                               return (cc < in_slice ? wave_key0 : app_blk * kBlockKeys) + (int64_t)list[cc];
                                             },
-                                            a.partial + (bh * a.nranges + slice * 16 + wave) * kPartialStride);
-  // ---- static chunks of this head ----
-  if (wave == 0) {
-    const int chunks = (int)((a.n_static + kStaticPerRange - 1) / kStaticPerRange);
-    for (int sc = slice; sc < chunks; sc += a.lg_nslices) {
-      const int64_t first = (int64_t)sc * kStaticPerRange;
-      const int64_t left = a.n_static - first;
-      const int stotal = (int)(left < kStaticPerRange ? left : kStaticPerRange);
-      gather_estimate_wave<FP32, (FP32 ? 4 : 8)>(a, unit, bh, stotal, false, hv,
-                                                [&](int cc) { return static_key(a, first + cc); },
-                                                a.partial + (bh * a.nranges + a.lg_nslices * 16 + sc) * kPartialStride);
-    }
-  }
+                                            a.partial + (bh * a.nranges + slot) * kPartialStride);
 }
 
 template <int KT, int WDT, int LT>

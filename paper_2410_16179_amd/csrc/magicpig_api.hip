@@ -76,7 +76,7 @@ HashWs ws_hash_layout(const magicpig_params* p) {
 size_t ws_hash(const magicpig_params* p) { return p->dtype == MAGICPIG_BF16 ? ws_hash_layout(p).total : 256; }
 
 // decode workspace: [partials | ballots]
-struct AttnWs { size_t partial_off, masks_off, total; int nranges, nscan, f_nranges, f_nstatic, f_wave_blocks; int64_t n_static; };
+struct AttnWs { size_t partial_off, masks_off, total; int nranges, nscan, f_nranges, f_wave_blocks; int64_t n_static; };
 AttnWs ws_attention_layout(const magicpig_params* p) {
   AttnWs w{};
   const int64_t nblk = mp::key_blocks(p->n_ctx);
@@ -85,16 +85,15 @@ AttnWs ws_attention_layout(const magicpig_params* p) {
   const int64_t st = (int64_t)p->n_sink + p->n_local;
   w.n_static = st < p->n_ctx ? st : p->n_ctx;
   w.nranges = w.nscan + (int)((w.n_static + mp::kStaticPerRange - 1) / mp::kStaticPerRange);
-  // the one-launch scan + gather has shorter runs, hence more partials per head
-  w.f_nstatic = (int)((w.n_static + mp::kFusedStatic - 1) / mp::kFusedStatic);
+  // the one-launch scan + gather: one partial per run and head
   // runs of 16 key blocks per workgroup when that still fills the chip, shorter runs otherwise
   const int64_t units = (int64_t)p->batch * p->n_kv_heads;
   w.f_wave_blocks = mp::kFusedWaveBlocks;
   while (w.f_wave_blocks > 1 && units * ((nblk + 4 * w.f_wave_blocks - 1) / (4 * w.f_wave_blocks)) < mp::kFusedFill)
     w.f_wave_blocks /= 2;
-  w.f_nranges = w.f_nstatic + (int)((nblk + 4 * w.f_wave_blocks - 1) / (4 * w.f_wave_blocks));
-  // lookup + gather in one launch: 16 partials per slice and the static chunks
-  const int lg = (int)((nblk + mp::kLgSliceBlocks - 1) / mp::kLgSliceBlocks) * 16 + (w.nranges - w.nscan);
+  w.f_nranges = (int)((nblk + 4 * w.f_wave_blocks - 1) / (4 * w.f_wave_blocks));
+  // lookup + gather in one launch: 16 partials per slice
+  const int lg = (int)((nblk + mp::kLgSliceBlocks - 1) / mp::kLgSliceBlocks) * 16;
   size_t most = (size_t)(w.f_nranges > w.nranges ? w.f_nranges : w.nranges);
   if ((size_t)lg > most) most = (size_t)lg;
   w.partial_off = 0;
@@ -228,7 +227,7 @@ int run_attention_impl(const magicpig_params* p, const void* q, const void* K_ca
   a.partial = reinterpret_cast<float*>(wsb + wl.partial_off); a.out = out;
   a.masks = reinterpret_cast<uint64_t*>(wsb + wl.masks_off);
   a.nranges = wl.nranges; a.nscan = wl.nscan; a.n_static = wl.n_static;
-  a.f_nranges = wl.f_nranges; a.f_nstatic = wl.f_nstatic; a.f_wave_blocks = wl.f_wave_blocks;
+  a.f_nranges = wl.f_nranges; a.f_wave_blocks = wl.f_wave_blocks;
   a.dbg_counts = dbg_counts; a.dbg_cand = dbg_cand; a.dbg_ncand = dbg_ncand; a.dbg_cand_cap = dbg_cand_cap;
   a.is_fp32 = p->dtype == MAGICPIG_FP32;
   a.B = p->batch; a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.K = p->K; a.L = p->L;

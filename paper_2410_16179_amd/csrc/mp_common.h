@@ -124,9 +124,9 @@ struct AttnArgs {
   int nranges;               // partials per head: nscan runs of kRangeBlocks key blocks + static runs
   int nscan;                 // runs of kRangeBlocks key blocks per head
   int64_t n_static;          // keys in the static set T
-  // scan and gather in one launch: one workgroup and one partial per head for every kFusedBlocks
-  // key blocks, then f_nstatic partials per head for the chunks of the static set
-  int f_nranges, f_nstatic, f_wave_blocks;   // f_wave_blocks: key blocks per wavefront (1, 2, 4)
+  // scan and gather in one launch: one workgroup, and one partial per head, for every run of
+  // 4 * f_wave_blocks key blocks (f_wave_blocks: key blocks per wavefront, 1, 2 or 4)
+  int f_nranges, f_wave_blocks;
   // lookup + gather in one launch: slices of the indexed range; the first lg_app_runs of them
   // also take a run of 16 appended key blocks each
   int lg_nslices, lg_app_runs;
@@ -161,7 +161,6 @@ constexpr int kFusedWaveBlocks = 4;           // most key blocks a wavefront sca
 constexpr int kFusedBlocks = 4 * kFusedWaveBlocks;        // most key blocks per workgroup
 constexpr int kFusedFill = 768;               // workgroups of it that are resident at once (3 per compute unit)
 constexpr int kFusedIters = 8;             // its gather batch: rows per quarter wavefront
-constexpr int kFusedStatic = 4 * kFusedIters;             // static keys per workgroup and head there
 
 // host-side launchers (defined next to their kernels)
 hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s);

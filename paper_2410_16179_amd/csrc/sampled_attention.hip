@@ -104,10 +104,10 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
   }
   float* pp = a.partial + (bh * a.nranges + range) * kPartialStride;
   if (!is_static) {
-    gather_estimate_wave<FP32, kGatherIters<FP32>>(a, unit, bh, total, true, hv,
+    gather_estimate_wave<FP32, kGatherIters<FP32>>(a, unit, bh, total, total, hv,
                                [&](int c) { return blk0 * kBlockKeys + (int64_t)list[c]; }, pp);
   } else {
-    gather_estimate_wave<FP32, kGatherIters<FP32>>(a, unit, bh, total, false, hv,
+    gather_estimate_wave<FP32, kGatherIters<FP32>>(a, unit, bh, total, 0, hv,
                                [&](int c) { return static_key(a, static_first + c); }, pp);
   }
 }
@@ -126,10 +126,10 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
 // more partials and gather batches; the 142 registers of this form (three wavefronts per SIMD)
 // measured faster than the same kernel held to 128.
 // The grid is one workgroup per run (at 8 KV heads x 98304 keys: 768, exactly what is resident
-// at once; workgroups that start late end last).  The static set T is cut into chunks of
-// kFusedStatic keys; chunk c of the launch is taken, after its own run, by the c-th workgroup in
-// dispatch order: those finish their scan first and have the time.
-// One partial per (head, run) and per (head, static chunk).
+// at once; workgroups that start late end last).  The keys of the static set T are dealt over
+// the runs of their KV head (key j to run j mod runs) and join the gather batches there, so
+// they cost neither workgroups nor batches nor partials of their own.
+// One partial per (head, run).
 template <int KT, int WDT, int LT, bool FP32>
 __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
   constexpr int kIt = FP32 ? (kFusedIters + 1) / 2 : kFusedIters;   // the same registers per batch
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
   __shared__ uint16_t lists[4][kFusedBlocks * kBlockKeys];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int unit = blockIdx.y, run = blockIdx.x;
-  const int nruns = gridDim.x;                             // = f_nranges - f_nstatic
+  const int nruns = gridDim.x;                             // = f_nranges
   const int G = a.Hq / a.Hkv;
   const int64_t head0 = (int64_t)(unit / a.Hkv) * a.Hq + (int64_t)(unit % a.Hkv) * G;
   const int64_t nblk = key_blocks(a.n);
@@ -178,27 +178,16 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
     }
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
     __builtin_amdgcn_wave_barrier();
-    gather_estimate_wave<FP32, kIt>(a, unit, head0 + h, total, true, hv,
-                                    [&](int cc) { return blk0 * kBlockKeys + (int64_t)list[cc]; },
+    // static keys run, run + nruns, ... ride along behind the sampled ones
+    const int nst = static_share(a, run, nruns);
+    gather_estimate_wave<FP32, kIt>(a, unit, head0 + h, total + nst, total, hv,
+                                    [&](int cc) {
+                                      return cc < total ? blk0 * kBlockKeys + (int64_t)list[cc]
+                                                        : static_key(a, run + (int64_t)(cc - total) * nruns);
+                                    },
                                     a.partial + ((head0 + h) * a.f_nranges + run) * kPartialStride);
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
     __builtin_amdgcn_wave_barrier();
-  }
-  // ---- static chunks of the launch, dealt out in dispatch order ----
-  const int chunks = (int)gridDim.y * a.f_nstatic;
-  for (int c = (int)blockIdx.y * nruns + run; c < chunks; c += nruns * (int)gridDim.y) {
-    const int su = c / a.f_nstatic, sc = c % a.f_nstatic;
-    const int64_t shead0 = (int64_t)(su / a.Hkv) * a.Hq + (int64_t)(su % a.Hkv) * G;
-    const int64_t first = (int64_t)sc * kFusedStatic;
-    const int64_t left = a.n_static - first;
-    const int total = (int)(left < kFusedStatic ? left : kFusedStatic);
-    for (int h = wave; h < G; h += 4) {
-      HeadVectors<FP32> hv;
-      request_head_vectors<FP32>(a, su, shead0 + h, hv);
-      gather_estimate_wave<FP32, kIt>(a, su, shead0 + h, total, false, hv,
-                                      [&](int cc) { return static_key(a, first + cc); },
-                                      a.partial + ((shead0 + h) * a.f_nranges + nruns + sc) * kPartialStride);
-    }
   }
 }
 
@@ -305,7 +294,7 @@ static hipError_t launch_merge(const AttnArgs& a, int64_t heads, hipStream_t s, 
 }
 
 static hipError_t launch_scan_gather(const AttnArgs& a, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
-  const dim3 block(256), grid((unsigned)(a.f_nranges - a.f_nstatic), (unsigned)(a.B * a.Hkv));
+  const dim3 block(256), grid((unsigned)a.f_nranges, (unsigned)(a.B * a.Hkv));
 #define MP_TUNED(KT, LL)                                                                            \
   if (a.K == KT && a.L == LL) {                                                                     \
     if (a.is_fp32)                                                                                  \
@@ -343,8 +332,7 @@ hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, 
     if (lookup && !a.dbg_counts && (a.tau == 1 || a.tau == 2) && app_runs <= nslices) {
       // lookup and gather of the indexed keys, the static set, and scan and gather of the keys
       // appended since the build (as long as they are few), in one launch
-      const int nchunks = (int)((a.n_static + kStaticPerRange - 1) / kStaticPerRange);
-      b.nranges = nslices * 16 + nchunks;
+      b.nranges = nslices * 16;
       if ((e = launch_lookup_gather(b, *tables, nslices, app_runs, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr)) != hipSuccess)
         return e;
       if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
