@@ -426,7 +426,6 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
   constexpr int kSliceWords = kLgSliceBlocks * 2;       // 32-key words of a slice
   constexpr int kWaveWords = kLgWaveBlocks * 2;
   __shared__ uint32_t seen[kSliceWords], twice[kSliceWords];
-  __shared__ uint32_t bstart[512], blen[512];
   __shared__ uint32_t qs[256];
   __shared__ uint16_t lists[16][kLgWaveBlocks * kBlockKeys + kBlockKeys];
   const int tid = threadIdx.x;
@@ -452,48 +451,64 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
   }
   if (tid < a.NQ) qs[tid] = qword;
   __syncthreads();
-  for (int t = tid; t < a.L; t += 1024) {
+  // wavefront v reads tables v, v+16, ...: lane k finds the bucket of table v + 16 k (its code
+  // from the query's plane words, then two offsets); the descriptors reach the other lanes as
+  // scalars.  Up to 128 entries of each bucket are requested before any is used; longer
+  // buckets are finished in a loop.
+  constexpr int kMaxB = 32;                             // L <= 512 tables over 16 wavefronts
+  const int nbk = (a.L - wave + 15) >> 4;
+  uint32_t my_start = 0, my_len = 0;
+  if (lane < nbk) {
+    const int t = wave + 16 * lane;
     const uint32_t* qw = qs + (t >> 5) * a.K;
     uint32_t code = 0;
     for (int b = 0; b < a.K; ++b) code |= ((qw[b] >> (t & 31)) & 1u) << b;
-    const uint32_t s0 = offs[(int64_t)t * (nb + 1) + code], s1 = offs[(int64_t)t * (nb + 1) + code + 1];
-    bstart[t] = s0;
-    blen[t] = s1 - s0;
+    const uint32_t* o = offs + (int64_t)t * (nb + 1) + code;
+    my_start = o[0];
+    my_len = o[1] - my_start;
   }
-  __syncthreads();
-  // wavefront v reads tables v, v+16, ...: up to 128 entries of each bucket are requested before
-  // any is used; longer buckets are finished in a loop
-  {
-    constexpr int kMaxB = 32;                           // L <= 512 tables over 16 wavefronts
-    uint32_t e0[kMaxB], e1[kMaxB];
-    const int nbk = (a.L - wave + 15) >> 4;
+  uint32_t e0[kMaxB], e1[kMaxB];
 #pragma unroll
-    for (int k = 0; k < kMaxB; ++k) {
-      e0[k] = 0xffffffffu; e1[k] = 0xffffffffu;
-      if (k < nbk) {
-        const int t = wave + 16 * k;
-        const uint32_t len = blen[t];
-        const uint32_t* p = idxs + (int64_t)t * tb.n_cap + bstart[t];
-        if ((uint32_t)lane < len) e0[k] = p[lane];
-        if ((uint32_t)lane + 64 < len) e1[k] = p[lane + 64];
+  for (int k = 0; k < kMaxB; ++k) {
+    e0[k] = 0xffffffffu; e1[k] = 0xffffffffu;
+    if (k < nbk) {
+      const uint32_t start = __builtin_amdgcn_readlane(my_start, k), len = __builtin_amdgcn_readlane(my_len, k);
+      const uint32_t* p = idxs + (int64_t)(wave + 16 * k) * tb.n_cap + start;
+      if ((uint32_t)lane < len) e0[k] = p[lane];
+      if ((uint32_t)lane + 64 < len) e1[k] = p[lane + 64];
+    }
+  }
+  // Marking: absent entries and keys of other slices fall out of range.  The first atomics of
+  // eight buckets are issued together and their answers (was the key seen before?) used
+  // afterwards, so the LDS round trips overlap instead of following each other.
+  constexpr uint32_t kSliceKeys = kLgSliceBlocks * kBlockKeys;
+#pragma unroll
+  for (int c0 = 0; c0 < kMaxB; c0 += 8) {
+    if (c0 < nbk) {
+      uint32_t before[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const uint32_t rel = ((i & 1) ? e1[c0 + (i >> 1)] : e0[c0 + (i >> 1)]) - key_lo;
+        before[i] = 0u;
+        if (rel < kSliceKeys) before[i] = atomicOr(&seen[rel >> 5], 1u << (rel & 31));
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const uint32_t rel = ((i & 1) ? e1[c0 + (i >> 1)] : e0[c0 + (i >> 1)]) - key_lo;
+        if (rel < kSliceKeys && ((before[i] >> (rel & 31)) & 1u)) atomicOr(&twice[rel >> 5], 1u << (rel & 31));
       }
     }
-    auto mark = [&](uint32_t key) {
-      const uint32_t rel = key - key_lo;                // absent entries and other slices: out of range
-      if (rel < (uint32_t)(kLgSliceBlocks * kBlockKeys)) {
-        const uint32_t bit = 1u << (rel & 31);
-        if (atomicOr(&seen[rel >> 5], bit) & bit) atomicOr(&twice[rel >> 5], bit);
-      }
-    };
-#pragma unroll
-    for (int k = 0; k < kMaxB; ++k) {
-      if (k < nbk) {
-        mark(e0[k]);
-        mark(e1[k]);
-        const int t = wave + 16 * k;
-        if (blen[t] > 128) {
-          const uint32_t* p = idxs + (int64_t)t * tb.n_cap + bstart[t];
-          for (uint32_t j = 128 + lane; j < blen[t]; j += 64) mark(p[j]);
+  }
+#pragma unroll 1
+  for (int k = 0; k < nbk; ++k) {
+    const uint32_t len = __shfl(my_len, k);
+    if (len > 128) {
+      const uint32_t* p = idxs + (int64_t)(wave + 16 * k) * tb.n_cap + __shfl(my_start, k);
+      for (uint32_t j = 128 + lane; j < len; j += 64) {
+        const uint32_t rel = p[j] - key_lo;
+        if (rel < kSliceKeys) {
+          const uint32_t bit = 1u << (rel & 31);
+          if (atomicOr(&seen[rel >> 5], bit) & bit) atomicOr(&twice[rel >> 5], bit);
         }
       }
     }
