@@ -159,15 +159,21 @@ int magicpig_sampled_attention(const magicpig_params* params, const void* q, con
  * a decode step then reads only the L buckets selected by the query's codes instead of every
  * key's code, and obtains the same counts on the keys it touches and the same sample S.
  * Supported for K <= 12, L <= 255, batch * n_q_heads <= 65535 (otherwise the size is 0 and the
- * calls return MAGICPIG_UNSUPPORTED).  The buffer holds [batch*n_kv_heads][L][2^K + 1] uint32
- * bucket offsets followed (256-byte aligned) by [batch*n_kv_heads][L][n_cap] uint32 key indices;
- * the order of the indices inside a bucket is unspecified.  Tables are rebuilt from the packed
+ * calls return MAGICPIG_UNSUPPORTED).  The buffer holds, each part 256-byte aligned: a header of
+ * 256 bytes (word 0: number of 16384-key windows when the buckets are ordered by window, else
+ * 0); [batch*n_kv_heads][L][2^K + 1] uint32 bucket offsets; [batch*n_kv_heads][L][n_cap] uint32
+ * key indices; [batch*n_kv_heads][L][windows][2^K] uint32 fill levels of the buckets at the
+ * start of every window (room for ceil(n_cap / 16384) windows).  A build with the large
+ * workspace orders every bucket by window (keys of window 0 first, ...), which lets a decode
+ * step read, for a range of keys, only the piece of a bucket that holds them; inside a
+ * window's piece, and in buckets of the one-pass build, the order is unspecified.  Tables are
+ * rebuilt from the packed
  * key codes; they are not extended incrementally: keys appended after a build are found by
  * scanning their packed codes (see n_indexed below) until the next build. */
 size_t magicpig_table_bytes(const magicpig_params* params);
 /* magicpig_build_tables works with any workspace (NULL included).  Given one of at least
- * magicpig_table_build_workspace_bytes(params) bytes (2 bytes per key and table plus the bucket
- * fill levels per window of 16384 keys; 0 if tables are unsupported) it first writes every key's
+ * magicpig_table_build_workspace_bytes(params) bytes (2 bytes per key and table; 0 if tables
+ * are unsupported) it first writes every key's
  * code per table there and then places the keys window by window, which is several times faster
  * than scattering them in one pass.  The resulting tables hold the same buckets either way. */
 size_t magicpig_table_build_workspace_bytes(const magicpig_params* params);

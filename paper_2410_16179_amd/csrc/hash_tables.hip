@@ -59,6 +59,8 @@ __global__ __launch_bounds__(256) void ht_build_kernel(TableArgs a) {
   const int64_t nblk = key_blocks(a.n);
   const uint32_t* ucodes = a.kcodes + (int64_t)unit * a.blocks_cap * (kBlockKeys * (int64_t)a.NW);
   const bool windowed = !SCATTER && a.codes16 != nullptr;
+  // (the lookup reads from the header whether the buckets are ordered by window)
+  if (!SCATTER && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) a.header[0] = windowed ? (uint32_t)a.windows : 0u;
   constexpr int64_t kWinBlocks = kBuildWindow / kBlockKeys;
   const int64_t nwin = windowed ? a.windows : 1;
   for (int64_t win = 0; win < nwin; ++win) {
@@ -412,14 +414,16 @@ hipError_t launch_build_tables(const TableArgs& t, hipStream_t s) {
 
 // Lookup and gather in one launch for min_hits 1 or 2: a workgroup of 16 wavefronts per (query
 // head, slice of kLgSliceBlocks key blocks of the indexed range).  It reads the L buckets of the
-// head like table_lookup_bitmap_kernel (every slice of a head reads them all: 58 KB at 96k keys,
-// served by L2 after the first), marks only the keys of its slice in the "seen" / "seen twice"
-// bitmaps in LDS, and wavefront v then expands the bits of its kLgWaveBlocks blocks into an index
-// list and gathers and weighs those keys (gather_estimate_wave) without the ballots ever leaving
-// the compute unit: one partial per (head, slice, wavefront).  The keys of the static set T are
-// dealt over these wavefronts (key j to wavefront j mod their number) and join the batches.  The keys
-// appended since the build, 16 code blocks per slice, are found by the collision scan in the
-// workgroups of slice 0, 1, ... and join the gather batches there.
+// head: of window-ordered tables (the build with a workspace) only the pieces that hold the
+// keys of its slice, which is a build window, so that a head's buckets are read once in all;
+// otherwise whole buckets, of which it keeps the keys of its slice.  The keys are marked in
+// "seen" / "seen twice" bitmaps in LDS, and wavefront v then expands the bits of its
+// kLgWaveBlocks blocks into an index list and gathers and weighs those keys
+// (gather_estimate_wave) without the ballots ever leaving the compute unit: one partial per
+// (head, slice, wavefront).  The keys of the static set T are dealt over these wavefronts (key
+// j to wavefront j mod their number) and join the batches.  The keys appended since the build,
+// 16 code blocks per slice, are found by the collision scan in the workgroups of slice 0, 1,
+// ... and join the gather batches there.
 // KT, WDT, LT: the collision scan's compile-time K, ceil(L/32) and tables of the last group (0: any).
 template <int KT, int WDT, int LT, bool FP32>
 __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableArgs tb) {
@@ -457,6 +461,7 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
   // buckets are finished in a loop.
   constexpr int kMaxB = 32;                             // L <= 512 tables over 16 wavefronts
   const int nbk = (a.L - wave + 15) >> 4;
+  const int windows = (int)tb.header[0];                // 0: buckets in no particular order
   uint32_t my_start = 0, my_len = 0;
   if (lane < nbk) {
     const int t = wave + 16 * lane;
@@ -465,51 +470,101 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
     for (int b = 0; b < a.K; ++b) code |= ((qw[b] >> (t & 31)) & 1u) << b;
     const uint32_t* o = offs + (int64_t)t * (nb + 1) + code;
     my_start = o[0];
-    my_len = o[1] - my_start;
-  }
-  uint32_t e0[kMaxB], e1[kMaxB];
-#pragma unroll
-  for (int k = 0; k < kMaxB; ++k) {
-    e0[k] = 0xffffffffu; e1[k] = 0xffffffffu;
-    if (k < nbk) {
-      const uint32_t start = __builtin_amdgcn_readlane(my_start, k), len = __builtin_amdgcn_readlane(my_len, k);
-      const uint32_t* p = idxs + (int64_t)(wave + 16 * k) * tb.n_cap + start;
-      if ((uint32_t)lane < len) e0[k] = p[lane];
-      if ((uint32_t)lane + 64 < len) e1[k] = p[lane + 64];
+    uint32_t my_end = o[1];
+    if (windows > 0) {
+      // window-ordered buckets: only the piece that holds the keys of this slice
+      const uint32_t* wc = tb.wincum + (((int64_t)unit * a.L + t) * windows + slice) * nb + code;
+      if (slice + 1 < windows) my_end = my_start + wc[nb];
+      my_start += wc[0];
     }
+    my_len = my_end - my_start;
   }
-  // Marking: absent entries and keys of other slices fall out of range.  The first atomics of
-  // eight buckets are issued together and their answers (was the key seen before?) used
-  // afterwards, so the LDS round trips overlap instead of following each other.
   constexpr uint32_t kSliceKeys = kLgSliceBlocks * kBlockKeys;
+  auto mark = [&](uint32_t key) {
+    const uint32_t rel = key - key_lo;                  // absent entries and other slices: out of range
+    if (rel < kSliceKeys) {
+      const uint32_t bit = 1u << (rel & 31);
+      if (atomicOr(&seen[rel >> 5], bit) & bit) atomicOr(&twice[rel >> 5], bit);
+    }
+  };
+  if (windows > 0) {
+    // Window-ordered tables: a piece holds about 16 keys (n 2^-K per window of 16384 keys), so
+    // half a wavefront reads a piece: lanes 0..31 that of table v + 32 j, lanes 32..63 that of
+    // table v + 32 j + 16.  The first atomics of all pieces are issued together and their
+    // answers (was the key seen before?) used afterwards, so the LDS round trips overlap.
+    // Pieces of more than 32 keys are finished in a loop.
+    const int half = lane >> 5, li = lane & 31;
+    uint32_t e[kMaxB / 2];
 #pragma unroll
-  for (int c0 = 0; c0 < kMaxB; c0 += 8) {
-    if (c0 < nbk) {
-      uint32_t before[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const uint32_t rel = ((i & 1) ? e1[c0 + (i >> 1)] : e0[c0 + (i >> 1)]) - key_lo;
-        before[i] = 0u;
-        if (rel < kSliceKeys) before[i] = atomicOr(&seen[rel >> 5], 1u << (rel & 31));
-      }
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const uint32_t rel = ((i & 1) ? e1[c0 + (i >> 1)] : e0[c0 + (i >> 1)]) - key_lo;
-        if (rel < kSliceKeys && ((before[i] >> (rel & 31)) & 1u)) atomicOr(&twice[rel >> 5], 1u << (rel & 31));
+    for (int j = 0; j < kMaxB / 2; ++j) {
+      e[j] = 0xffffffffu;
+      if (2 * j < nbk) {
+        const int k = 2 * j + half;
+        const uint32_t start = __shfl(my_start, k), len = __shfl(my_len, k);   // (0 for k >= nbk)
+        const uint32_t* p = idxs + (int64_t)(wave + 16 * k) * tb.n_cap + start;
+        if ((uint32_t)li < len) e[j] = p[li];
       }
     }
-  }
+    uint32_t before[kMaxB / 2];
+#pragma unroll
+    for (int j = 0; j < kMaxB / 2; ++j) {
+      const uint32_t rel = e[j] - key_lo;
+      before[j] = 0u;
+      if (2 * j < nbk && rel < kSliceKeys) before[j] = atomicOr(&seen[rel >> 5], 1u << (rel & 31));
+    }
+#pragma unroll
+    for (int j = 0; j < kMaxB / 2; ++j) {
+      const uint32_t rel = e[j] - key_lo;
+      if (2 * j < nbk && rel < kSliceKeys && ((before[j] >> (rel & 31)) & 1u)) atomicOr(&twice[rel >> 5], 1u << (rel & 31));
+    }
 #pragma unroll 1
-  for (int k = 0; k < nbk; ++k) {
-    const uint32_t len = __shfl(my_len, k);
-    if (len > 128) {
-      const uint32_t* p = idxs + (int64_t)(wave + 16 * k) * tb.n_cap + __shfl(my_start, k);
-      for (uint32_t j = 128 + lane; j < len; j += 64) {
-        const uint32_t rel = p[j] - key_lo;
-        if (rel < kSliceKeys) {
-          const uint32_t bit = 1u << (rel & 31);
-          if (atomicOr(&seen[rel >> 5], bit) & bit) atomicOr(&twice[rel >> 5], bit);
+    for (int k = 0; k < nbk; ++k) {
+      const uint32_t len = __shfl(my_len, k);
+      if (len > 32) {
+        const uint32_t* p = idxs + (int64_t)(wave + 16 * k) * tb.n_cap + __shfl(my_start, k);
+        for (uint32_t j = 32 + lane; j < len; j += 64) mark(p[j]);
+      }
+    }
+  } else {
+    // Buckets in no particular order: up to 128 entries of each bucket are requested before any
+    // is used; longer buckets are finished in a loop.
+    uint32_t e0[kMaxB], e1[kMaxB];
+#pragma unroll
+    for (int k = 0; k < kMaxB; ++k) {
+      e0[k] = 0xffffffffu; e1[k] = 0xffffffffu;
+      if (k < nbk) {
+        const uint32_t start = __builtin_amdgcn_readlane(my_start, k), len = __builtin_amdgcn_readlane(my_len, k);
+        const uint32_t* p = idxs + (int64_t)(wave + 16 * k) * tb.n_cap + start;
+        if ((uint32_t)lane < len) e0[k] = p[lane];
+        if ((uint32_t)lane + 64 < len) e1[k] = p[lane + 64];
+      }
+    }
+    // Marking: absent entries and keys of other slices fall out of range.  The first atomics of
+    // eight buckets are issued together and their answers (was the key seen before?) used
+    // afterwards, so the LDS round trips overlap instead of following each other.
+#pragma unroll
+    for (int c0 = 0; c0 < kMaxB; c0 += 8) {
+      if (c0 < nbk) {
+        uint32_t before[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const uint32_t rel = ((i & 1) ? e1[c0 + (i >> 1)] : e0[c0 + (i >> 1)]) - key_lo;
+          before[i] = 0u;
+          if (rel < kSliceKeys) before[i] = atomicOr(&seen[rel >> 5], 1u << (rel & 31));
         }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const uint32_t rel = ((i & 1) ? e1[c0 + (i >> 1)] : e0[c0 + (i >> 1)]) - key_lo;
+          if (rel < kSliceKeys && ((before[i] >> (rel & 31)) & 1u)) atomicOr(&twice[rel >> 5], 1u << (rel & 31));
+        }
+      }
+    }
+#pragma unroll 1
+    for (int k = 0; k < nbk; ++k) {
+      const uint32_t len = __shfl(my_len, k);
+      if (len > 128) {
+        const uint32_t* p = idxs + (int64_t)(wave + 16 * k) * tb.n_cap + __shfl(my_start, k);
+        for (uint32_t j = 128 + lane; j < len; j += 64) mark(p[j]);
       }
     }
   }

@@ -108,28 +108,45 @@ bool tables_supported(const magicpig_params* p) {
   return p->K <= 12 && p->L <= 255 && (int64_t)p->batch * p->n_q_heads <= 65535;
 }
 
-// workspace of the two-pass table build: [codes per table and key | bucket fill levels per window]
-struct BuildWs { size_t codes_off, cum_off, total; int windows; };
+// workspace of the two-pass table build: the code of every key in every table
+struct BuildWs { size_t codes_off, total; int windows; };
 BuildWs ws_build_layout(const magicpig_params* p) {
   BuildWs w{};
   const size_t units = (size_t)p->batch * p->n_kv_heads;
   const int64_t n = p->n_ctx > 0 ? p->n_ctx : 1;
   w.windows = (int)((n + mp::kBuildWindow - 1) / mp::kBuildWindow);
   w.codes_off = 0;
-  w.cum_off = align256(units * p->L * (size_t)mp::key_blocks(p->n_cap) * mp::kBlockKeys * sizeof(uint16_t));
-  w.total = w.cum_off + align256(units * p->L * (size_t)w.windows * ((size_t)1 << p->K) * sizeof(uint32_t));
+  w.total = align256(units * p->L * (size_t)mp::key_blocks(p->n_cap) * mp::kBlockKeys * sizeof(uint16_t));
   return w;
+}
+
+// tables: [header | bucket offsets | key indices | bucket fill levels at the start of every window]
+struct TableLayout { size_t header_off, offsets_off, indices_off, wincum_off, total; };
+TableLayout table_layout(const magicpig_params* p) {
+  TableLayout t{};
+  const size_t units = (size_t)p->batch * p->n_kv_heads;
+  const size_t nb = (size_t)1 << p->K;
+  const size_t windows_cap = (size_t)((p->n_cap + mp::kBuildWindow - 1) / mp::kBuildWindow);
+  t.header_off = 0;
+  t.offsets_off = 256;
+  t.indices_off = t.offsets_off + align256(units * p->L * (nb + 1) * 4);
+  t.wincum_off = t.indices_off + align256(units * p->L * (size_t)p->n_cap * 4);
+  t.total = t.wincum_off + align256(units * p->L * (windows_cap > 0 ? windows_cap : 1) * nb * 4);
+  return t;
 }
 
 void fill_table_args(const magicpig_params* p, const void* tables, mp::TableArgs* t) {
   const size_t units = (size_t)p->batch * p->n_kv_heads;
+  const TableLayout tl = table_layout(p);
   char* base = reinterpret_cast<char*>(const_cast<void*>(tables));
   t->kcodes = nullptr;
-  t->offsets = reinterpret_cast<uint32_t*>(base);
-  t->indices = reinterpret_cast<uint32_t*>(base + align256(units * p->L * (((size_t)1 << p->K) + 1) * 4));
+  t->header = reinterpret_cast<uint32_t*>(base + tl.header_off);
+  t->offsets = reinterpret_cast<uint32_t*>(base + tl.offsets_off);
+  t->indices = reinterpret_cast<uint32_t*>(base + tl.indices_off);
+  t->wincum = reinterpret_cast<uint32_t*>(base + tl.wincum_off);
   t->K = p->K; t->L = p->L; t->NW = mp::code_words(p->K, p->L); t->units = (int)units;
   t->n = p->n_ctx; t->n_cap = p->n_cap; t->blocks_cap = mp::key_blocks(p->n_cap);
-  t->codes16 = nullptr; t->wincum = nullptr; t->windows = 1;
+  t->codes16 = nullptr; t->windows = 1;
 }
 
 int check_hash_keys_args(const magicpig_params* p, const void* K_cache, const float* mu, const void* W,
@@ -396,8 +413,7 @@ int magicpig_sampled_attention(const magicpig_params* p, const void* q, const vo
 
 size_t magicpig_table_bytes(const magicpig_params* p) {
   if (check_params(p) != MAGICPIG_OK || !tables_supported(p)) return 0;
-  const size_t units = (size_t)p->batch * p->n_kv_heads;
-  return align256(units * p->L * (((size_t)1 << p->K) + 1) * 4) + align256(units * p->L * (size_t)p->n_cap * 4);
+  return table_layout(p).total;
 }
 
 size_t magicpig_table_build_workspace_bytes(const magicpig_params* p) {
@@ -419,7 +435,6 @@ int magicpig_build_tables(const magicpig_params* p, const uint32_t* key_codes, v
   if (workspace && aligned16(workspace) && workspace_bytes >= bw.total) {
     char* wsb = reinterpret_cast<char*>(workspace);
     t.codes16 = reinterpret_cast<uint16_t*>(wsb + bw.codes_off);
-    t.wincum = reinterpret_cast<uint32_t*>(wsb + bw.cum_off);
     t.windows = bw.windows;
   }
   const hipError_t e = mp::launch_build_tables(t, reinterpret_cast<hipStream_t>(hip_stream));

@@ -139,14 +139,16 @@ struct AttnArgs {
 // Bucketed hash tables of the cached keys.
 struct TableArgs {
   const uint32_t* kcodes;      // packed key codes (build only)
+  uint32_t* header;            // word 0: windows of the window-ordered build, 0 when buckets are unordered
   uint32_t* offsets;           // [units][L][2^K + 1]
   uint32_t* indices;           // [units][L][n_cap]
   int K, L, NW, units;
   int64_t n, n_cap, blocks_cap;   // n: keys [0, n) are in the tables
   // build with a large workspace: per-table codes of every key and, for every window of
   // kBuildWindow keys, the number of keys of each bucket in the windows before it
-  uint16_t* codes16;           // [units][L][n_cap], or null (one-pass scatter)
-  uint32_t* wincum;            // [units][L][windows][2^K]
+  uint16_t* codes16;           // [units][L][n_cap] (workspace), or null (one-pass scatter)
+  uint32_t* wincum;            // [units][L][windows][2^K], part of the tables: with it the piece of a
+                               // bucket that holds the keys of one window can be read alone
   int windows;
 };
 constexpr int kBuildWindow = 16384;   // keys one workgroup places into the buckets of one table
@@ -154,8 +156,9 @@ constexpr int kBuildWindow = 16384;   // keys one workgroup places into the buck
 constexpr int kPartialStride = 132;   // 128 output elements, running max, running sum, pad
 constexpr int kRangeBlocks = 16;      // key blocks per gather wavefront (1024 keys)
 constexpr int kStaticPerRange = 32;   // static (sink / local) keys per gather wavefront
-constexpr int kLgWaveBlocks = 12;     // lookup + gather in one launch: key blocks per wavefront,
-constexpr int kLgSliceBlocks = 16 * kLgWaveBlocks;   // and per workgroup (16 wavefronts)
+constexpr int kLgWaveBlocks = 16;     // lookup + gather in one launch: key blocks per wavefront,
+constexpr int kLgSliceBlocks = 16 * kLgWaveBlocks;   // and per workgroup (16 wavefronts): one build window
+static_assert(kLgSliceBlocks * kBlockKeys == kBuildWindow, "a lookup slice is a window of the table build");
 // the one-launch scan + gather: four wavefronts per workgroup
 constexpr int kFusedWaveBlocks = 4;           // most key blocks a wavefront scans, one after the other
 constexpr int kFusedBlocks = 4 * kFusedWaveBlocks;        // most key blocks per workgroup

@@ -108,10 +108,19 @@ class Session:
         units, L, nb = self.B * self.Hkv, self.L, 1 << self.K
         raw = self.tables.cpu().numpy().view(np.uint32)
         noff = units * L * (nb + 1)
-        off = raw[:noff].reshape(units, L, nb + 1)
-        start = (noff * 4 + 255) // 256 * 256 // 4
+        o0 = 256 // 4                                     # behind the header
+        off = raw[o0:o0 + noff].reshape(units, L, nb + 1)
+        start = o0 + (noff * 4 + 255) // 256 * 256 // 4
         idx = raw[start:start + units * L * self.n_cap].reshape(units, L, self.n_cap)
         return off, idx
+
+    def table_windows(self):
+        """Header word 0 of the tables and the fill levels [units, L, windows, 2^K] behind the indices."""
+        units, L, nb = self.B * self.Hkv, self.L, 1 << self.K
+        raw = self.tables.cpu().numpy().view(np.uint32)
+        windows = int(raw[0])
+        start = 256 // 4 + (units * L * (nb + 1) * 4 + 255) // 256 * 256 // 4 + (units * L * self.n_cap * 4 + 255) // 256 * 256 // 4
+        return windows, raw[start:start + units * L * max(windows, 0) * nb].reshape(units, L, max(windows, 0), nb)
 
     def attend(self, debug=True, cand_cap=None, tables=False, with_counts=True):
         B, Hq, n = self.B, self.Hq, self.n

@@ -218,8 +218,11 @@ def test_both_table_builds_give_the_same_buckets(oracle):
         codes = s.key_table_codes()                              # [B, Hkv, n, L]
         s.build_tables(big_workspace=False)
         off1, idx1 = s.table_buckets()
+        assert s.table_windows()[0] == 0                         # one-pass build: buckets in no order
         s.build_tables(big_workspace=True)
         off2, idx2 = s.table_buckets()
+        windows, fill = s.table_windows()
+        assert windows == (n + 16383) // 16384
         np.testing.assert_array_equal(off1, off2)
         nb = 1 << w.K
         for unit in range(2):
@@ -233,6 +236,13 @@ def test_both_table_builds_give_the_same_buckets(oracle):
                     ref = np.flatnonzero(codes[0, unit, :, t] == c)
                     np.testing.assert_array_equal(np.sort(idx1[unit, t, lo:hi]), ref)
                     np.testing.assert_array_equal(np.sort(idx2[unit, t, lo:hi]), ref)
+                    # window-ordered build: the piece of window v holds exactly the bucket's keys of
+                    # [16384 v, 16384 (v + 1)), and the fill levels say where it starts
+                    for v in range(windows):
+                        a = lo + fill[unit, t, v, c]
+                        b = lo + fill[unit, t, v + 1, c] if v + 1 < windows else hi
+                        np.testing.assert_array_equal(np.sort(idx2[unit, t, a:b]),
+                                                      ref[(ref >= 16384 * v) & (ref < 16384 * (v + 1))])
 
 
 def test_tables_over_a_prefix_and_scan_of_the_appended_keys(oracle):
