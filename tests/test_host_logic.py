@@ -44,6 +44,17 @@ def test_sizes_and_paper_projector_size():
     assert mp.magicpig_code_words_per_key(params(K=8, L=75)) == 16 + 3
     assert mp.magicpig_code_words_per_key(params(K=6, L=64)) == 12     # whole groups: nothing to pack
     assert mp.magicpig_workspace_bytes(p) >= 256
+    # hash tables: header, offsets [units][L][2^K + 1], indices [units][L][n_cap], fill levels
+    # [units][L][windows of 16384 keys][2^K], each part rounded up to 256 bytes
+    up = lambda x: (x + 255) // 256 * 256
+    units, nb = p.batch * p.n_kv_heads, 1 << p.K
+    for n_cap in (1000, 16384, 16385, 40000):
+        pt = params(n_ctx=min(1000, n_cap), n_cap=n_cap)
+        windows = (n_cap + 16383) // 16384
+        assert mp.magicpig_table_bytes(pt) == (256 + up(units * p.L * (nb + 1) * 4) + up(units * p.L * n_cap * 4)
+                                               + up(units * p.L * windows * nb * 4))
+        assert mp.magicpig_table_build_workspace_bytes(pt) == up(units * p.L * ((n_cap + 63) // 64 * 64) * 2)
+    assert mp.magicpig_table_bytes(params(K=13)) == 0               # unsupported: no tables
     # Table "overhead of LSH": the (10,150) projector for d = 128 in bf16 is 384 KB
     assert 128 * p.K * p.L * 2 == 384000
 
