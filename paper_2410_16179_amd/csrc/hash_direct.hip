@@ -171,12 +171,20 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   const bool col_ok = tid < 32 * a.K && t < a.L;
   const int j = col_ok ? t * a.K + b : 0;
   // 32-bit element offsets from the (uniform) projector base keep the 128 addresses cheap
+  // wavefronts whose 64 threads all lie behind the last column (K < 16: 32 K < 512) neither load
+  // nor multiply: the column loads of a workgroup are what its compute unit issues longest
+  const bool wave_has_columns = wave * 64 < 32 * a.K;
   float wf[kHeadDim];
   const uint32_t ucol = (uint32_t)ncol, uj = (uint32_t)j;
+  if (wave_has_columns) {
 #pragma unroll
-  for (uint32_t i = 0; i < (uint32_t)kHeadDim; ++i) {
-    if constexpr (FP32) wf[i] = reinterpret_cast<const float*>(a.W)[i * ucol + uj];
-    else wf[i] = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(a.W)[i * ucol + uj] << 16);
+    for (uint32_t i = 0; i < (uint32_t)kHeadDim; ++i) {
+      if constexpr (FP32) wf[i] = reinterpret_cast<const float*>(a.W)[i * ucol + uj];
+      else wf[i] = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(a.W)[i * ucol + uj] << 16);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < kHeadDim; ++i) wf[i] = 0.f;
   }
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
   __builtin_amdgcn_wave_barrier();
@@ -227,6 +235,7 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   // float32 values is exact.
   const float kClose32 = with_mu ? 1.6e-5f : 8.0e-6f;
   float s32[2] = {0.f, 0.f}, w2 = 0.f;
+  if (wave_has_columns) {
 #pragma unroll
   for (int i4 = 0; i4 < kHeadDim / 4; ++i4) {
     const float4 x0 = sx[0][i4], x1 = sx[1][i4];
@@ -238,6 +247,7 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
       s32[1] = fmaf(xc[e], wv, s32[1]);
       w2 = fmaf(wv, wv, w2);
     }
+  }
   }
   const float wnorm = __builtin_sqrtf(w2);
   float m32[2] = {sxnorm[0] * wnorm, sxnorm[1] * wnorm};
