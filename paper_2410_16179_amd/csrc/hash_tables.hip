@@ -461,7 +461,9 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
   // buckets are finished in a loop.
   constexpr int kMaxB = 32;                             // L <= 512 tables over 16 wavefronts
   const int nbk = (a.L - wave + 15) >> 4;
-  const int windows = (int)tb.header[0];                // 0: buckets in no particular order
+  // 0: buckets in no particular order (also taken when the tables were built over another number
+  // of keys than this call says: whole buckets are then read, never a piece that is not there)
+  const int windows = (int)tb.header[0] == a.lg_nslices ? a.lg_nslices : 0;
   uint32_t my_start = 0, my_len = 0;
   if (lane < nbk) {
     const int t = wave + 16 * lane;
