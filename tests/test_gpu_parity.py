@@ -140,6 +140,10 @@ def test_full_batches_many_query_vectors(oracle):
     # 512 query vectors per step: the few-vectors kernel walks several pairs per workgroup
     run_case(oracle, wl.scaled(wl.CONFIGS["C4"], n_ctx=200), oracle_codes_too=False)
     run_case(oracle, wl.scaled(wl.CONFIGS["C5"], n_ctx=150), oracle_codes_too=False)
+    # 544 heads: beyond the number up to which the hash-table step looks up and gathers in one
+    # launch, so its production form runs the lookup and the gather as separate launches
+    run_case(oracle, wl.scaled(wl.CONFIGS["C4"], batch=17, n_ctx=300), oracle_codes_too=False,
+             heads=[(0, 0), (9, 17), (16, 31)], indexed=(128,))
 
 
 @pytest.mark.parametrize("K,L,Hq,Hkv,dtype", [(7, 65, 4, 2, "bf16"), (3, 33, 2, 2, "fp32"),
