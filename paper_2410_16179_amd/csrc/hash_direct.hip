@@ -152,7 +152,12 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
 // to be regrouped from column order (table-major) into the bit-plane words of the code layout.
 // A launch takes two sets of vectors (the first `pairs0` rows of the grid code a0's, the rest
 // a1's), so that a decode step codes its queries and its new keys together.
-template <bool FP32>
+// QUAD (the number of columns K*L is a multiple of four): a lane loads four neighbouring columns
+// of a row at once, 16 lanes cover the 64 columns of the wavefront, and the four 16-lane groups
+// take a quarter of the rows each (group g the rows 32 g .. 32 g + 31): a quarter of the load
+// instructions for the same bytes.  The partial sums of the four groups are added at the end and
+// lane (g, i) keeps column 4 i + g of the wavefront.
+template <bool FP32, bool QUAD>
 __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashDirectArgs a1, int pairs0) {
   __shared__ long long limbs[8][kLimbs];
   __shared__ unsigned char sbit[2][512];
@@ -167,20 +172,43 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   const int64_t r0 = (int64_t)((int)blockIdx.y - (second ? pairs0 : 0)) * per_wg;
   const int nrow = a.total_rows - r0 >= per_wg ? per_wg : 1;
   const int ncol = a.K * a.L;
-  const int t = 32 * w + tid / a.K, b = tid % a.K;
-  const bool col_ok = tid < 32 * a.K && t < a.L;
+  // column of this thread inside the 32 K columns of the table word
+  const int cid = QUAD ? wave * 64 + 4 * (lane & 15) + (lane >> 4) : tid;
+  const int t = 32 * w + cid / a.K, b = cid % a.K;
+  const bool col_ok = cid < 32 * a.K && t < a.L;
   const int j = col_ok ? t * a.K + b : 0;
   // 32-bit element offsets from the (uniform) projector base keep the 128 addresses cheap
   // wavefronts whose 64 threads all lie behind the last column (K < 16: 32 K < 512) neither load
   // nor multiply: the column loads of a workgroup are what its compute unit issues longest
   const bool wave_has_columns = wave * 64 < 32 * a.K;
+  // !QUAD: wf[i] = W[i][j].  QUAD: wf[4 k + c] = W[32 g + k][j4 + c], j4 the first column of
+  // the lane's four (whole quads lie inside or outside the projector: K*L is a multiple of 4)
   float wf[kHeadDim];
   const uint32_t ucol = (uint32_t)ncol, uj = (uint32_t)j;
   if (wave_has_columns) {
+    if constexpr (QUAD) {
+      const int g = lane >> 4;
+      const int c4 = wave * 64 + 4 * (lane & 15);
+      const bool quad_ok = 32 * w * a.K + c4 + 3 < ncol && c4 < 32 * a.K;
+      const uint32_t j4 = quad_ok ? (uint32_t)(32 * w * a.K + c4) : 0u;
 #pragma unroll
-    for (uint32_t i = 0; i < (uint32_t)kHeadDim; ++i) {
-      if constexpr (FP32) wf[i] = reinterpret_cast<const float*>(a.W)[i * ucol + uj];
-      else wf[i] = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(a.W)[i * ucol + uj] << 16);
+      for (uint32_t k = 0; k < 32u; ++k) {
+        const uint32_t at = (32u * (uint32_t)g + k) * ucol + j4;
+        if constexpr (FP32) {
+          const float4 v = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.W) + at);
+          wf[4 * k] = v.x; wf[4 * k + 1] = v.y; wf[4 * k + 2] = v.z; wf[4 * k + 3] = v.w;
+        } else {
+          const uint2 v = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a.W) + at);
+          wf[4 * k] = __uint_as_float(v.x << 16); wf[4 * k + 1] = __uint_as_float(v.x & 0xffff0000u);
+          wf[4 * k + 2] = __uint_as_float(v.y << 16); wf[4 * k + 3] = __uint_as_float(v.y & 0xffff0000u);
+        }
+      }
+    } else {
+#pragma unroll
+      for (uint32_t i = 0; i < (uint32_t)kHeadDim; ++i) {
+        if constexpr (FP32) wf[i] = reinterpret_cast<const float*>(a.W)[i * ucol + uj];
+        else wf[i] = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(a.W)[i * ucol + uj] << 16);
+      }
     }
   } else {
 #pragma unroll
@@ -200,6 +228,7 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   // The two vectors (or the vector and its centering vector) are staged once in LDS as float32
   // and read back as broadcasts: every thread needs all 128 elements of both.
   __shared__ float4 sx[2][kHeadDim / 4];
+  __shared__ float sxq[2][kHeadDim];                      // QUAD: sxq[v][4 k + g] = x_v[32 g + k]
   __shared__ float sxnorm[2];
   {
     const int rr = (tid >> 5) & 1, i4 = tid & 31;         // threads 0..63: four elements each
@@ -216,6 +245,14 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
                         __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xffff0000u));
       }
       sx[rr][i4] = v;
+      if constexpr (QUAD) {
+        const float ve[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int e = 4 * i4 + c;                        // element e = 32 g + k
+          sxq[rr][4 * (e & 31) + (e >> 5)] = ve[c];
+        }
+      }
       // Euclidean norm of the staged vector (32 lanes hold one vector)
       float q2 = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, v.w * v.w)));
 #pragma unroll
@@ -236,18 +273,44 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   const float kClose32 = with_mu ? 1.6e-5f : 8.0e-6f;
   float s32[2] = {0.f, 0.f}, w2 = 0.f;
   if (wave_has_columns) {
+    if constexpr (QUAD) {
+      const int g = lane >> 4;
+      float p0[4] = {0.f, 0.f, 0.f, 0.f}, p1[4] = {0.f, 0.f, 0.f, 0.f}, pw[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int i4 = 0; i4 < kHeadDim / 4; ++i4) {
-    const float4 x0 = sx[0][i4], x1 = sx[1][i4];
-    const float xa[4] = {x0.x, x0.y, x0.z, x0.w}, xc[4] = {x1.x, x1.y, x1.z, x1.w};
+      for (int k = 0; k < 32; ++k) {
+        const float xa = sxq[0][4 * k + g], xc = sxq[1][4 * k + g];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float wv = wf[i4 * 4 + e];
-      s32[0] = fmaf(xa[e], wv, s32[0]);
-      s32[1] = fmaf(xc[e], wv, s32[1]);
-      w2 = fmaf(wv, wv, w2);
+        for (int c = 0; c < 4; ++c) {
+          const float wv = wf[4 * k + c];
+          p0[c] = fmaf(xa, wv, p0[c]);
+          p1[c] = fmaf(xc, wv, p1[c]);
+          pw[c] = fmaf(wv, wv, pw[c]);
+        }
+      }
+      // the four row quarters of a column sit in the lanes i, i + 16, i + 32, i + 48
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        p0[c] += __shfl_xor(p0[c], 16); p0[c] += __shfl_xor(p0[c], 32);
+        p1[c] += __shfl_xor(p1[c], 16); p1[c] += __shfl_xor(p1[c], 32);
+        pw[c] += __shfl_xor(pw[c], 16); pw[c] += __shfl_xor(pw[c], 32);
+      }
+      s32[0] = g == 0 ? p0[0] : g == 1 ? p0[1] : g == 2 ? p0[2] : p0[3];
+      s32[1] = g == 0 ? p1[0] : g == 1 ? p1[1] : g == 2 ? p1[2] : p1[3];
+      w2 = g == 0 ? pw[0] : g == 1 ? pw[1] : g == 2 ? pw[2] : pw[3];
+    } else {
+#pragma unroll
+      for (int i4 = 0; i4 < kHeadDim / 4; ++i4) {
+        const float4 x0 = sx[0][i4], x1 = sx[1][i4];
+        const float xa[4] = {x0.x, x0.y, x0.z, x0.w}, xc[4] = {x1.x, x1.y, x1.z, x1.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float wv = wf[i4 * 4 + e];
+          s32[0] = fmaf(xa[e], wv, s32[0]);
+          s32[1] = fmaf(xc[e], wv, s32[1]);
+          w2 = fmaf(wv, wv, w2);
+        }
+      }
     }
-  }
   }
   const float wnorm = __builtin_sqrtf(w2);
   float m32[2] = {sxnorm[0] * wnorm, sxnorm[1] * wnorm};
@@ -267,7 +330,26 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   while (redo) {
     const int src = __ffsll((unsigned long long)redo) - 1;
     redo &= redo - 1;
-    if (lane == src) {
+    if constexpr (QUAD) {
+      // the column is spread over the four lanes (g', i) of the owner's i: each writes its quarter
+      const int gs = src >> 4;                           // wave-uniform: which of the four columns
+      if ((lane & 15) == (src & 15)) {
+        float* dst = reinterpret_cast<float*>(scol[wave]) + 32 * (lane >> 4);
+        if (gs == 0) {
+#pragma unroll
+          for (int k = 0; k < 32; ++k) dst[k] = wf[4 * k];
+        } else if (gs == 1) {
+#pragma unroll
+          for (int k = 0; k < 32; ++k) dst[k] = wf[4 * k + 1];
+        } else if (gs == 2) {
+#pragma unroll
+          for (int k = 0; k < 32; ++k) dst[k] = wf[4 * k + 2];
+        } else {
+#pragma unroll
+          for (int k = 0; k < 32; ++k) dst[k] = wf[4 * k + 3];
+        }
+      }
+    } else if (lane == src) {
 #pragma unroll
       for (int i4 = 0; i4 < kHeadDim / 4; ++i4)
         scol[wave][i4] = make_float4(wf[4 * i4], wf[4 * i4 + 1], wf[4 * i4 + 2], wf[4 * i4 + 3]);
@@ -316,7 +398,7 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
       if (lane == src) bit = r;
       pending &= pending - 1;
     }
-    sbit[rr][tid] = (unsigned char)(bit && col_ok);
+    sbit[rr][cid] = (unsigned char)(bit && col_ok);
   }
   __syncthreads();
   // regroup: item (row, plane b, table beta) reads the bit of column beta*K + b
@@ -372,8 +454,14 @@ hipError_t launch_hash_rows(const HashDirectArgs& a, const HashDirectArgs* b, hi
   const int pairs1 = (int)(b && b->mu ? rows1 : (rows1 + 1) / 2);
   const dim3 grid((unsigned)table_words(a.L), (unsigned)(pairs0 + pairs1)), block(512);
   const HashDirectArgs& a1 = b ? *b : a;
-  if (a.is_fp32) hipLaunchKernelGGL(hash_rows_kernel<true>, grid, block, 0, s, a, a1, pairs0);
-  else hipLaunchKernelGGL(hash_rows_kernel<false>, grid, block, 0, s, a, a1, pairs0);
+  const bool quad = (a.K * a.L) % 4 == 0;     // four columns per load (16-byte aligned base, checked by the caller)
+  if (a.is_fp32) {
+    if (quad) hipLaunchKernelGGL((hash_rows_kernel<true, true>), grid, block, 0, s, a, a1, pairs0);
+    else hipLaunchKernelGGL((hash_rows_kernel<true, false>), grid, block, 0, s, a, a1, pairs0);
+  } else {
+    if (quad) hipLaunchKernelGGL((hash_rows_kernel<false, true>), grid, block, 0, s, a, a1, pairs0);
+    else hipLaunchKernelGGL((hash_rows_kernel<false, false>), grid, block, 0, s, a, a1, pairs0);
+  }
   return hipGetLastError();
 }
 
