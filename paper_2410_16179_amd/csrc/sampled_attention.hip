@@ -4,7 +4,9 @@
 // Retrieval by scanning the packed codes of every key (magicpig_sampled_attention):
 //   scan_gather_kernel, then merge_partials_kernel.
 // Retrieval through the hash tables (magicpig_sampled_attention_tables):
-//   table lookup [+ collision_scan_kernel over the keys appended since the build],
+//   lookup_gather_kernel (hash_tables.hip: lookup, gather, scan of the few appended keys in one
+//   launch), merge_partials_kernel; or, with many heads, for the count output and for other
+//   min_hits: table lookup [+ collision_scan_kernel over the keys appended since the build],
 //   gather_estimate_kernel, merge_partials_kernel.
 //
 // collision scan (scan_blocks)
@@ -16,9 +18,9 @@
 //   No LDS, no barrier, about 60 VGPRs.
 // gather and estimate (gather_estimate_wave)
 //   One wavefront per (query head, run of 16 key blocks): the ballots are expanded into an
-//   index list in LDS by a wavefront prefix sum (further wavefronts take the static sink and
-//   local-window keys, 32 each, so that no wavefront needs a second batch in the usual
-//   case); rows are gathered four at a time (a quarter wavefront holds one 128-element row)
+//   index list in LDS by a wavefront prefix sum (the static sink and local-window keys ride
+//   along in these batches, or, in gather_estimate_kernel, are taken 32 each by wavefronts of
+//   their own); rows are gathered four at a time (a quarter wavefront holds one 128-element row)
 //   with up to 32 K rows and 32 V rows in flight; q.k, q.(k-mu), |k-mu|^2 are reduced over
 //   the 16 lanes of a row, the inclusion probability u_i and the logit q.k/sqrt(d) - log u_i
 //   are evaluated once per candidate, and an online max/sum softmax accumulates the weighted
