@@ -255,6 +255,10 @@ def test_tables_over_a_prefix_and_scan_of_the_appended_keys(oracle):
     run_case(oracle, w, oracle_codes_too=False, indexed=(0, 64, 1984, 2944))
     w4 = wl.scaled(wl.CONFIGS["C4"], batch=2, n_ctx=1500)
     run_case(oracle, w4, oracle_codes_too=False, indexed=(1024,))
+    # three build windows (the last one partial) and 25 appended code blocks, two runs of them, in
+    # the one-launch lookup; 16384 indexed: one window, too many appended keys for that form
+    w3 = wl.scaled(wl.CONFIGS["C2"], n_ctx=40000, n_q_heads=8, n_kv_heads=2)
+    run_case(oracle, w3, oracle_codes_too=False, heads=[(0, 1), (0, 6)], indexed=(38400, 16384))
 
 
 def test_decode_steps_append_keys_behind_the_tables(oracle):
