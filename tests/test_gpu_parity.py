@@ -220,11 +220,17 @@ def test_both_table_builds_give_the_same_buckets(oracle):
         s.set_mu(oracle_mu(oracle, data["K"], n))
         s.hash_keys()
         codes = s.key_table_codes()                              # [B, Hkv, n, L]
+        by_scan = s.attend(debug=False)["out"]
         s.build_tables(big_workspace=False)
         off1, idx1 = s.table_buckets()
         assert s.table_windows()[0] == 0                         # one-pass build: buckets in no order
+        by_unordered_tables = s.attend(debug=False, tables=True)["out"]
         s.build_tables(big_workspace=True)
         off2, idx2 = s.table_buckets()
+        by_window_ordered_tables = s.attend(debug=False, tables=True)["out"]
+        # the decode step gives the same result whichever way the sample is retrieved
+        for o in (by_unordered_tables, by_window_ordered_tables):
+            assert rel_err(o.reshape(-1, 128), by_scan.reshape(-1, 128)) <= 1e-5
         windows, fill = s.table_windows()
         assert windows == (n + 16383) // 16384
         np.testing.assert_array_equal(off1, off2)
