@@ -107,16 +107,20 @@ __device__ inline void load_code_block(const uint32_t* blkp, int lane, uint32_t 
 
 // Reports the keys of block `blk` that query head `head` samples (lane = key, cnt = its number
 // of colliding tables): the ballot of the sampled keys, plus the optional debug outputs.
+// DBG = false leaves the debug outputs out (and their pointers out of the scalar registers).
+template <bool DBG>
 __device__ inline uint64_t report_block(const AttnArgs& a, int64_t head, int64_t blk, int lane, uint32_t cnt) {
   const int64_t i = blk * kBlockKeys + lane;
   const bool valid = i < a.n;
   const bool in_T = i < a.n_sink || i >= a.n - a.n_local;
   const bool hit = valid && !in_T && (a.tau <= 0 || (int)cnt >= a.tau);
   const uint64_t m = __ballot(hit);
-  if (a.dbg_counts && valid) a.dbg_counts[head * a.n + i] = (uint16_t)cnt;
-  if (a.dbg_cand && hit) {
-    const int pos = atomicAdd(&a.dbg_ncand[head], 1);
-    if (pos < a.dbg_cand_cap) a.dbg_cand[head * a.dbg_cand_cap + pos] = (int32_t)i;
+  if constexpr (DBG) {
+    if (a.dbg_counts && valid) a.dbg_counts[head * a.n + i] = (uint16_t)cnt;
+    if (a.dbg_cand && hit) {
+      const int pos = atomicAdd(&a.dbg_ncand[head], 1);
+      if (pos < a.dbg_cand_cap) a.dbg_cand[head * a.dbg_cand_cap + pos] = (int32_t)i;
+    }
   }
   return m;
 }
@@ -128,7 +132,7 @@ __device__ inline uint64_t report_block(const AttnArgs& a, int64_t head, int64_t
 // instantiations, 0 for the generic one.
 // BPW: all code words of the blocks are requested before the first comparison, and each
 // scalar-loaded query word serves BPW keys per lane.
-template <int KT, int WDT, int LT, int BPW, class Emit>
+template <int KT, int WDT, int LT, int BPW, bool DBG, class Emit>
 __device__ inline void scan_blocks(const AttnArgs& a, int unit, int64_t blk0, int lane, int h_begin, int h_end, Emit emit) {
   constexpr bool kGeneric = (KT == 0);
   const int64_t nblk = key_blocks(a.n);
@@ -204,7 +208,7 @@ __device__ inline void scan_blocks(const AttnArgs& a, int unit, int64_t blk0, in
 #pragma unroll
     for (int j = 0; j < BPW; ++j) {
       const int64_t blk = blk0 + j;
-      if (blk < nblk) emit(h, blk, report_block(a, head0 + h, blk, lane, cnt[j]));
+      if (blk < nblk) emit(h, blk, report_block<DBG>(a, head0 + h, blk, lane, cnt[j]));
     }
   }
 }

@@ -451,7 +451,7 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
   const int64_t app_blk = a.blk_begin + (int64_t)slice * 16 + wave;
   if (slice < a.lg_app_runs && app_blk < key_blocks(a.n)) {
     const int hg = (int)(bh % a.Hq) % G;
-    scan_blocks<KT, WDT, LT, 1>(a, unit, app_blk, lane, hg, hg + 1, [&](int, int64_t, uint64_t m) { app_mask = m; });
+    scan_blocks<KT, WDT, LT, 1, true>(a, unit, app_blk, lane, hg, hg + 1, [&](int, int64_t, uint64_t m) { app_mask = m; });
   }
   if (tid < a.NQ) qs[tid] = qword;
   __syncthreads();

@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
   if (blk0 >= nblk) return;
   const int G = a.Hq / a.Hkv;
   const int64_t head0 = (int64_t)(unit / a.Hkv) * a.Hq + (int64_t)(unit % a.Hkv) * G;
-  scan_blocks<KT, WDT, LT, BPW>(a, unit, blk0, lane, 0, G, [&](int h, int64_t blk, uint64_t m) {
+  scan_blocks<KT, WDT, LT, BPW, true>(a, unit, blk0, lane, 0, G, [&](int h, int64_t blk, uint64_t m) {
     if (lane == 0) a.masks[(head0 + h) * nblk + blk] = m;
   });
 }
@@ -132,7 +132,8 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
 // the runs of their KV head (key j to run j mod runs) and join the gather batches there, so
 // they cost neither workgroups nor batches nor partials of their own.
 // One partial per (head, run).
-template <int KT, int WDT, int LT, bool FP32>
+// DBG: with the debug outputs (counts, candidate lists).
+template <int KT, int WDT, int LT, bool FP32, bool DBG>
 __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
   constexpr int kIt = FP32 ? (kFusedIters + 1) / 2 : kFusedIters;   // the same registers per batch
   __shared__ uint64_t smask[8][kFusedBlocks];
@@ -150,7 +151,7 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
   for (int j = 0; j < wave_blocks; ++j) {
     const int bi = wave * wave_blocks + j;
     if (blk0 + bi < nblk) {
-      scan_blocks<KT, WDT, LT, 1>(a, unit, blk0 + bi, lane, 0, G, [&](int h, int64_t, uint64_t m) {
+      scan_blocks<KT, WDT, LT, 1, DBG>(a, unit, blk0 + bi, lane, 0, G, [&](int h, int64_t, uint64_t m) {
         if (lane == 0) smask[h][bi] = m;
       });
     } else if (lane < G) {
@@ -158,10 +159,18 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
     }
   }
   __syncthreads();
+  // The gather reads its arguments from the kernel argument segment again, through a pointer the
+  // compiler cannot trace back: otherwise it loads them all at the start of the kernel and keeps
+  // them in scalar registers across the scan, whose query words then no longer fit (50 spills,
+  // a reload on every third instruction of the compare loop).
+  typedef const AttnArgs __attribute__((address_space(4))) * const_args_ptr;
+  const_args_ptr kp = (const_args_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(kp));
+  const AttnArgs& ga = *(const AttnArgs*)kp;
   uint16_t* list = lists[wave];
   for (int h = wave; h < G; h += 4) {
     HeadVectors<FP32> hv;
-    request_head_vectors<FP32>(a, unit, head0 + h, hv);
+    request_head_vectors<FP32>(ga, unit, head0 + h, hv);
     // ---- the ballots of head h as an index list (wavefront prefix sum) ----
     uint64_t m = lane < run_blocks ? smask[h][lane] : 0;
     const int c = __popcll(m);
@@ -181,13 +190,13 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
     __builtin_amdgcn_wave_barrier();
     // static keys run, run + nruns, ... ride along behind the sampled ones
-    const int nst = static_share(a, run, nruns);
-    gather_estimate_wave<FP32, kIt>(a, unit, head0 + h, total + nst, total, hv,
+    const int nst = static_share(ga, run, nruns);
+    gather_estimate_wave<FP32, kIt>(ga, unit, head0 + h, total + nst, total, hv,
                                     [&](int cc) {
                                       return cc < total ? blk0 * kBlockKeys + (int64_t)list[cc]
-                                                        : static_key(a, run + (int64_t)(cc - total) * nruns);
+                                                        : static_key(ga, run + (int64_t)(cc - total) * nruns);
                                     },
-                                    a.partial + ((head0 + h) * a.f_nranges + run) * kPartialStride);
+                                    ga.partial + ((head0 + h) * ga.f_nranges + run) * kPartialStride);
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
     __builtin_amdgcn_wave_barrier();
   }
@@ -295,22 +304,26 @@ static hipError_t launch_merge(const AttnArgs& a, int64_t heads, hipStream_t s, 
   return hipGetLastError();
 }
 
-static hipError_t launch_scan_gather(const AttnArgs& a, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
-  const dim3 block(256), grid((unsigned)a.f_nranges, (unsigned)(a.B * a.Hkv));
-#define MP_TUNED(KT, LL)                                                                            \
-  if (a.K == KT && a.L == LL) {                                                                     \
-    if (a.is_fp32)                                                                                  \
-      launch_timed(scan_gather_kernel<KT, (LL + 31) / 32, LL - 32 * ((LL + 31) / 32 - 1), true>,    \
-                   grid, block, s, start, stop, a);                                                 \
-    else                                                                                            \
-      launch_timed(scan_gather_kernel<KT, (LL + 31) / 32, LL - 32 * ((LL + 31) / 32 - 1), false>,   \
-                   grid, block, s, start, stop, a);                                                 \
-    return hipGetLastError();                                                                       \
+template <int KT, int WDT, int LT>
+static void launch_scan_gather_for(const AttnArgs& a, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
+  const dim3 block(256);
+  const bool dbg = a.dbg_counts || a.dbg_cand;
+  if (a.is_fp32) {
+    if (dbg) launch_timed(scan_gather_kernel<KT, WDT, LT, true, true>, grid, block, s, start, stop, a);
+    else launch_timed(scan_gather_kernel<KT, WDT, LT, true, false>, grid, block, s, start, stop, a);
+  } else {
+    if (dbg) launch_timed(scan_gather_kernel<KT, WDT, LT, false, true>, grid, block, s, start, stop, a);
+    else launch_timed(scan_gather_kernel<KT, WDT, LT, false, false>, grid, block, s, start, stop, a);
   }
-  MP_TUNED(10, 150) MP_TUNED(9, 120) MP_TUNED(10, 170) MP_TUNED(8, 75)
-#undef MP_TUNED
-  if (a.is_fp32) launch_timed(scan_gather_kernel<0, 0, 0, true>, grid, block, s, start, stop, a);
-  else launch_timed(scan_gather_kernel<0, 0, 0, false>, grid, block, s, start, stop, a);
+}
+
+static hipError_t launch_scan_gather(const AttnArgs& a, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
+  const dim3 grid((unsigned)a.f_nranges, (unsigned)(a.B * a.Hkv));
+  if (a.K == 10 && a.L == 150) launch_scan_gather_for<10, 5, 22>(a, grid, s, start, stop);
+  else if (a.K == 9 && a.L == 120) launch_scan_gather_for<9, 4, 24>(a, grid, s, start, stop);
+  else if (a.K == 10 && a.L == 170) launch_scan_gather_for<10, 6, 10>(a, grid, s, start, stop);
+  else if (a.K == 8 && a.L == 75) launch_scan_gather_for<8, 3, 11>(a, grid, s, start, stop);
+  else launch_scan_gather_for<0, 0, 0>(a, grid, s, start, stop);
   return hipGetLastError();
 }
 
