@@ -105,18 +105,24 @@ __device__ inline void load_code_block(const uint32_t* blkp, int lane, uint32_t 
   }
 }
 
-// Reports the keys of block `blk` that query head `head` samples (lane = key, cnt = its number
-// of colliding tables): the ballot of the sampled keys, plus the optional debug outputs.
-// DBG = false leaves the debug outputs out (and their pointers out of the scalar registers).
-template <bool DBG>
-__device__ inline uint64_t report_block(const AttnArgs& a, int64_t head, int64_t blk, int lane, uint32_t cnt) {
+// Lanes of block `blk` that hold a real key outside the static set (lane = key): what a query
+// head can sample there.
+__device__ inline uint64_t eligible_keys(const AttnArgs& a, int64_t blk, int lane) {
   const int64_t i = blk * kBlockKeys + lane;
-  const bool valid = i < a.n;
-  const bool in_T = i < a.n_sink || i >= a.n - a.n_local;
-  const bool hit = valid && !in_T && (a.tau <= 0 || (int)cnt >= a.tau);
-  const uint64_t m = __ballot(hit);
+  return __ballot(i < a.n && !(i < a.n_sink || i >= a.n - a.n_local));
+}
+
+// The keys of block `blk` that query head `head` samples, as a ballot (lane = key, cnt = its
+// number of colliding tables, eligible = eligible_keys of the block); with DBG also the optional
+// debug outputs (DBG = false keeps their pointers out of the scalar registers).
+template <bool DBG>
+__device__ inline uint64_t report_block(const AttnArgs& a, int64_t head, int64_t blk, int lane, uint32_t cnt,
+                                        uint64_t eligible) {
+  const uint64_t m = a.tau <= 0 ? eligible : (__ballot((int)cnt >= a.tau) & eligible);
   if constexpr (DBG) {
-    if (a.dbg_counts && valid) a.dbg_counts[head * a.n + i] = (uint16_t)cnt;
+    const int64_t i = blk * kBlockKeys + lane;
+    const bool hit = (m >> lane) & 1;
+    if (a.dbg_counts && i < a.n) a.dbg_counts[head * a.n + i] = (uint16_t)cnt;
     if (a.dbg_cand && hit) {
       const int pos = atomicAdd(&a.dbg_ncand[head], 1);
       if (pos < a.dbg_cand_cap) a.dbg_cand[head * a.dbg_cand_cap + pos] = (int32_t)i;
@@ -167,6 +173,9 @@ __device__ inline void scan_blocks(const AttnArgs& a, int unit, int64_t blk0, in
     }
   }
 
+  uint64_t eligible[BPW];
+#pragma unroll
+  for (int j = 0; j < BPW; ++j) eligible[j] = blk0 + j < nblk ? eligible_keys(a, blk0 + j, lane) : 0ull;
 #pragma unroll 1
   for (int h = h_begin; h < h_end; ++h) {
     const const_u32_ptr qh = qc + h * NQ;
@@ -208,7 +217,7 @@ __device__ inline void scan_blocks(const AttnArgs& a, int unit, int64_t blk0, in
 #pragma unroll
     for (int j = 0; j < BPW; ++j) {
       const int64_t blk = blk0 + j;
-      if (blk < nblk) emit(h, blk, report_block<DBG>(a, head0 + h, blk, lane, cnt[j]));
+      if (blk < nblk) emit(h, blk, report_block<DBG>(a, head0 + h, blk, lane, cnt[j], eligible[j]));
     }
   }
 }
