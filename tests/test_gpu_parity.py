@@ -70,6 +70,7 @@ def run_case(oracle, w: wl.Workload, seed=0, alpha=0.8, use_mu=True, n_cap=None,
         assert res["ncand"][b, h] == ref["S"][b][h].size
         np.testing.assert_array_equal(res["S"][b][h], ref["S"][b][h])
         worst = max(worst, rel_err(res["out"][b, h][None], ref["out"][b, h][None]))
+    print(f"   worst output error against the oracle {worst:.2e} (tolerance {TOL:.0e})", flush=True)
     assert worst <= TOL, worst
     # production call (no debug outputs) gives the same result
     res2 = s.attend(debug=False)
