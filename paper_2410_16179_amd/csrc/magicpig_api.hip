@@ -86,11 +86,18 @@ AttnWs ws_attention_layout(const magicpig_params* p) {
   w.n_static = st < p->n_ctx ? st : p->n_ctx;
   w.nranges = w.nscan + (int)((w.n_static + mp::kStaticPerRange - 1) / mp::kStaticPerRange);
   // the one-launch scan + gather: one partial per run and head
-  // runs of 16 key blocks per workgroup when that still fills the chip, shorter runs otherwise
+  // The shortest runs (4 wave_blocks key blocks per workgroup) whose workgroups are all resident
+  // at once, give or take a dozen: a second, mostly empty round of workgroups would
+  // start late and end last (measured at 8 KV heads: 100000 keys 48.6 -> 44.8 us per step, 65536
+  // keys 36.1 -> 33.7, 32768 keys 27.4 -> 23.9 against runs of 16, 8 or 4 blocks chosen to fill
+  // the chip at least once).  When even the longest runs do not fit (large batches) the rounds
+  // are many anyway: 16 blocks.
   const int64_t units = (int64_t)p->batch * p->n_kv_heads;
-  w.f_wave_blocks = mp::kFusedWaveBlocks;
-  while (w.f_wave_blocks > 1 && units * ((nblk + 4 * w.f_wave_blocks - 1) / (4 * w.f_wave_blocks)) < mp::kFusedFill)
-    w.f_wave_blocks /= 2;
+  auto groups = [&](int wb) { return units * ((nblk + 4 * wb - 1) / (4 * wb)); };
+  const int64_t fits = mp::kFusedFill + mp::kFusedFill / 64;   // 780: a dozen late workgroups cost less than longer runs
+  w.f_wave_blocks = 1;
+  while (w.f_wave_blocks < mp::kFusedWaveBlocks && groups(w.f_wave_blocks) > fits) ++w.f_wave_blocks;
+  if (groups(w.f_wave_blocks) > fits) w.f_wave_blocks = 4;
   w.f_nranges = (int)((nblk + 4 * w.f_wave_blocks - 1) / (4 * w.f_wave_blocks));
   // lookup + gather in one launch: 16 partials per slice
   const int lg = (int)((nblk + mp::kLgSliceBlocks - 1) / mp::kLgSliceBlocks) * 16;

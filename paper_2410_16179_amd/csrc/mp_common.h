@@ -160,7 +160,7 @@ constexpr int kLgWaveBlocks = 16;     // lookup + gather in one launch: key bloc
 constexpr int kLgSliceBlocks = 16 * kLgWaveBlocks;   // and per workgroup (16 wavefronts): one build window
 static_assert(kLgSliceBlocks * kBlockKeys == kBuildWindow, "a lookup slice is a window of the table build");
 // the one-launch scan + gather: four wavefronts per workgroup
-constexpr int kFusedWaveBlocks = 4;           // most key blocks a wavefront scans, one after the other
+constexpr int kFusedWaveBlocks = 6;           // most key blocks a wavefront scans, one after the other
 constexpr int kFusedBlocks = 4 * kFusedWaveBlocks;        // most key blocks per workgroup
 constexpr int kFusedFill = 768;               // workgroups of it that are resident at once (3 per compute unit)
 constexpr int kFusedIters = 8;             // its gather batch: rows per quarter wavefront

@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
   const int G = a.Hq / a.Hkv;
   const int64_t head0 = (int64_t)(unit / a.Hkv) * a.Hq + (int64_t)(unit % a.Hkv) * G;
   const int64_t nblk = key_blocks(a.n);
-  const int wave_blocks = a.f_wave_blocks;                 // 1, 2 or 4: key blocks per wavefront
+  const int wave_blocks = a.f_wave_blocks;                 // 1 .. kFusedWaveBlocks key blocks per wavefront
   const int run_blocks = 4 * wave_blocks;
   const int64_t blk0 = (int64_t)run * run_blocks;
 #pragma unroll 1
@@ -175,12 +175,13 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
     uint64_t m = lane < run_blocks ? smask[h][lane] : 0;
     const int c = __popcll(m);
     int incl = c;
+    static_assert(kFusedBlocks <= 32, "the ballots of a run are summed over 32 lanes");
 #pragma unroll
-    for (int o = 1; o < kFusedBlocks; o <<= 1) {
+    for (int o = 1; o < 32; o <<= 1) {
       const int v = __shfl_up(incl, o);
       if (lane >= o) incl += v;
     }
-    const int total = __shfl(incl, kFusedBlocks - 1);
+    const int total = __shfl(incl, 31);
     int pos = incl - c;
     while (m) {
       const int bit = __ffsll((unsigned long long)m) - 1;
