@@ -125,7 +125,7 @@ struct AttnArgs {
   int nscan;                 // runs of kRangeBlocks key blocks per head
   int64_t n_static;          // keys in the static set T
   // scan and gather in one launch: one workgroup, and one partial per head, for every run of
-  // 4 * f_wave_blocks key blocks (f_wave_blocks: key blocks per wavefront, 1, 2 or 4)
+  // 4 * f_wave_blocks key blocks (f_wave_blocks: key blocks per wavefront, 1 .. kFusedWaveBlocks)
   int f_nranges, f_wave_blocks;
   // lookup + gather in one launch: slices of the indexed range; the first lg_app_runs of them
   // also take a run of 16 appended key blocks each

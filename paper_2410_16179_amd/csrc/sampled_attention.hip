@@ -115,7 +115,7 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
 }
 
 // Scan and gather in one launch (the whole context is scanned, no hash tables): a workgroup of
-// four wavefronts compares a run of up to kFusedBlocks = 16 consecutive code blocks with the G
+// four wavefronts compares a run of up to kFusedBlocks = 24 consecutive code blocks with the G
 // heads' codes (scan_blocks, f_wave_blocks blocks per wavefront one after the other), leaves the
 // ballots in LDS, and wavefront h then gathers and weighs the keys that head h samples from the
 // run (16 blocks: about 17 at a sampling rate of 1.6 %, one batch of the 32-row gather).  As
@@ -123,10 +123,10 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
 // (ballots, then rows) on an idle memory system; here the rows of one workgroup travel while
 // the others still stream codes, and only the gather of the last workgroups is exposed
 // (measured at 32 heads x 98304 keys: 33 us against 25.6 + 13.7 us).  The host picks the run
-// length: 16 blocks when that still gives the chip its 768 workgroups, 8 or 4 for shorter
-// contexts.  At the long-context shapes shorter runs measured the same kernel time but cost
-// more partials and gather batches; the 142 registers of this form (three wavefronts per SIMD)
-// measured faster than the same kernel held to 128.
+// length, 4 to 24 blocks: the shortest whose workgroups are all resident at once (16 blocks at
+// that shape).  Shorter runs measured the same kernel time there but cost more partials and
+// gather batches; the 143 registers of this form (three wavefronts per SIMD) measured faster
+// than the same kernel held to 128.
 // The grid is one workgroup per run (at 8 KV heads x 98304 keys: 768, exactly what is resident
 // at once; workgroups that start late end last).  The keys of the static set T are dealt over
 // the runs of their KV head (key j to run j mod runs) and join the gather batches there, so
