@@ -52,3 +52,12 @@ def test_c3_ragged_context_in_a_larger_cache(oracle):
     heads = [(0, h) for h in (28, 29, 30, 31)]
     ref, res, worst = run_case(oracle, w, heads=heads, n_cap=98304, oracle_codes_too=False)
     assert np.isfinite(res["out"]).all()
+
+
+def test_100000_keys_runs_of_twenty_blocks(oracle):
+    # 8 KV heads x 100000 keys: runs of 16 key blocks would leave a few workgroups for a second
+    # round, so the scan + gather takes runs of 20 (five per wavefront), the last one partial
+    w = wl.scaled(wl.CONFIGS["C3"], n_ctx=100000)
+    heads = [(0, h) for h in (12, 13, 14, 15)]
+    ref, res, worst = run_case(oracle, w, heads=heads, oracle_codes_too=False)
+    assert np.isfinite(res["out"]).all()
