@@ -347,10 +347,12 @@ hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, 
     const int app_runs = (int)((key_blocks(a.n) - b.blk_begin + 15) / 16);
     // One launch for lookup, gather, the static set and the few keys appended since the build
     // pays while its workgroups (one per head and slice, one per compute unit at a time) are
-    // few: it removes launches and round trips from a latency-bound step.  With many heads the
-    // step is throughput-bound, and separate lookup and gather launches, each filling the chip
-    // with its own kind of work, measured 35-40 % faster (batch 16 x 65536 keys, batch 8 x 131072).
-    const bool few = heads * nslices <= 2 * kNumCU;
+    // resident all at once: it removes launches and round trips from a latency-bound step.  Beyond
+    // that a second round of workgroups costs more than the launches saved (64 heads x 98304
+    // keys: 42.9 against 37.9 us per step), and with many heads the step is throughput-bound:
+    // separate lookup and gather launches, each filling the chip with its own kind of work,
+    // measured 35-40 % faster (batch 16 x 65536 keys, batch 8 x 131072).
+    const bool few = heads * nslices <= kNumCU;
     if (lookup && few && !a.dbg_counts && (a.tau == 1 || a.tau == 2) && app_runs <= nslices) {
       b.nranges = nslices * 16;
       if ((e = launch_lookup_gather(b, *tables, nslices, app_runs, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr)) != hipSuccess)
