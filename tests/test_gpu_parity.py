@@ -149,7 +149,9 @@ def test_full_batches_many_query_vectors(oracle):
 
 @pytest.mark.parametrize("K,L,Hq,Hkv,dtype", [(7, 65, 4, 2, "bf16"), (3, 33, 2, 2, "fp32"),
                                               (16, 40, 8, 1, "bf16"), (1, 1, 1, 1, "fp32"),
-                                              (5, 512, 2, 1, "bf16")])
+                                              (5, 512, 2, 1, "bf16"),
+                                              # the larger tables of the paper's hyper-parameter study
+                                              (11, 300, 8, 2, "bf16"), (10, 220, 8, 2, "bf16")])
 def test_generic_table_shapes(oracle, K, L, Hq, Hkv, dtype):
     w = wl.Workload("gen", 1, Hq, Hkv, 1500, K, L, dtype, (8,))
     run_case(oracle, w)
