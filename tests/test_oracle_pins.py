@@ -30,6 +30,63 @@ def f32(rng, *shape):
     return rng.standard_normal(shape).astype(np.float32)
 
 
+# ---- key centering vector, Sec. 4.3 "Data pre-processing" ------------------------------
+def test_key_mean_hand_example_with_exact_rationals(oracle):
+    # four keys of three coordinates; expected values written out by hand as exact fractions
+    Kmat = np.array([[1.0, -2.0, 0.5],
+                     [3.0, 4.0, 0.25],
+                     [-1.0, 7.0, 0.125],
+                     [5.0, -1.0, 0.0625]], np.float32)
+    expected = [Fraction(8, 4), Fraction(8, 4), Fraction(15, 16) / 4]      # column sums / n
+    got = oracle.key_mean(Kmat)
+    assert got.dtype == np.float64 and got.shape == (3,)
+    assert [Fraction(float(v)) for v in got] == expected                   # exact: dyadic values
+    # one mean per coordinate over the keys, not one per key over the coordinates
+    assert oracle.key_mean(np.ones((5, 2), np.float32) * np.array([1.0, 3.0], np.float32)).tolist() == [1.0, 3.0]
+
+
+def test_key_mean_runs_over_every_key_with_divisor_n(oracle):
+    # sink keys (first 4), the local window (last 64) and the keys in between all count, and the
+    # divisor is the number of keys n: each alternative reading moves the expected value
+    n, d, n_sink, n_local = 200, 4, 4, 64
+    Kmat = np.zeros((n, d), np.float32)
+    Kmat[:n_sink, 0] = 50.0                 # only the sink keys are non-zero in coordinate 0
+    Kmat[n - n_local:, 1] = 25.0            # only the local window in coordinate 1
+    Kmat[n_sink:n - n_local, 2] = 4.0       # only the LSH-eligible keys in coordinate 2
+    Kmat[:, 3] = np.arange(n, dtype=np.float32)
+    mu = oracle.key_mean(Kmat)
+    assert mu[0] == 50.0 * n_sink / n       # would be 0 if sink keys were left out
+    assert mu[1] == 25.0 * n_local / n      # would be 0 if the local window were left out
+    assert mu[2] == 4.0 * (n - n_sink - n_local) / n    # would be 4 over the eligible keys only
+    assert mu[3] == (n - 1) / 2.0           # (n-1)/2 with divisor n; n/2 with divisor n-1
+    # against an independent routine on random data (math.fsum: correctly rounded column sums)
+    rng = np.random.default_rng(7)
+    R = f32(rng, 333, 5)
+    ref = [math.fsum(float(x) for x in R[:, j]) / 333 for j in range(5)]
+    np.testing.assert_allclose(oracle.key_mean(R), ref, rtol=1e-14)
+    # float32 inputs are averaged in float64: a float32 running sum would lose the small terms
+    big = np.array([[2.0 ** 24], [1.0], [1.0], [-(2.0 ** 24)]], np.float32)
+    assert oracle.key_mean(big)[0] == 0.5
+
+
+def test_key_mean_of_no_keys_is_zero(oracle):
+    mu = oracle.key_mean(np.zeros((0, 128), np.float32))
+    assert mu.shape == (128,) and not mu.any()
+
+
+def test_decode_step_centers_with_the_mean_of_all_keys(oracle):
+    # decode_step without an explicit mu must use key_mean over all n keys, rounded to float32
+    rng = np.random.default_rng(11)
+    Kc = f32(rng, 1, 1, 90, 8) + np.float32(3.0)
+    Vc = f32(rng, 1, 1, 90, 8)
+    q = f32(rng, 1, 1, 8)
+    W = f32(rng, 8, 12)
+    r = oracle.decode_step(q, Kc, Vc, W, 3, 4, n_sink=2, n_local=5)
+    hand = (Kc[0, 0].astype(np.float64).sum(axis=0) / 90).astype(np.float32)
+    np.testing.assert_array_equal(r["mu"][0, 0], hand)
+    np.testing.assert_array_equal(r["key_codes"][0, 0], oracle.hash_keys(Kc[0, 0], W, hand, 3, 4))
+
+
 # ---- P1: per-hyperplane agreement probability, Sec. 2.2 -------------------------------
 @pytest.mark.parametrize("deg", [30, 60, 90, 120, 150])
 def test_agreement_probability_matches_empirical_hyperplanes(oracle, deg):
