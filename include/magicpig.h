@@ -13,10 +13,11 @@
  *  - `params` is HOST memory, read during the call only.  Every other pointer is a
  *    DEVICE pointer owned by the caller (the library allocates and frees nothing; the
  *    only state it keeps is the per-thread event setting of
- *    magicpig_profile_stage_events and the last HIP error).  `workspace` is
- *    caller-owned device scratch of at least magicpig_workspace_bytes(params) bytes,
- *    256-byte aligned; its contents need not be preserved or initialised between calls,
- *    and two calls that share it must be ordered on one stream.
+ *    magicpig_profile_stage_events and the last HIP error).  `workspace` is caller-owned device scratch, 16-byte
+ *    aligned; magicpig_workspace_bytes(params) bytes are enough for every call (each call
+ *    checks only what it needs itself: query hashing and the hashing of a few appended keys
+ *    need none and accept NULL); its contents need not be preserved or initialised between
+ *    calls, and two calls that share it must be ordered on one stream.
  *  - `hip_stream` is a hipStream_t (NULL = default stream).  Calls enqueue work and
  *    return without synchronising.
  *  - Return value: MAGICPIG_OK or a negative status.  Arguments are validated before any
@@ -37,6 +38,9 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+
+/* The library is built with hidden symbol visibility; these entry points are what it exports. */
+#define MAGICPIG_API __attribute__((visibility("default")))
 
 enum { MAGICPIG_BF16 = 0, MAGICPIG_FP32 = 1 };
 
@@ -64,6 +68,14 @@ typedef struct magicpig_params {
   int64_t k_stride_b, k_stride_h, k_stride_n;   /* element strides of the K cache */
   int64_t v_stride_b, v_stride_h, v_stride_n;   /* element strides of the V cache; the decode
                          step needs row strides (*_stride_n) below 2^31 elements */
+  const int64_t* n_ctx_dev;   /* NULL, or a DEVICE pointer to the context length of the running
+                         decode loop (Algorithm 1 is run once per generated token: the context grows
+                         by one key per step).  When set, magicpig_hash_decode_step and
+                         magicpig_sampled_attention[_tables] read the length from there when
+                         their kernels run, so that one captured HIP graph serves every step of the
+                         loop; n_ctx is then the largest value the word may hold (grids and
+                         workspace are sized for it; larger values are clamped to it).  The other
+                         calls ignore it. */
 } magicpig_params;
 
 /* ---- packed code layout (part of the contract: the caller stores codes between calls) ----
@@ -85,20 +97,22 @@ typedef struct magicpig_params {
  * wavefront reads a contiguous 256*NW-byte block.  magicpig_key_code_index() evaluates
  * this formula.
  */
-size_t magicpig_code_words_per_key(const magicpig_params* params);     /* NW */
-size_t magicpig_code_words_per_query(const magicpig_params* params);   /* NQ */
-size_t magicpig_key_code_bytes(const magicpig_params* params);    /* whole key-code buffer  */
-size_t magicpig_query_code_bytes(const magicpig_params* params);
+MAGICPIG_API size_t magicpig_code_words_per_key(const magicpig_params* params);     /* NW */
+MAGICPIG_API size_t magicpig_code_words_per_query(const magicpig_params* params);   /* NQ */
+MAGICPIG_API size_t magicpig_key_code_bytes(const magicpig_params* params);    /* whole key-code buffer  */
+MAGICPIG_API size_t magicpig_query_code_bytes(const magicpig_params* params);
 /* u32 index of word x of key i of (b, g) in the key-code buffer; (size_t)-1 if out of range */
-size_t magicpig_key_code_index(const magicpig_params* params, int32_t b, int32_t g,
+MAGICPIG_API size_t magicpig_key_code_index(const magicpig_params* params, int32_t b, int32_t g,
                                int64_t key, int32_t word);
-/* Scratch needed by any of the calls below for these params (0 on invalid params). */
-size_t magicpig_workspace_bytes(const magicpig_params* params);
+/* Scratch that is enough for any of the calls below with these params (0 on invalid params):
+ * the largest of what the key mean, the prefill key hashing (which grows with n_cap) and the
+ * decode step need. */
+MAGICPIG_API size_t magicpig_workspace_bytes(const magicpig_params* params);
 
 /* Key centering vector (Sec. 4.3 "Data pre-processing"): mu[b,g,:] = (1/n_ctx) sum_i k_i over
  * keys [0, n_ctx) of each (batch, KV head), accumulated in float32 per row group and float64
  * across groups, rounded to float32.  mu_out [batch, n_kv_heads, 128] float32. */
-int magicpig_key_mean(const magicpig_params* params, const void* K_cache, float* mu_out,
+MAGICPIG_API int magicpig_key_mean(const magicpig_params* params, const void* K_cache, float* mu_out,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* SimHash codes of cached keys (Sec. 4.3 "Hash function selection"; Algorithm 1 input HT):
@@ -108,7 +122,7 @@ int magicpig_key_mean(const magicpig_params* params, const void* K_cache, float*
  * summation order).  mu may be NULL (no centering).  Requires first_key + n_keys <= n_cap;
  * n_ctx is not consulted, so keys can be appended with a frozen mu.  Writes only the words
  * of those keys. */
-int magicpig_hash_keys(const magicpig_params* params, const void* K_cache, const float* mu,
+MAGICPIG_API int magicpig_hash_keys(const magicpig_params* params, const void* K_cache, const float* mu,
                        const void* W, int64_t first_key, int64_t n_keys, uint32_t* key_codes,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
@@ -118,10 +132,10 @@ int magicpig_hash_keys(const magicpig_params* params, const void* K_cache, const
  * global list overflowed and the whole call was redone by the float64 kernel; total number of
  * pairs whose matrix-core result was too close to zero and was re-evaluated exactly }.
  * (size_t)-1 when the params are invalid or not bf16. */
-size_t magicpig_hash_keys_stats_offset(const magicpig_params* params);
+MAGICPIG_API size_t magicpig_hash_keys_stats_offset(const magicpig_params* params);
 
 /* SimHash codes of the decode queries (Algorithm 1 "Encode(q, W)"); queries are not centered. */
-int magicpig_hash_query(const magicpig_params* params, const void* q, const void* W,
+MAGICPIG_API int magicpig_hash_query(const magicpig_params* params, const void* q, const void* W,
                         uint32_t* q_codes, void* workspace, size_t workspace_bytes,
                         void* hip_stream);
 
@@ -129,8 +143,11 @@ int magicpig_hash_query(const magicpig_params* params, const void* q, const void
  * hash structure, "Encode(q, W)" codes its query): magicpig_hash_keys for the keys
  * [first_key, first_key + n_keys) (normally the one key the step appended) together with
  * magicpig_hash_query, same arguments, same results.  With more than 128 key vectors
- * (batch * n_kv_heads * n_keys) it simply makes the two calls one after the other. */
-int magicpig_hash_decode_step(const magicpig_params* params, const void* q, const void* K_cache,
+ * (batch * n_kv_heads * n_keys) it simply makes the two calls one after the other.
+ * With params->n_ctx_dev set the keys are the newest n_keys >= 1 keys of the context as it stands
+ * when the kernel runs, [*n_ctx_dev - n_keys, *n_ctx_dev), and first_key is ignored (nothing is
+ * coded if that range does not lie inside [0, n_cap)); at most 128 key vectors then. */
+MAGICPIG_API int magicpig_hash_decode_step(const magicpig_params* params, const void* q, const void* K_cache,
                               const float* mu, const void* W, int64_t first_key, int64_t n_keys,
                               uint32_t* key_codes, uint32_t* q_codes, void* workspace,
                               size_t workspace_bytes, void* hip_stream);
@@ -147,7 +164,7 @@ int magicpig_hash_decode_step(const magicpig_params* params, const void* q, cons
  * dbg_cand [batch, n_q_heads, dbg_cand_cap] int32 receives S_h in unspecified order and
  * dbg_ncand [batch, n_q_heads] int32 its size (entries beyond the capacity are counted but
  * not stored; dbg_ncand must be zeroed by the caller). */
-int magicpig_sampled_attention(const magicpig_params* params, const void* q, const void* K_cache,
+MAGICPIG_API int magicpig_sampled_attention(const magicpig_params* params, const void* q, const void* K_cache,
                                const void* V_cache, const float* mu, const uint32_t* key_codes,
                                const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
                                int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
@@ -170,14 +187,14 @@ int magicpig_sampled_attention(const magicpig_params* params, const void* q, con
  * rebuilt from the packed
  * key codes; they are not extended incrementally: keys appended after a build are found by
  * scanning their packed codes (see n_indexed below) until the next build. */
-size_t magicpig_table_bytes(const magicpig_params* params);
+MAGICPIG_API size_t magicpig_table_bytes(const magicpig_params* params);
 /* magicpig_build_tables works with any workspace (NULL included).  Given one of at least
  * magicpig_table_build_workspace_bytes(params) bytes (2 bytes per key and table; 0 if tables
  * are unsupported) it first writes every key's
  * code per table there and then places the keys window by window, which is several times faster
  * than scattering them in one pass.  The resulting tables hold the same buckets either way. */
-size_t magicpig_table_build_workspace_bytes(const magicpig_params* params);
-int magicpig_build_tables(const magicpig_params* params, const uint32_t* key_codes, void* tables,
+MAGICPIG_API size_t magicpig_table_build_workspace_bytes(const magicpig_params* params);
+MAGICPIG_API int magicpig_build_tables(const magicpig_params* params, const uint32_t* key_codes, void* tables,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 /* magicpig_sampled_attention with the collision scan replaced by the table lookup for the keys
  * [0, n_indexed) the tables were built over (magicpig_build_tables with n_ctx = n_indexed and
@@ -186,7 +203,7 @@ int magicpig_build_tables(const magicpig_params* params, const uint32_t* key_cod
  * key_codes may be NULL when no block lies behind the indexed keys.  Every other argument,
  * the result and the debug outputs are as in magicpig_sampled_attention (dbg_counts is 0 for
  * indexed keys that share no bucket with the query, which is also their true count). */
-int magicpig_sampled_attention_tables(const magicpig_params* params, const void* q, const void* K_cache,
+MAGICPIG_API int magicpig_sampled_attention_tables(const magicpig_params* params, const void* q, const void* K_cache,
                                       const void* V_cache, const float* mu, const void* tables,
                                       int64_t n_indexed, const uint32_t* key_codes,
                                       const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
@@ -200,11 +217,11 @@ int magicpig_sampled_attention_tables(const magicpig_params* params, const void*
  * gather / estimator kernel, events[3] the end of the merge kernel.  magicpig_sampled_attention
  * scans and gathers in one kernel: events[0] / events[1] are its begin / end and events[2] is
  * recorded on the stream right behind it.  NULL switches it off. */
-void magicpig_profile_stage_events(void* const* events);
+MAGICPIG_API void magicpig_profile_stage_events(void* const* events);
 
-const char* magicpig_status_string(int status);
+MAGICPIG_API const char* magicpig_status_string(int status);
 /* Text of the HIP error behind the most recent MAGICPIG_LAUNCH_FAILED on this thread. */
-const char* magicpig_last_hip_error(void);
+MAGICPIG_API const char* magicpig_last_hip_error(void);
 
 #ifdef __cplusplus
 }

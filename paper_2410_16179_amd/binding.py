@@ -32,6 +32,7 @@ class magicpig_params(ctypes.Structure):
         ("n_ctx", ctypes.c_int64), ("n_cap", ctypes.c_int64),
         ("k_stride_b", ctypes.c_int64), ("k_stride_h", ctypes.c_int64), ("k_stride_n", ctypes.c_int64),
         ("v_stride_b", ctypes.c_int64), ("v_stride_h", ctypes.c_int64), ("v_stride_n", ctypes.c_int64),
+        ("n_ctx_dev", ctypes.c_void_p),
     ]
 
 
@@ -98,13 +99,19 @@ def _ptr(t) -> int | None:
     return None if t is None else t.data_ptr()
 
 
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
 def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
 def make_params(*, batch, n_q_heads, n_kv_heads, K, L, n_ctx, dtype, n_cap=None, min_hits=2,
-                n_sink=4, n_local=64, head_dim=128, k_strides=None, v_strides=None) -> magicpig_params:
-    """Parameter block; strides default to a contiguous [batch, n_kv_heads, n_cap, 128] cache."""
+                n_sink=4, n_local=64, head_dim=128, k_strides=None, v_strides=None,
+                n_ctx_dev=None) -> magicpig_params:
+    """Parameter block; strides default to a contiguous [batch, n_kv_heads, n_cap, 128] cache.
+    n_ctx_dev: an int64 device tensor holding the live context length, or None."""
     n_cap = n_ctx if n_cap is None else n_cap
     dense = (n_kv_heads * n_cap * head_dim, n_cap * head_dim, head_dim)
     ks = dense if k_strides is None else tuple(k_strides)
@@ -112,7 +119,8 @@ def make_params(*, batch, n_q_heads, n_kv_heads, K, L, n_ctx, dtype, n_cap=None,
     code = {"bf16": MAGICPIG_BF16, "fp32": MAGICPIG_FP32, torch.bfloat16: MAGICPIG_BF16,
             torch.float32: MAGICPIG_FP32}.get(dtype, dtype)
     return magicpig_params(batch, n_q_heads, n_kv_heads, head_dim, K, L, min_hits, n_sink, n_local,
-                           code, n_ctx, n_cap, ks[0], ks[1], ks[2], vs[0], vs[1], vs[2])
+                           code, n_ctx, n_cap, ks[0], ks[1], ks[2], vs[0], vs[1], vs[2],
+                           None if n_ctx_dev is None else n_ctx_dev.data_ptr())
 
 
 def magicpig_code_words_per_key(params) -> int:
@@ -162,16 +170,15 @@ def magicpig_hash_keys(params, K_cache, mu, W, first_key, n_keys, key_codes, wor
                                     workspace.numel() * workspace.element_size(), _stream()))
 
 
-def magicpig_hash_query(params, q, W, q_codes, workspace) -> None:
+def magicpig_hash_query(params, q, W, q_codes, workspace=None) -> None:
     _check(lib().magicpig_hash_query(ctypes.byref(params), _ptr(q), _ptr(W), _ptr(q_codes),
-                                     _ptr(workspace), workspace.numel() * workspace.element_size(),
-                                     _stream()))
+                                     _ptr(workspace), _nbytes(workspace), _stream()))
 
 
-def magicpig_hash_decode_step(params, q, K_cache, mu, W, first_key, n_keys, key_codes, q_codes, workspace) -> None:
+def magicpig_hash_decode_step(params, q, K_cache, mu, W, first_key, n_keys, key_codes, q_codes, workspace=None) -> None:
     _check(lib().magicpig_hash_decode_step(ctypes.byref(params), _ptr(q), _ptr(K_cache), _ptr(mu), _ptr(W),
                                            first_key, n_keys, _ptr(key_codes), _ptr(q_codes), _ptr(workspace),
-                                           workspace.numel() * workspace.element_size(), _stream()))
+                                           _nbytes(workspace), _stream()))
 
 
 def magicpig_sampled_attention(params, q, K_cache, V_cache, mu, key_codes, q_codes, out,

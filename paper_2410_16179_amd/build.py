@@ -1,27 +1,44 @@
-"""Builds libmagicpig.so (gfx950) in-tree with hipcc.  `python -m paper_2410_16179_amd.build`."""
+"""Builds libmagicpig.so (gfx950) in-tree with hipcc.  `python -m paper_2410_16179_amd.build`.
+
+Every source file is compiled to an object of its own (in parallel), then linked.  Symbols are
+hidden by default: the library exports only the entry points include/magicpig.h declares."""
 from __future__ import annotations
 
 import glob
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libmagicpig.so")
+OBJ_DIR = os.path.join(PKG, "_build")
 
 FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
     # packed-FP32 instruction selection is switched off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 ]
 
 
-def build(verbose: bool = True, extra: list[str] | None = None) -> str:
+def build(verbose: bool = True, extra: list[str] | None = None, jobs: int = 6) -> str:
     srcs = sorted(glob.glob(os.path.join(PKG, "csrc", "*.hip")))
-    cmd = ["hipcc", *FLAGS, *(extra or []), "-I", os.path.join(ROOT, "include"),
-           "-I", os.path.join(PKG, "csrc"), "-o", LIB, *srcs]
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc")]
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(OBJ_DIR, os.path.basename(src)[:-4] + ".o")
+        cmd = ["hipcc", *FLAGS, *(extra or []), *inc, "-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        objs = list(pool.map(compile_one, srcs))
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -81,6 +81,19 @@ __device__ inline float inclusion_probability(float cosv, const AttnArgs& a) {
   return sum;
 }
 
+// The context length of the step: the launch-time value, or - when the caller keeps it in device
+// memory (a decode loop replayed from a captured graph) - what that word holds now, clamped to
+// the value the launch was sized for.  The static set follows it.
+__device__ inline void resolve_context(AttnArgs& a) {
+  if (a.n_dev) {
+    int64_t n = *a.n_dev;
+    n = n < 0 ? 0 : (n > a.n ? a.n : n);
+    a.n = n;
+    const int64_t st = (int64_t)a.n_sink + a.n_local;
+    a.n_static = st < n ? st : n;
+  }
+}
+
 // Code words are read once per decode step: the non-temporal hint keeps them from displacing
 // the rest of the working set in L2 (measured: about 7 % faster scan).
 template <int NW>
@@ -122,7 +135,7 @@ __device__ inline uint64_t report_block(const AttnArgs& a, int64_t head, int64_t
   if constexpr (DBG) {
     const int64_t i = blk * kBlockKeys + lane;
     const bool hit = (m >> lane) & 1;
-    if (a.dbg_counts && i < a.n) a.dbg_counts[head * a.n + i] = (uint16_t)cnt;
+    if (a.dbg_counts && i < a.n) a.dbg_counts[head * a.dbg_stride + i] = (uint16_t)cnt;
     if (a.dbg_cand && hit) {
       const int pos = atomicAdd(&a.dbg_ncand[head], 1);
       if (pos < a.dbg_cand_cap) a.dbg_cand[head * a.dbg_cand_cap + pos] = (int32_t)i;
@@ -224,16 +237,22 @@ __device__ inline void scan_blocks(const AttnArgs& a, int unit, int64_t blk0, in
 
 // j-th key of the static set T: the sink keys, then the local window (every key when the
 // context is no longer than n_sink + n_local).
+__device__ inline int64_t static_key_of(int64_t n, int64_t n_static, int n_sink, int n_local, int64_t j) {
+  const int64_t sink_keys = n_static < n ? n_sink : n_static;
+  return j < sink_keys ? j : j + (n - n_local - n_sink);
+}
 __device__ inline int64_t static_key(const AttnArgs& a, int64_t j) {
-  const int64_t sink_keys = a.n_static < a.n ? a.n_sink : a.n_static;
-  return j < sink_keys ? j : j + (a.n - a.n_local - a.n_sink);
+  return static_key_of(a.n, a.n_static, a.n_sink, a.n_local, j);
 }
 
 // The static set dealt over `slots` gather wavefronts of a head: slot s takes the static keys
 // s, s + slots, s + 2 slots, ... (at long contexts at most one each), which ride along in the
 // batch of its sampled keys instead of costing batches of their own.
+__device__ inline int static_share_of(int64_t n_static, int slot, int slots) {
+  return slot < n_static ? (int)((n_static - slot + slots - 1) / slots) : 0;
+}
 __device__ inline int static_share(const AttnArgs& a, int slot, int slots) {
-  return slot < a.n_static ? (int)((a.n_static - slot + slots - 1) / slots) : 0;
+  return static_share_of(a.n_static, slot, slots);
 }
 
 // The query row and the centering vector of a wavefront's head, eight elements per lane (the

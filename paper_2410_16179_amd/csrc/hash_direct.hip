@@ -167,6 +167,9 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   const int w = blockIdx.x;
   const bool second = (int)blockIdx.y >= pairs0;
   const HashDirectArgs& a = second ? a1 : a0;
+  // keys of a decode step whose context length lives in device memory: the newest n_keys keys
+  const int64_t first_key = a.n_dev ? *a.n_dev - a.n_keys : a.first_key;
+  if (a.n_dev && (first_key < 0 || first_key + a.n_keys > a.n_cap)) return;   // (uniform in the workgroup)
   // vectors with a centering term cost twice the arithmetic: they are taken one per workgroup
   const int per_wg = a.mu ? 1 : 2;
   const int64_t r0 = (int64_t)((int)blockIdx.y - (second ? pairs0 : 0)) * per_wg;
@@ -222,7 +225,7 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
   for (int rr = 0; rr < 2; ++rr) {
     const int64_t r = r0 + (rr < nrow ? rr : 0);
     unit[rr] = r / a.n_keys;
-    key[rr] = a.first_key + r % a.n_keys;
+    key[rr] = first_key + r % a.n_keys;
     xb[rr] = (unit[rr] / a.n_kv_heads) * a.stride_b + (unit[rr] % a.n_kv_heads) * a.stride_h + key[rr] * a.stride_n;
   }
   // The two vectors (or the vector and its centering vector) are staged once in LDS as float32

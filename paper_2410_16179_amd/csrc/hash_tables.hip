@@ -15,7 +15,7 @@
 //   L2 (the one-pass scatter keeps thousands of lines half written per workgroup and writes
 //   each store to HBM on its own).
 //   lookup_gather_kernel  : the decode step's retrieval for min_hits 1 or 2: one workgroup per
-//       (query head, slice of 12288 keys) reads the L buckets, marks the keys of its slice in
+//       (query head, slice of 16384 keys: one window of the build) reads the L buckets, marks the keys of its slice in
 //       LDS bitmaps and gathers and weighs them right away; the few keys appended since the
 //       build are found by the collision scan in the same workgroups.
 //   table_lookup_kernel, table_lookup_bitmap_kernel: the lookup alone (hit counts per key in
@@ -207,6 +207,7 @@ __global__ __launch_bounds__(256) void ht_place_kernel(TableArgs a) {
 __global__ __launch_bounds__(1024) void table_lookup_kernel(AttnArgs a, TableArgs tb) {
   __shared__ uint32_t counters[kLookupRunKeys / 4];   // one byte per key of the run
   __shared__ uint32_t bstart[512], blen[512];
+  resolve_context(a);
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int run = blockIdx.x;
@@ -295,7 +296,7 @@ __global__ __launch_bounds__(1024) void table_lookup_kernel(AttnArgs a, TableArg
       for (int j = 0; j < 32; ++j) {
         const int64_t i = kfirst + j;
         const int cnt = (counters[tid * 8 + (j >> 2)] >> (8 * (j & 3))) & 0xff;
-        if (a.dbg_counts && i < a.n) a.dbg_counts[bh * a.n + i] = (uint16_t)cnt;
+        if (a.dbg_counts && i < a.n) a.dbg_counts[bh * a.dbg_stride + i] = (uint16_t)cnt;
         if (a.dbg_cand && ((bits >> j) & 1u)) {
           const int pos = atomicAdd(&a.dbg_ncand[bh], 1);
           if (pos < a.dbg_cand_cap) a.dbg_cand[bh * a.dbg_cand_cap + pos] = (int32_t)i;
@@ -313,6 +314,7 @@ __global__ __launch_bounds__(1024) void table_lookup_bitmap_kernel(AttnArgs a, T
   extern __shared__ uint32_t bitmap[];                  // seen[nw], twice[nw]
   __shared__ uint32_t bstart[512], blen[512];
   __shared__ uint32_t qs[256];
+  resolve_context(a);
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int64_t bh = blockIdx.x;
@@ -432,6 +434,7 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
   __shared__ uint32_t seen[kSliceWords], twice[kSliceWords];
   __shared__ uint32_t qs[256];
   __shared__ uint16_t lists[16][kLgWaveBlocks * kBlockKeys + kBlockKeys];
+  resolve_context(a);
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int slice = blockIdx.x;

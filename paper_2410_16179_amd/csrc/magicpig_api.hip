@@ -27,9 +27,11 @@ int check_params(const magicpig_params* p) {
   if (p->K < 1 || p->K > 16 || p->L < 1 || p->L > 512) return MAGICPIG_UNSUPPORTED;
   if (p->dtype != MAGICPIG_BF16 && p->dtype != MAGICPIG_FP32) return MAGICPIG_UNSUPPORTED;
   const int G = p->n_q_heads / p->n_kv_heads;
-  if (G != 1 && G != 2 && G != 4 && G != 8) return MAGICPIG_UNSUPPORTED;
+  if (G > 8) return MAGICPIG_UNSUPPORTED;                 // a workgroup keeps the ballots of at most eight heads
   if (p->n_cap > (int64_t)1 << 31) return MAGICPIG_UNSUPPORTED;
+  // one grid row per (batch, KV head); the few-vectors hashing takes two query vectors per grid row
   if ((int64_t)p->batch * p->n_kv_heads > 65535) return MAGICPIG_UNSUPPORTED;
+  if ((int64_t)p->batch * p->n_q_heads > 2 * 65535) return MAGICPIG_UNSUPPORTED;
   return MAGICPIG_OK;
 }
 
@@ -73,7 +75,12 @@ HashWs ws_hash_layout(const magicpig_params* p) {
   w.total = w.list_off + align256(w.list_cap * sizeof(unsigned long long));
   return w;
 }
-size_t ws_hash(const magicpig_params* p) { return p->dtype == MAGICPIG_BF16 ? ws_hash_layout(p).total : 256; }
+size_t ws_hash(const magicpig_params* p) { return p->dtype == MAGICPIG_BF16 ? ws_hash_layout(p).total : 0; }
+// what magicpig_hash_keys needs for n_keys keys per (batch, KV head): only the matrix-core path
+// (bf16, more vectors than the few-vectors kernel takes) uses scratch
+size_t ws_hash_for(const magicpig_params* p, int64_t n_keys) {
+  return (int64_t)p->batch * p->n_kv_heads * n_keys > kFewRows ? ws_hash(p) : 0;
+}
 
 // decode workspace: [partials | ballots]
 struct AttnWs { size_t partial_off, masks_off, total; int nranges, nscan, f_nranges, f_wave_blocks; int64_t n_static; };
@@ -163,11 +170,12 @@ int check_hash_keys_args(const magicpig_params* p, const void* K_cache, const fl
   if (st != MAGICPIG_OK) return st;
   if ((st = check_strides(p->k_stride_b, p->k_stride_h, p->k_stride_n)) != MAGICPIG_OK) return st;
   if (first_key < 0 || n_keys < 0 || first_key + n_keys > p->n_cap) return MAGICPIG_INVALID_ARG;
-  if (!W || !key_codes || !workspace || (!K_cache && n_keys > 0 && p->batch > 0)) return MAGICPIG_INVALID_ARG;
+  if (!W || !key_codes || (!K_cache && n_keys > 0 && p->batch > 0)) return MAGICPIG_INVALID_ARG;
   if (!aligned16(K_cache) || !aligned16(W) || !aligned16(key_codes) || !aligned16(workspace) ||
       (mu && !aligned16(mu)))
     return MAGICPIG_INVALID_ARG;
-  if (workspace_bytes < magicpig_workspace_bytes(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
+  const size_t need = ws_hash_for(p, n_keys);
+  if (need > 0 && (!workspace || workspace_bytes < need)) return MAGICPIG_WORKSPACE_TOO_SMALL;
   return MAGICPIG_OK;
 }
 
@@ -175,9 +183,10 @@ int check_hash_query_args(const magicpig_params* p, const void* q, const void* W
                           const void* workspace, size_t workspace_bytes) {
   const int st = check_params(p);
   if (st != MAGICPIG_OK) return st;
-  if (!W || !q_codes || !workspace || (!q && p->batch > 0)) return MAGICPIG_INVALID_ARG;
-  if (!aligned16(q) || !aligned16(W) || !aligned16(q_codes) || !aligned16(workspace)) return MAGICPIG_INVALID_ARG;
-  if (workspace_bytes < magicpig_workspace_bytes(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
+  // (query hashing uses no scratch: any workspace, NULL included, will do)
+  (void)workspace; (void)workspace_bytes;
+  if (!W || !q_codes || (!q && p->batch > 0)) return MAGICPIG_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(W) || !aligned16(q_codes)) return MAGICPIG_INVALID_ARG;
   return MAGICPIG_OK;
 }
 
@@ -195,6 +204,7 @@ mp::HashDirectArgs key_rows(const magicpig_params* p, const void* K_cache, const
   a.blocks_cap = mp::key_blocks(p->n_cap);
   a.total_rows = (int64_t)p->batch * p->n_kv_heads * n_keys;
   a.run_flag = nullptr;
+  a.n_dev = nullptr; a.n_cap = p->n_cap;
   return a;
 }
 
@@ -211,18 +221,18 @@ mp::HashDirectArgs query_rows(const magicpig_params* p, const void* q, const voi
   a.stride_b = 0; a.stride_h = 0; a.stride_n = mp::kHeadDim;
   a.blocks_cap = 0;
   a.run_flag = nullptr;
+  a.n_dev = nullptr; a.n_cap = 0;
   return a;
 }
 
-}  // namespace
-
-extern "C" {
-
+// Validation and launch of a decode step.  `scratch` receives the partials (and, for the separate
+// lookup / scan / gather launches, the ballots): scratch_bytes must cover ws_attention(p), or
+// only its partial region when ballots_needed is false (the one-launch scan + gather).
 int run_attention_impl(const magicpig_params* p, const void* q, const void* K_cache,
-                         const void* V_cache, const float* mu, const uint32_t* key_codes,
-                         const void* tables, int64_t n_indexed, const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
-                         int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
-                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+                       const void* V_cache, const float* mu, const uint32_t* key_codes,
+                       const void* tables, int64_t n_indexed, const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
+                       int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
+                       void* workspace, size_t workspace_bytes, bool ballots_needed, void* hip_stream) {
   int st = check_params(p);
   if (st != MAGICPIG_OK) return st;
   if ((st = check_strides(p->k_stride_b, p->k_stride_h, p->k_stride_n)) != MAGICPIG_OK) return st;
@@ -243,16 +253,19 @@ int run_attention_impl(const magicpig_params* p, const void* q, const void* K_ca
   if (!aligned16(q) || !aligned16(K_cache) || !aligned16(V_cache) || !aligned16(key_codes) || !aligned16(tables) ||
       !aligned16(q_codes) || !aligned16(out) || !aligned16(workspace) || (mu && !aligned16(mu)))
     return MAGICPIG_INVALID_ARG;
-  if (workspace_bytes < ws_attention(p)) return MAGICPIG_WORKSPACE_TOO_SMALL;
+  const AttnWs wl = ws_attention_layout(p);
+  if (workspace_bytes < (ballots_needed ? wl.total : wl.masks_off)) {
+    return MAGICPIG_WORKSPACE_TOO_SMALL;
+  }
   mp::AttnArgs a{};
   a.q = q; a.Kc = K_cache; a.Vc = V_cache; a.mu = mu; a.kcodes = key_codes; a.qcodes = q_codes;
-  const AttnWs wl = ws_attention_layout(p);
   char* wsb = reinterpret_cast<char*>(workspace);
   a.partial = reinterpret_cast<float*>(wsb + wl.partial_off); a.out = out;
   a.masks = reinterpret_cast<uint64_t*>(wsb + wl.masks_off);
   a.nranges = wl.nranges; a.nscan = wl.nscan; a.n_static = wl.n_static;
   a.f_nranges = wl.f_nranges; a.f_wave_blocks = wl.f_wave_blocks;
   a.dbg_counts = dbg_counts; a.dbg_cand = dbg_cand; a.dbg_ncand = dbg_ncand; a.dbg_cand_cap = dbg_cand_cap;
+  a.dbg_stride = p->n_ctx; a.n_dev = p->n_ctx_dev;
   a.is_fp32 = p->dtype == MAGICPIG_FP32;
   a.B = p->batch; a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.K = p->K; a.L = p->L;
   a.Wd = mp::table_words(p->L); a.NW = mp::code_words(p->K, p->L); a.NQ = mp::plane_words(p->K, p->L);
@@ -276,7 +289,9 @@ int run_attention_impl(const magicpig_params* p, const void* q, const void* K_ca
   return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
 }
 
+}  // namespace
 
+extern "C" {
 
 size_t magicpig_code_words_per_key(const magicpig_params* p) {
   if (check_params(p) != MAGICPIG_OK) return 0;
@@ -395,15 +410,19 @@ int magicpig_hash_decode_step(const magicpig_params* p, const void* q, const voi
                               uint32_t* q_codes, void* workspace, size_t workspace_bytes, void* hip_stream) {
   int st = check_hash_query_args(p, q, W, q_codes, workspace, workspace_bytes);
   if (st != MAGICPIG_OK) return st;
+  const bool live = p->n_ctx_dev != nullptr;             // the newest n_keys keys, wherever the context ends now
+  if (live) first_key = 0;
   if ((st = check_hash_keys_args(p, K_cache, mu, W, first_key, n_keys, key_codes, workspace, workspace_bytes)) != MAGICPIG_OK)
     return st;
+  if (live && (n_keys < 1 || (int64_t)p->batch * p->n_kv_heads * n_keys > kFewRows)) return MAGICPIG_UNSUPPORTED;
   if ((int64_t)p->batch * p->n_kv_heads * n_keys > kFewRows) {   // many keys: the two calls one after the other
     st = magicpig_hash_keys(p, K_cache, mu, W, first_key, n_keys, key_codes, workspace, workspace_bytes, hip_stream);
     if (st != MAGICPIG_OK) return st;
     return magicpig_hash_query(p, q, W, q_codes, workspace, workspace_bytes, hip_stream);
   }
   const mp::HashDirectArgs aq = query_rows(p, q, W, q_codes);
-  const mp::HashDirectArgs ak = key_rows(p, K_cache, mu, W, first_key, n_keys, key_codes);
+  mp::HashDirectArgs ak = key_rows(p, K_cache, mu, W, first_key, n_keys, key_codes);
+  ak.n_dev = p->n_ctx_dev;
   const hipError_t e = mp::launch_hash_rows(aq, &ak, reinterpret_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
 }
@@ -415,7 +434,7 @@ int magicpig_sampled_attention(const magicpig_params* p, const void* q, const vo
                                void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (p && p->n_ctx > 0 && p->batch > 0 && !key_codes) return MAGICPIG_INVALID_ARG;
   return run_attention_impl(p, q, K_cache, V_cache, mu, key_codes, nullptr, 0, q_codes, out, dbg_counts, dbg_cand,
-                       dbg_ncand, dbg_cand_cap, workspace, workspace_bytes, hip_stream);
+                            dbg_ncand, dbg_cand_cap, workspace, workspace_bytes, false, hip_stream);
 }
 
 size_t magicpig_table_bytes(const magicpig_params* p) {
@@ -456,7 +475,7 @@ int magicpig_sampled_attention_tables(const magicpig_params* p, const void* q, c
                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (p && p->n_ctx > 0 && p->batch > 0 && !tables) return MAGICPIG_INVALID_ARG;
   return run_attention_impl(p, q, K_cache, V_cache, mu, key_codes, tables, n_indexed, q_codes, out, dbg_counts, dbg_cand,
-                       dbg_ncand, dbg_cand_cap, workspace, workspace_bytes, hip_stream);
+                            dbg_ncand, dbg_cand_cap, workspace, workspace_bytes, true, hip_stream);
 }
 
 void magicpig_profile_stage_events(void* const* events) {

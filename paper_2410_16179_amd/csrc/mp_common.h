@@ -82,6 +82,11 @@ struct HashDirectArgs {
   int64_t blocks_cap;   // code blocks per unit
   int64_t total_rows;
   const int* run_flag;  // if not null the kernel does nothing unless *run_flag != 0
+  // hash_rows_kernel only: if not null, the context length in device memory; the vectors are then
+  // the newest n_keys keys [*n_dev - n_keys, *n_dev) of every unit instead of first_key ..
+  // (nothing is coded when that range does not lie inside [0, n_cap))
+  const int64_t* n_dev;
+  int64_t n_cap;
 };
 
 // Launch description of the matrix-core key hashing (bf16 keys).
@@ -116,9 +121,14 @@ struct AttnArgs {
   float* partial; float* out;
   uint64_t* masks;        // [B*Hq][key blocks] ballots of sampled + static keys
   uint16_t* dbg_counts; int32_t* dbg_cand; int32_t* dbg_ncand; int64_t dbg_cand_cap;
+  int64_t dbg_stride;     // keys per head in dbg_counts (the launch-time context length)
   int is_fp32;
   int B, Hq, Hkv, K, L, Wd, NW, NQ, tau, n_sink, n_local;
   int64_t n, blocks_cap;
+  // if not null: the context length in device memory, read by the kernels when they run (a decode
+  // loop replayed from a captured graph); `n` is then the largest value it may hold, for which
+  // grids and workspace were sized
+  const int64_t* n_dev;
   int64_t blk_begin;         // first key block the collision scan covers (blocks before it: table lookup)
   int64_t ks_b, ks_h, ks_n, vs_b, vs_h, vs_n;
   int nranges;               // partials per head: nscan runs of kRangeBlocks key blocks + static runs

@@ -17,7 +17,7 @@
 //   static set with count >= min_hits are reported as one 64-bit ballot per (head, block).
 //   No LDS, no barrier, about 60 VGPRs.
 // gather and estimate (gather_estimate_wave)
-//   One wavefront per (query head, run of 16 key blocks): the ballots are expanded into an
+//   One wavefront per (query head, run of key blocks): the ballots are expanded into an
 //   index list in LDS by a wavefront prefix sum (the static sink and local-window keys ride
 //   along in these batches, or, in gather_estimate_kernel, are taken 32 each by wavefronts of
 //   their own); rows are gathered four at a time (a quarter wavefront holds one 128-element row)
@@ -25,7 +25,7 @@
 //   the 16 lanes of a row, the inclusion probability u_i and the logit q.k/sqrt(d) - log u_i
 //   are evaluated once per candidate, and an online max/sum softmax accumulates the weighted
 //   V rows.  The wavefront stores a (max, sum, output) partial.
-// scan_gather_kernel does both for a run of 16 key blocks in one workgroup;
+// scan_gather_kernel does both for a run of 4 to 24 key blocks (chosen by the host) in one workgroup;
 // collision_scan_kernel / gather_estimate_kernel are the two as separate launches, joined by
 // the ballots in HBM.
 // merge_partials_kernel combines a head's partials (the "recursive attention" merge of
@@ -41,6 +41,7 @@ namespace mp {
 
 template <int KT, int WDT, int LT, int BPW>
 __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
+  resolve_context(a);
   // readfirstlane tells the compiler that the wavefront index (and everything derived from
   // it: KV head, query-code address) is uniform, so those loads become scalar
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -63,6 +64,7 @@ template <bool FP32> constexpr int kGatherIters = FP32 ? 4 : 8;
 template <bool FP32>
 __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
   __shared__ uint16_t lists[8][kRangeBlocks * kBlockKeys];
+  resolve_context(a);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int unit = blockIdx.y, range = blockIdx.x;
   const int b = unit / a.Hkv, g = unit % a.Hkv;
@@ -138,6 +140,8 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
   constexpr int kIt = FP32 ? (kFusedIters + 1) / 2 : kFusedIters;   // the same registers per batch
   __shared__ uint64_t smask[8][kFusedBlocks];
   __shared__ uint16_t lists[4][kFusedBlocks * kBlockKeys];
+  resolve_context(a);
+  const int64_t n_now = a.n, n_static_now = a.n_static;    // (the gather re-reads its arguments: these two it keeps)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int unit = blockIdx.y, run = blockIdx.x;
   const int nruns = gridDim.x;                             // = f_nranges
@@ -191,11 +195,12 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
     __builtin_amdgcn_wave_barrier();
     // static keys run, run + nruns, ... ride along behind the sampled ones
-    const int nst = static_share(ga, run, nruns);
+    const int nst = static_share_of(n_static_now, run, nruns);
     gather_estimate_wave<FP32, kIt>(ga, unit, head0 + h, total + nst, total, hv,
                                     [&](int cc) {
                                       return cc < total ? blk0 * kBlockKeys + (int64_t)list[cc]
-                                                        : static_key(ga, run + (int64_t)(cc - total) * nruns);
+                                                        : static_key_of(n_now, n_static_now, ga.n_sink, ga.n_local,
+                                                                        run + (int64_t)(cc - total) * nruns);
                                     },
                                     ga.partial + ((head0 + h) * ga.f_nranges + run) * kPartialStride);
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");

@@ -38,16 +38,30 @@ def pack_table_codes(codes: np.ndarray, K: int, L: int, pad_bit: int) -> np.ndar
 class Session:
     """Device buffers of one problem instance."""
 
-    def __init__(self, *, K, L, dtype, Kc, Vc, q, W, n_ctx=None, min_hits=2, n_sink=4, n_local=64):
+    def __init__(self, *, K, L, dtype, Kc, Vc, q, W, n_ctx=None, min_hits=2, n_sink=4, n_local=64,
+                 layout="dense", n_ctx_dev=None):
+        """layout "dense": K and V caches [B, Hkv, n_cap, 128]; "token_major": both caches stored
+        [B, n_cap, Hkv, row] with the heads of a token next to each other, K rows of 128 elements
+        and V rows padded to 160, handed to the library through its stride arguments."""
         B, Hkv, n_cap, d = Kc.shape
         self.B, self.Hq, self.Hkv, self.K, self.L = B, q.shape[1], Hkv, K, L
         self.n_cap = n_cap
         self.n = n_cap if n_ctx is None else n_ctx
         self.dtype = dtype
         self._pkw = dict(batch=B, n_q_heads=self.Hq, n_kv_heads=Hkv, K=K, L=L, n_cap=n_cap, dtype=dtype,
-                         min_hits=min_hits, n_sink=n_sink, n_local=n_local)
-        self.params = mp.make_params(n_ctx=self.n, **self._pkw)
+                         min_hits=min_hits, n_sink=n_sink, n_local=n_local, n_ctx_dev=n_ctx_dev)
         self.Kc, self.Vc, self.q, self.W = (to_dev(x, dtype) for x in (Kc, Vc, q, W))
+        if layout == "token_major":
+            vrow = 160
+            kt = self.Kc.permute(0, 2, 1, 3).contiguous()                       # [B, n_cap, Hkv, 128]
+            vt = torch.full((B, n_cap, Hkv, vrow), float("nan"), dtype=self.Vc.dtype, device="cuda")
+            vt[..., :d] = self.Vc.permute(0, 2, 1, 3)
+            self.Kc, self.Vc = kt, vt
+            self._pkw["k_strides"] = (n_cap * Hkv * d, d, Hkv * d)
+            self._pkw["v_strides"] = (n_cap * Hkv * vrow, vrow, Hkv * vrow)
+        else:
+            assert layout == "dense"
+        self.params = mp.make_params(n_ctx=self.n, **self._pkw)
         self.key_codes = mp.alloc_key_codes(self.params)
         self.q_codes = mp.alloc_query_codes(self.params)
         self.ws = mp.alloc_workspace(self.params)
@@ -76,6 +90,19 @@ class Session:
         torch.cuda.synchronize()
         raw = self.key_codes.cpu().numpy().view(np.uint32)
         words = raw[mp.key_code_gather_index(self.params)]
+        return mp.table_codes_from_words(mp.key_plane_words(words, self.K, self.L), self.K, self.L)
+
+    def key_table_codes_unit(self, b: int, g: int, rows=None) -> np.ndarray:
+        """[n_cap, L] (or [len(rows), L]) canonical codes of one (batch, KV head): reads only that
+        unit's part of the packed buffer."""
+        torch.cuda.synchronize()
+        one = mp.make_params(**{**self._pkw, "batch": 1, "n_kv_heads": 1, "n_q_heads": 1,
+                                "k_strides": None, "v_strides": None, "n_ctx_dev": None}, n_ctx=self.n)
+        idx = mp.key_code_gather_index(one)[0, 0]                       # [n_cap, NW] inside the unit
+        per_unit = (self.n_cap + 63) // 64 * 64 * self.NW
+        u = b * self.Hkv + g
+        raw = self.key_codes[u * per_unit:(u + 1) * per_unit].cpu().numpy().view(np.uint32)
+        words = raw[idx if rows is None else idx[np.asarray(rows)]]
         return mp.table_codes_from_words(mp.key_plane_words(words, self.K, self.L), self.K, self.L)
 
     def query_table_codes(self) -> np.ndarray:

@@ -44,10 +44,40 @@ def test_c5_one_sequence_group_of_eight(oracle):
     run_case(oracle, w, heads=heads, oracle_codes_too=False)
 
 
+def _finite_and_bounded(res, B, Hq):
+    # properties that hold for every head at any size: finite, inside the range of the values
+    out = res["out"]
+    assert out.shape == (B, Hq, 128) and np.isfinite(out).all() and np.abs(out).max() < 6.0
+
+
+def test_c4_whole_batch_at_full_context(oracle):
+    # batch 16 x 65536 keys, the launch shape the benchmark times for this workload (many rounds of
+    # workgroups in the scan + gather, separate lookup and gather launches through the tables, the
+    # 16-wavefront merge).  The GPU runs all 512 heads; the oracle checks every key code of seven
+    # (batch, KV head) units in the first, a middle and the last sequence, random keys of every
+    # unit, and counts, samples and outputs of seven heads there, peaked (h < 16) and flat.
+    w = wl.CONFIGS["C4"]
+    heads = [(0, 0), (0, 17), (7, 5), (7, 30), (15, 3), (15, 16), (15, 31)]
+    ref, res, worst = run_case(oracle, w, heads=heads, oracle_codes_too=False, random_rows=700)
+    _finite_and_bounded(res, w.batch, w.n_q_heads)
+    print(f"   C4 whole batch: {len(heads)} of {w.batch * w.n_q_heads} heads checked against the oracle, "
+          f"worst output error {worst:.2e}", flush=True)
+
+
+def test_c5_whole_batch_at_full_context(oracle):
+    # batch 8 x 131072 keys, 64 query heads (groups of eight), (10,170)
+    w = wl.CONFIGS["C5"]
+    heads = [(0, 7), (0, 40), (3, 21), (3, 63), (7, 0), (7, 33), (7, 58)]
+    ref, res, worst = run_case(oracle, w, heads=heads, oracle_codes_too=False, random_rows=1400)
+    _finite_and_bounded(res, w.batch, w.n_q_heads)
+    print(f"   C5 whole batch: {len(heads)} of {w.batch * w.n_q_heads} heads checked against the oracle, "
+          f"worst output error {worst:.2e}", flush=True)
+
+
 def test_c3_ragged_context_in_a_larger_cache(oracle):
-    # the benchmark shape with a context that ends inside a code block and inside a run of 16
-    # blocks (the last workgroup of a KV head scans 11 blocks and a part of the 12th), in a
-    # cache with spare capacity; the last KV head, all four of its query heads
+    # the benchmark shape with a context that ends inside a code block and inside a run of
+    # blocks (the last workgroup of a KV head scans fewer blocks than the others and a part of its
+    # last one), in a cache with spare capacity; the last KV head, all four of its query heads
     w = wl.scaled(wl.CONFIGS["C3"], n_ctx=98304 - 4 * 64 - 37)
     heads = [(0, h) for h in (28, 29, 30, 31)]
     ref, res, worst = run_case(oracle, w, heads=heads, n_cap=98304, oracle_codes_too=False)

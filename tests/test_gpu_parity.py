@@ -26,7 +26,8 @@ def oracle_mu(oracle, Kc, n):
 
 
 def run_case(oracle, w: wl.Workload, seed=0, alpha=0.8, use_mu=True, n_cap=None, check_codes=True,
-             oracle_codes_too=True, heads=None, centered_query=False, say="", indexed=()):
+             oracle_codes_too=True, heads=None, centered_query=False, say="", indexed=(), layout="dense",
+             check_key_mean=False, random_rows=0):
     print(f"[case] {say or w.name} B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} n={w.n_ctx} "
           f"K={w.K} L={w.L} tau={w.min_hits} dtype={w.dtype} seed={seed}", flush=True)
     data = wl.generate(w, seed, alpha)
@@ -45,8 +46,10 @@ def run_case(oracle, w: wl.Workload, seed=0, alpha=0.8, use_mu=True, n_cap=None,
                              mu=mu if use_mu else np.zeros((w.batch, w.n_kv_heads, 128), np.float32),
                              min_hits=w.min_hits, n_sink=w.n_sink, n_local=w.n_local, heads=heads)
     s = Session(K=w.K, L=w.L, dtype=w.dtype, Kc=Kc, Vc=Vc, q=q, W=W, n_ctx=n,
-                min_hits=w.min_hits, n_sink=w.n_sink, n_local=w.n_local)
+                min_hits=w.min_hits, n_sink=w.n_sink, n_local=w.n_local, layout=layout)
     s.set_mu(mu)
+    if check_key_mean:
+        assert np.abs(s.key_mean() - oracle_mu(oracle, Kc, n)).max() <= 1e-5 * np.abs(Kc).max()
     s.hash_keys(0, n)
     if w.dtype == "bf16" and n >= 1000:
         st = mp.hash_keys_stats(s.params, s.ws)
@@ -60,9 +63,21 @@ def run_case(oracle, w: wl.Workload, seed=0, alpha=0.8, use_mu=True, n_cap=None,
     pairs = heads if heads is not None else [(b, h) for b in range(w.batch) for h in range(w.n_q_heads)]
     if check_codes:
         np.testing.assert_array_equal(s.query_table_codes(), ref["q_codes"])
-        got = s.key_table_codes()[:, :, :n]
         for b, g in sorted({(b, h // w.group) for b, h in pairs}):
-            np.testing.assert_array_equal(got[b, g], ref["key_codes"][b, g])
+            np.testing.assert_array_equal(s.key_table_codes_unit(b, g)[:n], ref["key_codes"][b, g])
+        if random_rows > 0:
+            # everywhere else: random keys of every (batch, KV head) against the oracle's hashing
+            rng = np.random.default_rng(seed + 77)
+            checked = 0
+            for b in range(w.batch):
+                for g in range(w.n_kv_heads):
+                    rows = np.sort(rng.choice(n, size=min(random_rows, n), replace=False))
+                    want = oracle.hash_keys(Kc[b, g][rows], W, mu[b, g] if use_mu else None, w.K, w.L)
+                    np.testing.assert_array_equal(s.key_table_codes_unit(b, g, rows), want)
+                    checked += rows.size
+            print(f"   key codes: every key of {len({(b, h // w.group) for b, h in pairs})} (batch, KV head) units, and "
+                  f"{checked} random keys ({checked / (w.batch * w.n_kv_heads * n):.2%}) over all "
+                  f"{w.batch * w.n_kv_heads} units", flush=True)
     res = s.attend()
     worst = 0.0
     for b, h in pairs:
@@ -155,6 +170,35 @@ def test_full_batches_many_query_vectors(oracle):
 def test_generic_table_shapes(oracle, K, L, Hq, Hkv, dtype):
     w = wl.Workload("gen", 1, Hq, Hkv, 1500, K, L, dtype, (8,))
     run_case(oracle, w)
+
+
+def test_token_major_cache_with_padded_value_rows(oracle):
+    # K and V caches laid out [batch, token, KV head, row], V rows padded to 160 elements: every
+    # kernel that reads the caches (key mean, the three key-hashing paths, the gather) goes
+    # through the stride arguments, with different strides for K and V
+    w = wl.scaled(wl.CONFIGS["C2"], batch=2, n_ctx=1777, n_q_heads=8, n_kv_heads=2)
+    run_case(oracle, w, layout="token_major", check_key_mean=True, oracle_codes_too=False, indexed=(1024,))
+    w1 = wl.scaled(wl.CONFIGS["C1"], n_ctx=700)                     # float32 caches
+    run_case(oracle, w1, layout="token_major", check_key_mean=True, oracle_codes_too=False)
+    # a handful of keys appended behind the prefill: the few-vectors kernel reads strided rows too
+    data = wl.generate(w)
+    mu = oracle_mu(oracle, data["K"], 1700)
+    s = Session(K=w.K, L=w.L, dtype=w.dtype, Kc=data["K"], Vc=data["V"], q=data["q"], W=data["W"], layout="token_major")
+    s.set_mu(mu)
+    s.hash_keys(0, 1700)
+    s.hash_keys(1700, 40)                                            # 2 x 2 x 40 vectors: matrix cores
+    for i in range(1740, 1777):
+        s.hash_keys(i, 1)                                            # 4 vectors: few-vectors kernel
+    for b in range(2):
+        for g in range(2):
+            ref = oracle.hash_keys(data["K"][b, g], data["W"], mu[b, g], w.K, w.L)
+            np.testing.assert_array_equal(s.key_table_codes()[b, g], ref)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(24, 8), (6, 1), (5, 1), (7, 1)])
+def test_group_sizes_that_are_not_powers_of_two(oracle, Hq, Hkv):
+    w = wl.scaled(wl.CONFIGS["C2"], n_ctx=2100, n_q_heads=Hq, n_kv_heads=Hkv)
+    run_case(oracle, w, oracle_codes_too=False, indexed=(1024,))
 
 
 @pytest.mark.parametrize("tau", [0, 1, 3, 4, 5, 7])    # 5 and up: the term-by-term tail of the inclusion probability
