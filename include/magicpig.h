@@ -13,7 +13,8 @@
  *  - `params` is HOST memory, read during the call only.  Every other pointer is a
  *    DEVICE pointer owned by the caller (the library allocates and frees nothing; the
  *    only state it keeps is the per-thread event setting of
- *    magicpig_profile_stage_events and the last HIP error).  `workspace` is caller-owned device scratch, 16-byte
+ *    magicpig_profile_stage_events, the last HIP error, and the static scratch array of
+ *    magicpig_sampled_attention_noalloc).  `workspace` is caller-owned device scratch, 16-byte
  *    aligned; magicpig_workspace_bytes(params) bytes are enough for every call (each call
  *    checks only what it needs itself: query hashing and the hashing of a few appended keys
  *    need none and accept NULL); its contents need not be preserved or initialised between
@@ -49,7 +50,9 @@ enum {
   MAGICPIG_INVALID_ARG = -1,         /* null pointer, negative size, heads not divisible ... */
   MAGICPIG_UNSUPPORTED = -2,         /* head_dim != 128, K or L out of range, unknown dtype  */
   MAGICPIG_WORKSPACE_TOO_SMALL = -3,
-  MAGICPIG_LAUNCH_FAILED = -4        /* a HIP call failed; see magicpig_last_hip_error()      */
+  MAGICPIG_LAUNCH_FAILED = -4,       /* a HIP call failed; see magicpig_last_hip_error()      */
+  MAGICPIG_SCRATCH_TOO_SMALL = -5    /* magicpig_sampled_attention_noalloc: the step needs more
+                                        than MAGICPIG_STATIC_SCRATCH_BYTES of scratch          */
 };
 
 typedef struct magicpig_params {
@@ -71,7 +74,7 @@ typedef struct magicpig_params {
   const int64_t* n_ctx_dev;   /* NULL, or a DEVICE pointer to the context length of the running
                          decode loop (Algorithm 1 is run once per generated token: the context grows
                          by one key per step).  When set, magicpig_hash_decode_step and
-                         magicpig_sampled_attention[_tables] read the length from there when
+                         magicpig_sampled_attention[_tables|_noalloc] read the length from there when
                          their kernels run, so that one captured HIP graph serves every step of the
                          loop; n_ctx is then the largest value the word may hold (grids and
                          workspace are sized for it; larger values are clamped to it).  The other
@@ -169,6 +172,23 @@ MAGICPIG_API int magicpig_sampled_attention(const magicpig_params* params, const
                                const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
                                int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* For callers that cannot allocate device memory or carry a workspace around - code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc: the same decode step as
+ * magicpig_sampled_attention (same kernels, same result bit for bit, no debug outputs) with the
+ * scratch for its partial results in a static device array of MAGICPIG_STATIC_SCRATCH_BYTES that
+ * belongs to the library (each GPU the library runs on holds one until the process ends).  The
+ * call allocates and frees nothing.  A step that needs more scratch (4 * 132 bytes per query
+ * head and run of key blocks; batch 1 with 32 heads at 98304 keys needs 1.6 MB) is refused with
+ * MAGICPIG_SCRATCH_TOO_SMALL before anything is launched.  All calls on one GPU share that GPU's
+ * array: calls that overlap in time on one GPU (different streams or threads) race; order them.
+ * The first call on a GPU looks up the array's device address (once per GPU, with that GPU
+ * current) and should not itself be made under stream capture. */
+#define MAGICPIG_STATIC_SCRATCH_BYTES (8u << 20)
+MAGICPIG_API int magicpig_sampled_attention_noalloc(const magicpig_params* params, const void* q,
+                                                    const void* K_cache, const void* V_cache, const float* mu,
+                                                    const uint32_t* key_codes, const uint32_t* q_codes, float* out,
+                                                    void* hip_stream);
 
 /* ---- bucketed hash tables (the paper's retrieval structure: Algorithm 1 "Query(HT, q_code)";
  * App. E.2: L tables per key-value head, one key index per key and table) ----

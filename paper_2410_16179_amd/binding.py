@@ -44,6 +44,7 @@ EXPORTS = (
     "magicpig_status_string", "magicpig_last_hip_error", "magicpig_profile_stage_events",
     "magicpig_hash_keys_stats_offset", "magicpig_table_bytes", "magicpig_build_tables",
     "magicpig_sampled_attention_tables", "magicpig_hash_decode_step", "magicpig_table_build_workspace_bytes",
+    "magicpig_sampled_attention_noalloc",
 )
 
 _lib = None
@@ -75,6 +76,8 @@ def lib() -> ctypes.CDLL:
     L.magicpig_hash_decode_step.argtypes = [P, vp, vp, vp, vp, i64, i64, vp, vp, vp, sz, vp]
     L.magicpig_sampled_attention.restype = ctypes.c_int
     L.magicpig_sampled_attention.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
+    L.magicpig_sampled_attention_noalloc.restype = ctypes.c_int
+    L.magicpig_sampled_attention_noalloc.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp]
     L.magicpig_build_tables.restype = ctypes.c_int
     L.magicpig_build_tables.argtypes = [P, vp, vp, vp, sz, vp]
     L.magicpig_sampled_attention_tables.restype = ctypes.c_int
@@ -188,6 +191,12 @@ def magicpig_sampled_attention(params, q, K_cache, V_cache, mu, key_codes, q_cod
         ctypes.byref(params), _ptr(q), _ptr(K_cache), _ptr(V_cache), _ptr(mu), _ptr(key_codes),
         _ptr(q_codes), _ptr(out), _ptr(dbg_counts), _ptr(dbg_cand), _ptr(dbg_ncand), cap,
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def magicpig_sampled_attention_noalloc(params, q, K_cache, V_cache, mu, key_codes, q_codes, out) -> None:
+    _check(lib().magicpig_sampled_attention_noalloc(
+        ctypes.byref(params), _ptr(q), _ptr(K_cache), _ptr(V_cache), _ptr(mu), _ptr(key_codes),
+        _ptr(q_codes), _ptr(out), _stream()))
 
 
 def magicpig_table_bytes(params) -> int:

@@ -2,7 +2,14 @@
 // Validation touches no HIP call so that it can be exercised on a host without a GPU.
 #include "mp_common.h"
 
+#include <mutex>
 #include <string>
+
+// Scratch of magicpig_sampled_attention_noalloc: device memory that belongs to the library's
+// code object, one copy per GPU, there from the moment the library is loaded until the process
+// ends.  In host code this name only stands for the symbol; the device address of a GPU's copy
+// comes from hipGetSymbolAddress (static_scratch() below) and that is what kernels are given.
+static __device__ __align__(256) unsigned char scratch[MAGICPIG_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -16,6 +23,27 @@ int fail_hip(hipError_t e) {
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// Device address of the current GPU's copy of `scratch`, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(e);
+  if (dev < 0 || dev >= kMaxDevices) return MAGICPIG_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return fail_hip(e);
+    if (!ptr) return MAGICPIG_LAUNCH_FAILED;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return MAGICPIG_OK;
+}
 
 int check_params(const magicpig_params* p) {
   if (!p) return MAGICPIG_INVALID_ARG;
@@ -232,7 +260,8 @@ int run_attention_impl(const magicpig_params* p, const void* q, const void* K_ca
                        const void* V_cache, const float* mu, const uint32_t* key_codes,
                        const void* tables, int64_t n_indexed, const uint32_t* q_codes, float* out, uint16_t* dbg_counts,
                        int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
-                       void* workspace, size_t workspace_bytes, bool ballots_needed, void* hip_stream) {
+                       void* workspace, size_t workspace_bytes, bool ballots_needed, bool use_static_scratch,
+                       void* hip_stream) {
   int st = check_params(p);
   if (st != MAGICPIG_OK) return st;
   if ((st = check_strides(p->k_stride_b, p->k_stride_h, p->k_stride_n)) != MAGICPIG_OK) return st;
@@ -240,7 +269,7 @@ int run_attention_impl(const magicpig_params* p, const void* q, const void* K_ca
   // the gather forms row addresses from 32-bit row strides
   if (p->k_stride_n > INT32_MAX || p->v_stride_n > INT32_MAX) return MAGICPIG_UNSUPPORTED;
   const bool has_keys = p->n_ctx > 0 && p->batch > 0;
-  if (!out || !workspace || (!q && p->batch > 0)) return MAGICPIG_INVALID_ARG;
+  if (!out || (!workspace && !use_static_scratch) || (!q && p->batch > 0)) return MAGICPIG_INVALID_ARG;
   if (has_keys && (!K_cache || !V_cache || (!key_codes && !tables) || !q_codes)) return MAGICPIG_INVALID_ARG;
   if (tables) {
     if (!tables_supported(p)) return MAGICPIG_UNSUPPORTED;
@@ -254,7 +283,12 @@ int run_attention_impl(const magicpig_params* p, const void* q, const void* K_ca
       !aligned16(q_codes) || !aligned16(out) || !aligned16(workspace) || (mu && !aligned16(mu)))
     return MAGICPIG_INVALID_ARG;
   const AttnWs wl = ws_attention_layout(p);
-  if (workspace_bytes < (ballots_needed ? wl.total : wl.masks_off)) {
+  if (use_static_scratch) {
+    // everything above ran without a GPU call; the library's own scratch replaces the workspace
+    if (wl.masks_off > (size_t)MAGICPIG_STATIC_SCRATCH_BYTES) return MAGICPIG_SCRATCH_TOO_SMALL;
+    if (p->batch == 0) return MAGICPIG_OK;
+    if ((st = static_scratch(&workspace)) != MAGICPIG_OK) return st;
+  } else if (workspace_bytes < (ballots_needed ? wl.total : wl.masks_off)) {
     return MAGICPIG_WORKSPACE_TOO_SMALL;
   }
   mp::AttnArgs a{};
@@ -434,7 +468,15 @@ int magicpig_sampled_attention(const magicpig_params* p, const void* q, const vo
                                void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (p && p->n_ctx > 0 && p->batch > 0 && !key_codes) return MAGICPIG_INVALID_ARG;
   return run_attention_impl(p, q, K_cache, V_cache, mu, key_codes, nullptr, 0, q_codes, out, dbg_counts, dbg_cand,
-                            dbg_ncand, dbg_cand_cap, workspace, workspace_bytes, false, hip_stream);
+                            dbg_ncand, dbg_cand_cap, workspace, workspace_bytes, false, false, hip_stream);
+}
+
+int magicpig_sampled_attention_noalloc(const magicpig_params* p, const void* q, const void* K_cache,
+                                       const void* V_cache, const float* mu, const uint32_t* key_codes,
+                                       const uint32_t* q_codes, float* out, void* hip_stream) {
+  if (p && p->n_ctx > 0 && p->batch > 0 && !key_codes) return MAGICPIG_INVALID_ARG;
+  return run_attention_impl(p, q, K_cache, V_cache, mu, key_codes, nullptr, 0, q_codes, out, nullptr, nullptr,
+                            nullptr, 0, nullptr, 0, false, true, hip_stream);
 }
 
 size_t magicpig_table_bytes(const magicpig_params* p) {
@@ -475,7 +517,7 @@ int magicpig_sampled_attention_tables(const magicpig_params* p, const void* q, c
                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (p && p->n_ctx > 0 && p->batch > 0 && !tables) return MAGICPIG_INVALID_ARG;
   return run_attention_impl(p, q, K_cache, V_cache, mu, key_codes, tables, n_indexed, q_codes, out, dbg_counts, dbg_cand,
-                            dbg_ncand, dbg_cand_cap, workspace, workspace_bytes, true, hip_stream);
+                            dbg_ncand, dbg_cand_cap, workspace, workspace_bytes, true, false, hip_stream);
 }
 
 void magicpig_profile_stage_events(void* const* events) {
@@ -491,6 +533,8 @@ const char* magicpig_status_string(int status) {
     case MAGICPIG_UNSUPPORTED: return "unsupported configuration";
     case MAGICPIG_WORKSPACE_TOO_SMALL: return "workspace too small";
     case MAGICPIG_LAUNCH_FAILED: return "HIP launch failed";
+    case MAGICPIG_SCRATCH_TOO_SMALL:
+      return "the decode step needs more scratch than the library's static array holds: use the call that takes a workspace";
     default: return "unknown status";
   }
 }

@@ -58,7 +58,7 @@ def test_growing_context_one_graph_for_every_token(oracle, cfg, Hq, Hkv, n0):
     cand = torch.full((B, Hq, n_max), -1, dtype=torch.int32, device="cuda")
     ncand = torch.zeros((B, Hq), dtype=torch.int32, device="cuda")
     outs = {k: torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device="cuda")
-            for k in ("scan_dbg", "scan", "tables_dbg", "tables")}
+            for k in ("scan_dbg", "scan", "tables_dbg", "tables", "noalloc")}
     cand_t = torch.full_like(cand, -1)
     ncand_t = torch.zeros_like(ncand)
     counts_t = torch.zeros_like(counts)
@@ -73,6 +73,7 @@ def test_growing_context_one_graph_for_every_token(oracle, cfg, Hq, Hkv, n0):
                                       counts, cand, ncand, s.ws)
         mp.magicpig_sampled_attention(s.params, s.q, s.Kc, s.Vc, s.mu, s.key_codes, s.q_codes, outs["scan"],
                                       workspace=s.ws)
+        mp.magicpig_sampled_attention_noalloc(s.params, s.q, s.Kc, s.Vc, s.mu, s.key_codes, s.q_codes, outs["noalloc"])
         mp.magicpig_sampled_attention_tables(s.params, s.q, s.Kc, s.Vc, s.mu, s.tables, state["n_indexed"],
                                              s.key_codes, s.q_codes, outs["tables_dbg"], counts_t, cand_t, ncand_t, s.ws)
         mp.magicpig_sampled_attention_tables(s.params, s.q, s.Kc, s.Vc, s.mu, s.tables, state["n_indexed"],
@@ -126,6 +127,7 @@ def test_growing_context_one_graph_for_every_token(oracle, cfg, Hq, Hkv, n0):
         o = {k: v.cpu().numpy() for k, v in outs.items()}
         assert rel_err(o["scan_dbg"], ref["out"]) <= TOL
         np.testing.assert_array_equal(o["scan"], o["scan_dbg"])
+        np.testing.assert_array_equal(o["noalloc"], o["scan"])
         assert rel_err(o["tables_dbg"], ref["out"]) <= TOL and rel_err(o["tables"], ref["out"]) <= TOL
         # keys that were inside the local window at the prefill, or arrived later, are sampled now
         newly += sum(int((ref["S"][b][h] >= n0 - w.n_local).sum()) for b in range(B) for h in range(Hq))

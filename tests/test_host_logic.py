@@ -193,6 +193,18 @@ def test_argument_validation_without_a_gpu():
     assert attend_tables(params(K=13), 64) == -2                 # tables unsupported beyond K = 12
     assert mp.magicpig_workspace_bytes(params(K=0)) == 0
 
+    def attend_noalloc(pp, q=fake, out=fake, codes=fake):
+        return lib.magicpig_sampled_attention_noalloc(ctypes.byref(pp), q, fake, fake, None, codes, fake, out, None)
+
+    assert attend_noalloc(p, out=None) == -1
+    assert attend_noalloc(p, codes=None) == -1
+    assert attend_noalloc(params(K=17)) == -2
+    # batch 8 x 64 heads at 131072 keys needs 35 MB of partial results: beyond the static array
+    assert attend_noalloc(params(batch=8, n_q_heads=64, n_kv_heads=8, K=10, L=170, n_ctx=131072)) == -5
+    assert b"static" in lib.magicpig_status_string(-5)
+    assert lib.magicpig_status_string(-3) == b"workspace too small"
+    assert lib.magicpig_status_string(0) == b"ok"
+
 
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(mp, "_lib", None)
