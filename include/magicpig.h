@@ -155,6 +155,34 @@ MAGICPIG_API int magicpig_hash_decode_step(const magicpig_params* params, const 
                               uint32_t* key_codes, uint32_t* q_codes, void* workspace,
                               size_t workspace_bytes, void* hip_stream);
 
+/* ---- the hashing of a decode step from a prepared projector --------------------------------
+ * The decode step codes a handful of vectors against the whole projector and is bound by memory
+ * latency; reading W in a layout made for it (matrix-core fragments for bf16; Sec. 4.4 (3): the
+ * projections belong on the matrix units) takes the step from three dependent round trips to one.
+ * magicpig_prepare_projector writes that form once per model into `prepared`
+ * (magicpig_prepared_projector_bytes, 256-byte aligned, caller-owned; K, L, dtype of params are
+ * baked in; an opaque format).  magicpig_prepare_centering writes, once per sequence after
+ * magicpig_key_mean (the mean is frozen afterwards), the per-projection thresholds mu.W_j and
+ * |mu| of every (batch, KV head) into `centering` (magicpig_centering_bytes).
+ * magicpig_hash_query_prepared and magicpig_hash_decode_step_prepared then give the same codes,
+ * bit for bit, as magicpig_hash_query and magicpig_hash_decode_step (the sign of the exact sum:
+ * matrix-core results too close to zero are re-evaluated exactly inside the kernel).  They need
+ * no workspace.  In magicpig_hash_decode_step_prepared mu and centering go together (both NULL:
+ * no centering), q_codes may be NULL (keys only), n_keys may be 0 (queries only); at most 128 key
+ * vectors; params->n_ctx_dev is honoured as in magicpig_hash_decode_step. */
+MAGICPIG_API size_t magicpig_prepared_projector_bytes(const magicpig_params* params);
+MAGICPIG_API int magicpig_prepare_projector(const magicpig_params* params, const void* W, void* prepared,
+                                            void* hip_stream);
+MAGICPIG_API size_t magicpig_centering_bytes(const magicpig_params* params);
+MAGICPIG_API int magicpig_prepare_centering(const magicpig_params* params, const float* mu, const void* prepared,
+                                            void* centering, void* hip_stream);
+MAGICPIG_API int magicpig_hash_query_prepared(const magicpig_params* params, const void* q, const void* prepared,
+                                              uint32_t* q_codes, void* hip_stream);
+MAGICPIG_API int magicpig_hash_decode_step_prepared(const magicpig_params* params, const void* q,
+                                                    const void* K_cache, const float* mu, const void* centering,
+                                                    const void* prepared, int64_t first_key, int64_t n_keys,
+                                                    uint32_t* key_codes, uint32_t* q_codes, void* hip_stream);
+
 /* One decode step of sampled attention (Algorithm 1; Eq. "lsh sampling probability" and Eq.
  * "close form"): for every query head h with KV head g,
  *   count(h,i) = #{ t : code_q(h,t) == code_k(g,i,t) },
@@ -230,13 +258,18 @@ MAGICPIG_API int magicpig_sampled_attention_tables(const magicpig_params* params
                                       int32_t* dbg_cand, int32_t* dbg_ncand, int64_t dbg_cand_cap,
                                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Profiling aid (the only per-thread setting the library keeps): when `events` is non-NULL it
- * points to four hipEvent_t handles which later magicpig_sampled_attention[_tables] calls on
- * this host thread attach to their kernels: events[0] / events[1] receive the begin / end
- * timestamp of the retrieval kernel (collision scan or table lookup), events[2] the end of the
- * gather / estimator kernel, events[3] the end of the merge kernel.  magicpig_sampled_attention
- * scans and gathers in one kernel: events[0] / events[1] are its begin / end and events[2] is
- * recorded on the stream right behind it.  NULL switches it off. */
+/* Profiling aid, and the only setting the library keeps: a per-thread (thread_local) list of
+ * events, empty unless this function was called on the calling host thread; production callers
+ * never call it and pay one thread-local test per call.  When `events` is non-NULL it points to
+ * seven hipEvent_t handles which the later decode-step calls of this host thread attach to their
+ * kernels, so that the events carry the kernels' own begin / end timestamps (what a profiler
+ * reports) rather than dispatch times: magicpig_sampled_attention[_tables|_noalloc]: events[0] /
+ * events[1] begin / end of the retrieval kernel (collision scan or table lookup), events[2] end of
+ * the gather / estimator kernel, events[4] / events[3] begin / end of the merge kernel
+ * (magicpig_sampled_attention scans and gathers in one kernel: events[0] / events[1] are its
+ * begin / end and events[2] is recorded on the stream right behind it);
+ * magicpig_hash_query[_prepared] and magicpig_hash_decode_step[_prepared] (few-vectors kernels):
+ * events[5] / events[6] begin / end of the hashing kernel.  NULL switches it off. */
 MAGICPIG_API void magicpig_profile_stage_events(void* const* events);
 
 MAGICPIG_API const char* magicpig_status_string(int status);

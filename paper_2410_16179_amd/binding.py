@@ -14,7 +14,8 @@ import numpy as np
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libmagicpig.so")
+# (MAGICPIG_LIB names another build of the library, e.g. one compiled with other options)
+LIB_PATH = os.environ.get("MAGICPIG_LIB") or os.path.join(_PKG, "libmagicpig.so")
 
 MAGICPIG_BF16, MAGICPIG_FP32 = 0, 1
 
@@ -45,6 +46,8 @@ EXPORTS = (
     "magicpig_hash_keys_stats_offset", "magicpig_table_bytes", "magicpig_build_tables",
     "magicpig_sampled_attention_tables", "magicpig_hash_decode_step", "magicpig_table_build_workspace_bytes",
     "magicpig_sampled_attention_noalloc",
+    "magicpig_prepared_projector_bytes", "magicpig_prepare_projector", "magicpig_centering_bytes",
+    "magicpig_prepare_centering", "magicpig_hash_query_prepared", "magicpig_hash_decode_step_prepared",
 )
 
 _lib = None
@@ -62,7 +65,8 @@ def lib() -> ctypes.CDLL:
     vp, sz, i32, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int64
     for name in ("magicpig_code_words_per_key", "magicpig_code_words_per_query", "magicpig_key_code_bytes",
                  "magicpig_query_code_bytes", "magicpig_workspace_bytes",
-                 "magicpig_hash_keys_stats_offset", "magicpig_table_bytes", "magicpig_table_build_workspace_bytes"):
+                 "magicpig_hash_keys_stats_offset", "magicpig_table_bytes", "magicpig_table_build_workspace_bytes",
+                 "magicpig_prepared_projector_bytes", "magicpig_centering_bytes"):
         getattr(L, name).restype, getattr(L, name).argtypes = sz, [P]
     L.magicpig_key_code_index.restype = sz
     L.magicpig_key_code_index.argtypes = [P, i32, i32, i64, i32]
@@ -78,6 +82,14 @@ def lib() -> ctypes.CDLL:
     L.magicpig_sampled_attention.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
     L.magicpig_sampled_attention_noalloc.restype = ctypes.c_int
     L.magicpig_sampled_attention_noalloc.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.magicpig_prepare_projector.restype = ctypes.c_int
+    L.magicpig_prepare_projector.argtypes = [P, vp, vp, vp]
+    L.magicpig_prepare_centering.restype = ctypes.c_int
+    L.magicpig_prepare_centering.argtypes = [P, vp, vp, vp, vp]
+    L.magicpig_hash_query_prepared.restype = ctypes.c_int
+    L.magicpig_hash_query_prepared.argtypes = [P, vp, vp, vp, vp]
+    L.magicpig_hash_decode_step_prepared.restype = ctypes.c_int
+    L.magicpig_hash_decode_step_prepared.argtypes = [P, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
     L.magicpig_build_tables.restype = ctypes.c_int
     L.magicpig_build_tables.argtypes = [P, vp, vp, vp, sz, vp]
     L.magicpig_sampled_attention_tables.restype = ctypes.c_int
@@ -184,6 +196,33 @@ def magicpig_hash_decode_step(params, q, K_cache, mu, W, first_key, n_keys, key_
                                            _nbytes(workspace), _stream()))
 
 
+def magicpig_prepared_projector_bytes(params) -> int:
+    return lib().magicpig_prepared_projector_bytes(ctypes.byref(params))
+
+
+def magicpig_centering_bytes(params) -> int:
+    return lib().magicpig_centering_bytes(ctypes.byref(params))
+
+
+def magicpig_prepare_projector(params, W, prepared) -> None:
+    _check(lib().magicpig_prepare_projector(ctypes.byref(params), _ptr(W), _ptr(prepared), _stream()))
+
+
+def magicpig_prepare_centering(params, mu, prepared, centering) -> None:
+    _check(lib().magicpig_prepare_centering(ctypes.byref(params), _ptr(mu), _ptr(prepared), _ptr(centering), _stream()))
+
+
+def magicpig_hash_query_prepared(params, q, prepared, q_codes) -> None:
+    _check(lib().magicpig_hash_query_prepared(ctypes.byref(params), _ptr(q), _ptr(prepared), _ptr(q_codes), _stream()))
+
+
+def magicpig_hash_decode_step_prepared(params, q, K_cache, mu, centering, prepared, first_key, n_keys, key_codes,
+                                       q_codes) -> None:
+    _check(lib().magicpig_hash_decode_step_prepared(ctypes.byref(params), _ptr(q), _ptr(K_cache), _ptr(mu),
+                                                    _ptr(centering), _ptr(prepared), first_key, n_keys,
+                                                    _ptr(key_codes), _ptr(q_codes), _stream()))
+
+
 def magicpig_sampled_attention(params, q, K_cache, V_cache, mu, key_codes, q_codes, out,
                                dbg_counts=None, dbg_cand=None, dbg_ncand=None, workspace=None) -> None:
     cap = 0 if dbg_cand is None else dbg_cand.shape[-1]
@@ -219,11 +258,12 @@ def magicpig_sampled_attention_tables(params, q, K_cache, V_cache, mu, tables, n
 
 
 def magicpig_profile_stage_events(events) -> None:
-    """events: None, or four hipEvent_t handles (ints) recorded around the decode kernels."""
+    """events: None, or seven hipEvent_t handles (ints) attached to the decode kernels."""
     if events is None:
         lib().magicpig_profile_stage_events(None)
     else:
-        arr = (ctypes.c_void_p * 4)(*events)
+        assert len(events) == 7
+        arr = (ctypes.c_void_p * 7)(*events)
         lib().magicpig_profile_stage_events(arr)
 
 
@@ -249,6 +289,14 @@ def magicpig_table_build_workspace_bytes(params) -> int:
 
 def alloc_table_build_workspace(params, device="cuda") -> torch.Tensor:
     return torch.empty(max(magicpig_table_build_workspace_bytes(params), 256), dtype=torch.uint8, device=device)
+
+
+def alloc_prepared_projector(params, device="cuda") -> torch.Tensor:
+    return torch.empty(max(magicpig_prepared_projector_bytes(params), 256), dtype=torch.uint8, device=device)
+
+
+def alloc_centering(params, device="cuda") -> torch.Tensor:
+    return torch.empty(max(magicpig_centering_bytes(params), 256), dtype=torch.uint8, device=device)
 
 
 def alloc_workspace(params, device="cuda") -> torch.Tensor:

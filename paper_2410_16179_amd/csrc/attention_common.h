@@ -84,14 +84,21 @@ __device__ inline float inclusion_probability(float cosv, const AttnArgs& a) {
 // The context length of the step: the launch-time value, or - when the caller keeps it in device
 // memory (a decode loop replayed from a captured graph) - what that word holds now, clamped to
 // the value the launch was sized for.  The static set follows it.
-__device__ inline void resolve_context(AttnArgs& a) {
+// (The kernel arguments themselves are never copied or modified: they stay in the constant
+// argument segment, where the compiler reads them with scalar loads, dynamic indices included.)
+struct Ctx {
+  int64_t n, n_static;
+};
+__device__ inline Ctx resolve_context(const AttnArgs& a) {
+  Ctx c{a.n, a.n_static};
   if (a.n_dev) {
     int64_t n = *a.n_dev;
     n = n < 0 ? 0 : (n > a.n ? a.n : n);
-    a.n = n;
+    c.n = n;
     const int64_t st = (int64_t)a.n_sink + a.n_local;
-    a.n_static = st < n ? st : n;
+    c.n_static = st < n ? st : n;
   }
+  return c;
 }
 
 // Code words are read once per decode step: the non-temporal hint keeps them from displacing
@@ -120,22 +127,22 @@ __device__ inline void load_code_block(const uint32_t* blkp, int lane, uint32_t 
 
 // Lanes of block `blk` that hold a real key outside the static set (lane = key): what a query
 // head can sample there.
-__device__ inline uint64_t eligible_keys(const AttnArgs& a, int64_t blk, int lane) {
+__device__ inline uint64_t eligible_keys(const AttnArgs& a, const Ctx& c, int64_t blk, int lane) {
   const int64_t i = blk * kBlockKeys + lane;
-  return __ballot(i < a.n && !(i < a.n_sink || i >= a.n - a.n_local));
+  return __ballot(i < c.n && !(i < a.n_sink || i >= c.n - a.n_local));
 }
 
 // The keys of block `blk` that query head `head` samples, as a ballot (lane = key, cnt = its
 // number of colliding tables, eligible = eligible_keys of the block); with DBG also the optional
 // debug outputs (DBG = false keeps their pointers out of the scalar registers).
 template <bool DBG>
-__device__ inline uint64_t report_block(const AttnArgs& a, int64_t head, int64_t blk, int lane, uint32_t cnt,
+__device__ inline uint64_t report_block(const AttnArgs& a, const Ctx& c, int64_t head, int64_t blk, int lane, uint32_t cnt,
                                         uint64_t eligible) {
   const uint64_t m = a.tau <= 0 ? eligible : (__ballot((int)cnt >= a.tau) & eligible);
   if constexpr (DBG) {
     const int64_t i = blk * kBlockKeys + lane;
     const bool hit = (m >> lane) & 1;
-    if (a.dbg_counts && i < a.n) a.dbg_counts[head * a.dbg_stride + i] = (uint16_t)cnt;
+    if (a.dbg_counts && i < c.n) a.dbg_counts[head * a.dbg_stride + i] = (uint16_t)cnt;
     if (a.dbg_cand && hit) {
       const int pos = atomicAdd(&a.dbg_ncand[head], 1);
       if (pos < a.dbg_cand_cap) a.dbg_cand[head * a.dbg_cand_cap + pos] = (int32_t)i;
@@ -152,9 +159,9 @@ __device__ inline uint64_t report_block(const AttnArgs& a, int64_t head, int64_t
 // BPW: all code words of the blocks are requested before the first comparison, and each
 // scalar-loaded query word serves BPW keys per lane.
 template <int KT, int WDT, int LT, int BPW, bool DBG, class Emit>
-__device__ inline void scan_blocks(const AttnArgs& a, int unit, int64_t blk0, int lane, int h_begin, int h_end, Emit emit) {
+__device__ inline void scan_blocks(const AttnArgs& a, const Ctx& c, int unit, int64_t blk0, int lane, int h_begin, int h_end, Emit emit) {
   constexpr bool kGeneric = (KT == 0);
-  const int64_t nblk = key_blocks(a.n);
+  const int64_t nblk = key_blocks(c.n);
   const int G = a.Hq / a.Hkv;
   const int K = kGeneric ? a.K : KT;
   const int Wd = kGeneric ? a.Wd : WDT;
@@ -188,7 +195,7 @@ __device__ inline void scan_blocks(const AttnArgs& a, int unit, int64_t blk0, in
 
   uint64_t eligible[BPW];
 #pragma unroll
-  for (int j = 0; j < BPW; ++j) eligible[j] = blk0 + j < nblk ? eligible_keys(a, blk0 + j, lane) : 0ull;
+  for (int j = 0; j < BPW; ++j) eligible[j] = blk0 + j < nblk ? eligible_keys(a, c, blk0 + j, lane) : 0ull;
 #pragma unroll 1
   for (int h = h_begin; h < h_end; ++h) {
     const const_u32_ptr qh = qc + h * NQ;
@@ -230,7 +237,7 @@ __device__ inline void scan_blocks(const AttnArgs& a, int unit, int64_t blk0, in
 #pragma unroll
     for (int j = 0; j < BPW; ++j) {
       const int64_t blk = blk0 + j;
-      if (blk < nblk) emit(h, blk, report_block<DBG>(a, head0 + h, blk, lane, cnt[j], eligible[j]));
+      if (blk < nblk) emit(h, blk, report_block<DBG>(a, c, head0 + h, blk, lane, cnt[j], eligible[j]));
     }
   }
 }
@@ -241,8 +248,8 @@ __device__ inline int64_t static_key_of(int64_t n, int64_t n_static, int n_sink,
   const int64_t sink_keys = n_static < n ? n_sink : n_static;
   return j < sink_keys ? j : j + (n - n_local - n_sink);
 }
-__device__ inline int64_t static_key(const AttnArgs& a, int64_t j) {
-  return static_key_of(a.n, a.n_static, a.n_sink, a.n_local, j);
+__device__ inline int64_t static_key(const AttnArgs& a, const Ctx& c, int64_t j) {
+  return static_key_of(c.n, c.n_static, a.n_sink, a.n_local, j);
 }
 
 // The static set dealt over `slots` gather wavefronts of a head: slot s takes the static keys
@@ -251,8 +258,8 @@ __device__ inline int64_t static_key(const AttnArgs& a, int64_t j) {
 __device__ inline int static_share_of(int64_t n_static, int slot, int slots) {
   return slot < n_static ? (int)((n_static - slot + slots - 1) / slots) : 0;
 }
-__device__ inline int static_share(const AttnArgs& a, int slot, int slots) {
-  return static_share_of(a.n_static, slot, slots);
+__device__ inline int static_share(const Ctx& c, int slot, int slots) {
+  return static_share_of(c.n_static, slot, slots);
 }
 
 // The query row and the centering vector of a wavefront's head, eight elements per lane (the

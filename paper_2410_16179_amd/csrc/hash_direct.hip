@@ -11,6 +11,7 @@
 #include "exact_dot.h"
 #include "device_utils.h"
 #include <hip/hip_bf16.h>
+#include <hip/hip_ext.h>
 
 namespace mp {
 
@@ -450,7 +451,7 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
 }
 
 // `b` may be null (one set of vectors); both sets share K, L, the projector and the element type.
-hipError_t launch_hash_rows(const HashDirectArgs& a, const HashDirectArgs* b, hipStream_t s) {
+hipError_t launch_hash_rows(const HashDirectArgs& a, const HashDirectArgs* b, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
   const int64_t rows0 = a.total_rows > 0 ? a.total_rows : 0, rows1 = b && b->total_rows > 0 ? b->total_rows : 0;
   if (rows0 + rows1 <= 0) return hipSuccess;
   const int pairs0 = (int)(a.mu ? rows0 : (rows0 + 1) / 2);           // workgroups of the first set
@@ -458,12 +459,17 @@ hipError_t launch_hash_rows(const HashDirectArgs& a, const HashDirectArgs* b, hi
   const dim3 grid((unsigned)table_words(a.L), (unsigned)(pairs0 + pairs1)), block(512);
   const HashDirectArgs& a1 = b ? *b : a;
   const bool quad = (a.K * a.L) % 4 == 0;     // four columns per load (16-byte aligned base, checked by the caller)
+  // (with events the launch carries the kernel's own begin / end timestamps)
+  auto go = [&](auto kernel) {
+    if (start || stop) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, start, stop, 0, a, a1, pairs0);
+    else hipLaunchKernelGGL(kernel, grid, block, 0, s, a, a1, pairs0);
+  };
   if (a.is_fp32) {
-    if (quad) hipLaunchKernelGGL((hash_rows_kernel<true, true>), grid, block, 0, s, a, a1, pairs0);
-    else hipLaunchKernelGGL((hash_rows_kernel<true, false>), grid, block, 0, s, a, a1, pairs0);
+    if (quad) go(hash_rows_kernel<true, true>);
+    else go(hash_rows_kernel<true, false>);
   } else {
-    if (quad) hipLaunchKernelGGL((hash_rows_kernel<false, true>), grid, block, 0, s, a, a1, pairs0);
-    else hipLaunchKernelGGL((hash_rows_kernel<false, false>), grid, block, 0, s, a, a1, pairs0);
+    if (quad) go(hash_rows_kernel<false, true>);
+    else go(hash_rows_kernel<false, false>);
   }
   return hipGetLastError();
 }

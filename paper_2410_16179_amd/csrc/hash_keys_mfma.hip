@@ -13,8 +13,9 @@
 // Bit-exactness.  The hash bit is the sign of the exact sum  k.W_j - mu.W_j.  The MFMA
 // result acc ~ k.W_j - fl(mu.W_j) (the threshold enters as the initial accumulator) differs
 // from it by at most  bound_i = kGamma * (|k_i| + |mu|) * max_j |W_j|:  every bf16 product is
-// exact in float32, each of the 129 additions on any summation order rounds (or truncates)
-// with relative error <= 2^-23, and sum|terms| <= (|k_i| + |mu|) |W_j| by Cauchy-Schwarz.
+// exact in float32, the accumulation inside the matrix core loses at most kGamma of the sum of
+// magnitudes whatever its order and grouping (mp_common.h), and sum|terms| <= (|k_i| + |mu|) |W_j|
+// by Cauchy-Schwarz.
 // Elements with |acc| <= bound_i (a few in ten thousand) are listed in LDS and re-evaluated
 // at the end of the workgroup in float64 with the exact fallback of exact_dot.h, which
 // patches the bit.  Pairs beyond the LDS list go to a global list and recheck_kernel; if that
@@ -28,9 +29,6 @@ namespace mp {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-// 129 roundings of relative size 2^-23 in the worst (sequential, truncating) order:
-// (1 + 2^-23)^129 - 1 < 2^-15.98; 2^-15.9 leaves a few per cent on top.
-constexpr float kGamma = 1.6355e-5f;
 constexpr int kListCapLocal = 1536;       // flagged elements a workgroup can hold in LDS
 
 // Projection handled by row rho (0..31) of MFMA tile T: tile pair T/2 makes code words

@@ -207,7 +207,7 @@ __global__ __launch_bounds__(256) void ht_place_kernel(TableArgs a) {
 __global__ __launch_bounds__(1024) void table_lookup_kernel(AttnArgs a, TableArgs tb) {
   __shared__ uint32_t counters[kLookupRunKeys / 4];   // one byte per key of the run
   __shared__ uint32_t bstart[512], blen[512];
-  resolve_context(a);
+  const Ctx cx = resolve_context(a);
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int run = blockIdx.x;
@@ -271,12 +271,12 @@ __global__ __launch_bounds__(1024) void table_lookup_kernel(AttnArgs a, TableArg
   __syncthreads();
 
   // ballots of the blocks the tables cover: thread = 32 consecutive keys (half a block)
-  const int64_t nblk = key_blocks(a.n);
+  const int64_t nblk = key_blocks(cx.n);
   const int64_t kfirst = key0 + (int64_t)tid * 32;
   if (kfirst < key_blocks(tb.n) * kBlockKeys) {
     // positions of this thread's keys that are real and outside the static set
     const int64_t lo = (a.n_sink > kfirst ? a.n_sink : kfirst) - kfirst;
-    const int64_t hi_key = a.n - a.n_local < a.n ? a.n - a.n_local : a.n;
+    const int64_t hi_key = cx.n - a.n_local < cx.n ? cx.n - a.n_local : cx.n;
     const int64_t hi = (hi_key < kfirst + 32 ? hi_key : kfirst + 32) - kfirst;
     uint32_t elig = 0;
     if (hi > lo) elig = (hi - lo >= 32 ? 0xffffffffu : ((1u << (hi - lo)) - 1u)) << lo;
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(1024) void table_lookup_kernel(AttnArgs a, TableArg
       for (int j = 0; j < 32; ++j) {
         const int64_t i = kfirst + j;
         const int cnt = (counters[tid * 8 + (j >> 2)] >> (8 * (j & 3))) & 0xff;
-        if (a.dbg_counts && i < a.n) a.dbg_counts[bh * a.dbg_stride + i] = (uint16_t)cnt;
+        if (a.dbg_counts && i < cx.n) a.dbg_counts[bh * a.dbg_stride + i] = (uint16_t)cnt;
         if (a.dbg_cand && ((bits >> j) & 1u)) {
           const int pos = atomicAdd(&a.dbg_ncand[bh], 1);
           if (pos < a.dbg_cand_cap) a.dbg_cand[bh * a.dbg_cand_cap + pos] = (int32_t)i;
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(1024) void table_lookup_bitmap_kernel(AttnArgs a, T
   extern __shared__ uint32_t bitmap[];                  // seen[nw], twice[nw]
   __shared__ uint32_t bstart[512], blen[512];
   __shared__ uint32_t qs[256];
-  resolve_context(a);
+  const Ctx cx = resolve_context(a);
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int64_t bh = blockIdx.x;
@@ -374,10 +374,10 @@ __global__ __launch_bounds__(1024) void table_lookup_bitmap_kernel(AttnArgs a, T
   }
   __syncthreads();
   // ballots of the indexed range, 32 keys per word, static keys and keys beyond n masked out
-  const int64_t nblk = key_blocks(a.n);
+  const int64_t nblk = key_blocks(cx.n);
   const uint32_t* hit = a.tau >= 2 ? twice : seen;
   uint32_t* mout = reinterpret_cast<uint32_t*>(a.masks) + bh * nblk * 2;
-  const int64_t hi_key = a.n - a.n_local < a.n ? a.n - a.n_local : a.n;
+  const int64_t hi_key = cx.n - a.n_local < cx.n ? cx.n - a.n_local : cx.n;
   for (int i = tid; i < nw; i += 1024) {
     const int64_t kfirst = (int64_t)i * 32;
     const int64_t lo = (a.n_sink > kfirst ? a.n_sink : kfirst) - kfirst;
@@ -434,7 +434,7 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
   __shared__ uint32_t seen[kSliceWords], twice[kSliceWords];
   __shared__ uint32_t qs[256];
   __shared__ uint16_t lists[16][kLgWaveBlocks * kBlockKeys + kBlockKeys];
-  resolve_context(a);
+  const Ctx cx = resolve_context(a);
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int slice = blockIdx.x;
@@ -452,9 +452,9 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
   // wavefront gathers what its block samples with its own batch ----
   uint64_t app_mask = 0;
   const int64_t app_blk = a.blk_begin + (int64_t)slice * 16 + wave;
-  if (slice < a.lg_app_runs && app_blk < key_blocks(a.n)) {
+  if (slice < a.lg_app_runs && app_blk < key_blocks(cx.n)) {
     const int hg = (int)(bh % a.Hq) % G;
-    scan_blocks<KT, WDT, LT, 1, true>(a, unit, app_blk, lane, hg, hg + 1, [&](int, int64_t, uint64_t m) { app_mask = m; });
+    scan_blocks<KT, WDT, LT, 1, true>(a, cx, unit, app_blk, lane, hg, hg + 1, [&](int, int64_t, uint64_t m) { app_mask = m; });
   }
   if (tid < a.NQ) qs[tid] = qword;
   __syncthreads();
@@ -576,7 +576,7 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
   __syncthreads();
   // ---- gather: wavefront v takes blocks v*kLgWaveBlocks .. of the slice ----
   const uint32_t* hit = a.tau >= 2 ? twice : seen;
-  const int64_t hi_key = a.n - a.n_local < tb.n ? a.n - a.n_local : tb.n;   // indexed, not in the local window
+  const int64_t hi_key = cx.n - a.n_local < tb.n ? cx.n - a.n_local : tb.n;   // indexed, not in the local window
   const int64_t wave_key0 = (int64_t)key_lo + (int64_t)wave * (kLgWaveBlocks * kBlockKeys);
   uint16_t* list = lists[wave];
   HeadVectors<FP32> hv;
@@ -615,10 +615,10 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
   __builtin_amdgcn_wave_barrier();
   // static keys slot, slot + slots, ... ride along behind the sampled ones
   const int slots = a.lg_nslices * 16, slot = slice * 16 + wave;
-  const int nst = static_share(a, slot, slots);
+  const int nst = static_share(cx, slot, slots);
   gather_estimate_wave<FP32, (FP32 ? 4 : 8)>(a, unit, bh, n_sampled + nst, n_sampled, hv,
                                             [&](int cc) {
-                                              if (cc >= n_sampled) return static_key(a, slot + (int64_t)(cc - n_sampled) * slots);
+                                              if (cc >= n_sampled) return static_key(a, cx, slot + (int64_t)(cc - n_sampled) * slots);
                                               return (cc < in_slice ? wave_key0 : app_blk * kBlockKeys) + (int64_t)list[cc];
                                             },
                                             a.partial + (bh * a.nranges + slot) * kPartialStride);

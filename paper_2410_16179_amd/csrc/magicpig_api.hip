@@ -14,7 +14,8 @@ static __device__ __align__(256) unsigned char scratch[MAGICPIG_STATIC_SCRATCH_B
 namespace {
 
 thread_local std::string g_last_hip_error;
-thread_local hipEvent_t g_stage_events[4];
+constexpr int kStageEvents = 7;
+thread_local hipEvent_t g_stage_events[kStageEvents];
 thread_local bool g_have_stage_events = false;
 
 int fail_hip(hipError_t e) {
@@ -435,7 +436,9 @@ int magicpig_hash_query(const magicpig_params* p, const void* q, const void* W, 
   const int st = check_hash_query_args(p, q, W, q_codes, workspace, workspace_bytes);
   if (st != MAGICPIG_OK) return st;
   const mp::HashDirectArgs a = query_rows(p, q, W, q_codes);
-  const hipError_t e = mp::launch_hash_rows(a, nullptr, reinterpret_cast<hipStream_t>(hip_stream));
+  const hipError_t e = mp::launch_hash_rows(a, nullptr, reinterpret_cast<hipStream_t>(hip_stream),
+                                            g_have_stage_events ? g_stage_events[5] : nullptr,
+                                            g_have_stage_events ? g_stage_events[6] : nullptr);
   return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
 }
 
@@ -457,8 +460,107 @@ int magicpig_hash_decode_step(const magicpig_params* p, const void* q, const voi
   const mp::HashDirectArgs aq = query_rows(p, q, W, q_codes);
   mp::HashDirectArgs ak = key_rows(p, K_cache, mu, W, first_key, n_keys, key_codes);
   ak.n_dev = p->n_ctx_dev;
-  const hipError_t e = mp::launch_hash_rows(aq, &ak, reinterpret_cast<hipStream_t>(hip_stream));
+  const hipError_t e = mp::launch_hash_rows(aq, &ak, reinterpret_cast<hipStream_t>(hip_stream),
+                                            g_have_stage_events ? g_stage_events[5] : nullptr,
+                                            g_have_stage_events ? g_stage_events[6] : nullptr);
   return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
+}
+
+size_t magicpig_prepared_projector_bytes(const magicpig_params* p) {
+  if (check_params(p) != MAGICPIG_OK) return 0;
+  return mp::prepared_layout(p->K, p->L, p->dtype == MAGICPIG_FP32).total;
+}
+
+int magicpig_prepare_projector(const magicpig_params* p, const void* W, void* prepared, void* hip_stream) {
+  const int st = check_params(p);
+  if (st != MAGICPIG_OK) return st;
+  if (!W || !prepared || !aligned16(W) || !aligned16(prepared)) return MAGICPIG_INVALID_ARG;
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  const hipError_t e = p->dtype == MAGICPIG_FP32 ? mp::launch_prepare_projector_fp32(W, prepared, p->K, p->L, stream)
+                                                 : mp::launch_prepare_projector(W, prepared, p->K, p->L, stream);
+  return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
+}
+
+size_t magicpig_centering_bytes(const magicpig_params* p) {
+  if (check_params(p) != MAGICPIG_OK) return 0;
+  if (p->dtype == MAGICPIG_FP32) return 256;               // float32 keys are coded from mu itself
+  const size_t n = mp::centering_layout(p->K, p->L, (size_t)p->batch * p->n_kv_heads).total;
+  return n < 256 ? 256 : n;
+}
+
+int magicpig_prepare_centering(const magicpig_params* p, const float* mu, const void* prepared, void* centering,
+                               void* hip_stream) {
+  const int st = check_params(p);
+  if (st != MAGICPIG_OK) return st;
+  if (!mu || !prepared || !centering || !aligned16(mu) || !aligned16(prepared) || !aligned16(centering))
+    return MAGICPIG_INVALID_ARG;
+  if (p->dtype == MAGICPIG_FP32) return MAGICPIG_OK;       // nothing to prepare
+  const hipError_t e = mp::launch_prepare_centering(mu, prepared, centering, p->K, p->L, p->batch * p->n_kv_heads,
+                                                    reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
+}
+
+int magicpig_hash_decode_step_prepared(const magicpig_params* p, const void* q, const void* K_cache, const float* mu,
+                                       const void* centering, const void* prepared, int64_t first_key, int64_t n_keys,
+                                       uint32_t* key_codes, uint32_t* q_codes, void* hip_stream) {
+  int st = check_params(p);
+  if (st != MAGICPIG_OK) return st;
+  if (!prepared || !aligned16(prepared)) return MAGICPIG_INVALID_ARG;
+  const bool fp32 = p->dtype == MAGICPIG_FP32;
+  const void* W = reinterpret_cast<const char*>(prepared) + mp::prepared_layout(p->K, p->L, fp32).wt_off;   // (float32: the copy)
+  const bool with_q = q_codes != nullptr, with_k = n_keys > 0;
+  if (!with_q && !with_k) return MAGICPIG_OK;
+  if (with_q && (st = check_hash_query_args(p, q, W, q_codes, nullptr, 0)) != MAGICPIG_OK) return st;
+  const bool live = p->n_ctx_dev != nullptr;
+  if (live) first_key = 0;
+  if (with_k) {
+    if ((st = check_hash_keys_args(p, K_cache, mu, W, first_key, n_keys, key_codes, nullptr, 0)) != MAGICPIG_OK &&
+        st != MAGICPIG_WORKSPACE_TOO_SMALL)
+      return st;
+    // the few-vectors kernel only: a prefill goes through magicpig_hash_keys
+    if ((int64_t)p->batch * p->n_kv_heads * n_keys > kFewRows) return MAGICPIG_UNSUPPORTED;
+    if (mu && !fp32 && (!centering || !aligned16(centering))) return MAGICPIG_INVALID_ARG;
+  }
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  if (fp32) {
+    mp::HashDirectArgs aq = query_rows(p, q, W, q_codes);
+    mp::HashDirectArgs ak = key_rows(p, K_cache, mu, W, first_key, n_keys, key_codes);
+    ak.n_dev = p->n_ctx_dev;
+    if (!with_k) ak.total_rows = 0;
+    if (!with_q) aq.total_rows = 0;
+    const hipError_t e = with_q ? mp::launch_hash_rows(aq, with_k ? &ak : nullptr, stream) : mp::launch_hash_rows(ak, nullptr, stream);
+    return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
+  }
+  const mp::PreparedLayout pl = mp::prepared_layout(p->K, p->L, false);
+  const char* pb = reinterpret_cast<const char*>(prepared);
+  mp::HashFewArgs a{};
+  a.header = reinterpret_cast<const uint32_t*>(pb);
+  a.frag = pb + pl.frag_off; a.wt = pb + pl.wt_off;
+  if (with_k && mu) {
+    const mp::CenteringLayout cl = mp::centering_layout(p->K, p->L, (size_t)p->batch * p->n_kv_heads);
+    const char* cb = reinterpret_cast<const char*>(centering);
+    a.thr = reinterpret_cast<const float*>(cb + cl.thr_off);
+    a.munorm = reinterpret_cast<const float*>(cb + cl.munorm_off);
+    a.mu = mu;
+  }
+  a.q = q; a.qcodes = q_codes; a.n_q = with_q ? p->batch * p->n_q_heads : 0;
+  a.Kc = K_cache; a.kcodes = key_codes;
+  a.n_krows = with_k ? (int)((int64_t)p->batch * p->n_kv_heads * n_keys) : 0;
+  a.n_keys = n_keys > 0 ? n_keys : 1; a.first_key = first_key; a.n_cap = p->n_cap;
+  a.blocks_cap = mp::key_blocks(p->n_cap); a.n_dev = p->n_ctx_dev;
+  a.n_kv_heads = p->n_kv_heads;
+  a.stride_b = p->k_stride_b; a.stride_h = p->k_stride_h; a.stride_n = p->k_stride_n;
+  a.K = p->K; a.L = p->L; a.Wd = pl.Wd; a.P = pl.P;
+  a.NQ = mp::plane_words(p->K, p->L); a.NW = mp::code_words(p->K, p->L);
+  const hipError_t e = mp::launch_hash_few(a, stream, g_have_stage_events ? g_stage_events[5] : nullptr,
+                                           g_have_stage_events ? g_stage_events[6] : nullptr);
+  return e == hipSuccess ? MAGICPIG_OK : fail_hip(e);
+}
+
+int magicpig_hash_query_prepared(const magicpig_params* p, const void* q, const void* prepared, uint32_t* q_codes,
+                                 void* hip_stream) {
+  if (!q_codes) return MAGICPIG_INVALID_ARG;
+  return magicpig_hash_decode_step_prepared(p, q, nullptr, nullptr, nullptr, prepared, 0, 0, nullptr, q_codes, hip_stream);
 }
 
 int magicpig_sampled_attention(const magicpig_params* p, const void* q, const void* K_cache,
@@ -523,7 +625,7 @@ int magicpig_sampled_attention_tables(const magicpig_params* p, const void* q, c
 void magicpig_profile_stage_events(void* const* events) {
   g_have_stage_events = events != nullptr;
   if (events)
-    for (int i = 0; i < 4; ++i) g_stage_events[i] = reinterpret_cast<hipEvent_t>(events[i]);
+    for (int i = 0; i < kStageEvents; ++i) g_stage_events[i] = reinterpret_cast<hipEvent_t>(events[i]);
 }
 
 const char* magicpig_status_string(int status) {

@@ -106,6 +106,66 @@ struct HashMfmaArgs {
   unsigned long long* list; uint64_t list_cap;
 };
 
+// Matrix-core projections (bf16 products are exact in float32; float32 accumulation): whatever the
+// order and grouping of the 128 products and the initial value inside the matrix core, with each
+// alignment or rounding step losing at most 2^-23 of the running magnitude, the result is within
+// kGamma * sum|terms| of the exact sum.  A fused 16-term block with truncating alignment gives
+// (16 + 2) * 8 * 2^-23 = 2^-15.8; 2^-15 leaves a factor of 1.8.
+constexpr float kGamma = 3.0517578125e-5f;
+
+// The projector in the form the few-vectors matrix-core hashing reads (magicpig_prepare_projector):
+// [256-byte header | fragments | transposed copy].  Header words: magic, K, L, float bits of the
+// largest column norm.  Fragments: for table group w (32 tables) and plane pair p (planes 2p, 2p+1)
+// two MFMA A tiles of 32 rows x 128, tile row rho of tile tau being plane 2p + (rho/4)%2 of table
+// 32w + 31 - (16 tau + 4 (rho/8) + rho%4), in the lane order of v_mfma_f32_32x32x16_bf16: k-step s,
+// lane (rho, half) holds elements 16 s + 8 half .. + 7.  Transposed copy: [K*L][128] bf16.
+// float32 projectors: header and a plain copy.
+constexpr uint32_t kPreparedMagic = 0x4d505731u;
+struct PreparedLayout { size_t frag_off, wt_off, total; int P, Wd; };
+__host__ __device__ inline PreparedLayout prepared_layout(int K, int L, bool fp32) {
+  PreparedLayout l{};
+  l.P = (K + 1) / 2;
+  l.Wd = table_words(L);
+  l.frag_off = 256;
+  if (fp32) {
+    l.wt_off = 256;
+    l.total = 256 + (((size_t)K * L * kHeadDim * 4 + 255) & ~(size_t)255);
+    return l;
+  }
+  const size_t frag = (size_t)l.Wd * l.P * 2 * 8 * 64 * 16;
+  l.wt_off = l.frag_off + ((frag + 255) & ~(size_t)255);
+  l.total = l.wt_off + (((size_t)K * L * kHeadDim * 2 + 255) & ~(size_t)255);
+  return l;
+}
+// Centering prepared for the few-vectors hashing (magicpig_prepare_centering): per (batch, KV head)
+// the initial accumulators -fl(mu.W_j) in the order of the fragments above
+// ([unit][w][p][tau][lane half][16]), then |mu| per unit.
+struct CenteringLayout { size_t thr_off, munorm_off, total; };
+__host__ __device__ inline CenteringLayout centering_layout(int K, int L, size_t units) {
+  CenteringLayout c{};
+  const size_t thr = units * (size_t)table_words(L) * ((K + 1) / 2) * 64 * sizeof(float);
+  c.thr_off = 0;
+  c.munorm_off = (thr + 255) & ~(size_t)255;
+  c.total = c.munorm_off + ((units * sizeof(float) + 255) & ~(size_t)255);
+  return c;
+}
+
+// Launch description of the few-vectors matrix-core hashing (bf16): the queries of a decode step
+// and / or the newest keys of every (batch, KV head).
+struct HashFewArgs {
+  const uint32_t* header; const void* frag; const void* wt;    // prepared projector
+  const float* thr; const float* munorm;                        // prepared centering, or null (no centering)
+  const void* q; uint32_t* qcodes; int n_q;                     // query vectors [n_q][128], codes [n_q][NQ]
+  const void* Kc; const float* mu; uint32_t* kcodes;            // key vectors: key first_key + r % n_keys of unit r / n_keys
+  int n_krows;                                                  // units * n_keys (0: no keys)
+  int64_t n_keys, first_key, n_cap, blocks_cap;
+  const int64_t* n_dev;                                         // see HashDirectArgs::n_dev
+  int n_kv_heads;
+  int64_t stride_b, stride_h, stride_n;
+  int K, L, Wd, P, NQ, NW;
+  int q_groups;                                                 // grid rows that take queries (64 each); the rest take keys (32 each)
+};
+
 struct MeanArgs {
   const void* Kc; float* mu; double* partial;
   int is_fp32; int n_kv_heads; int units; int64_t n; int nchunk; int64_t rows_per_chunk;
@@ -177,9 +237,13 @@ constexpr int kFusedIters = 8;             // its gather batch: rows per quarter
 
 // host-side launchers (defined next to their kernels)
 hipError_t launch_hash_direct(const HashDirectArgs& a, hipStream_t s);
-hipError_t launch_hash_rows(const HashDirectArgs& a, const HashDirectArgs* b, hipStream_t s);
+hipError_t launch_hash_rows(const HashDirectArgs& a, const HashDirectArgs* b, hipStream_t s, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_hash_keys_mfma(const HashMfmaArgs& a, hipStream_t s);
 hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s);
+hipError_t launch_prepare_projector(const void* W, void* prepared, int K, int L, hipStream_t s);
+hipError_t launch_prepare_projector_fp32(const void* W, void* prepared, int K, int L, hipStream_t s);
+hipError_t launch_prepare_centering(const float* mu, const void* prepared, void* centering, int K, int L, int units, hipStream_t s);
+hipError_t launch_hash_few(const HashFewArgs& a, hipStream_t s, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, hipStream_t s, hipEvent_t const* stage_events);
 hipError_t launch_build_tables(const TableArgs& t, hipStream_t s);
 hipError_t launch_table_lookup(const AttnArgs& a, const TableArgs& t, hipStream_t s, hipEvent_t start, hipEvent_t stop);

@@ -41,17 +41,17 @@ namespace mp {
 
 template <int KT, int WDT, int LT, int BPW>
 __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
-  resolve_context(a);
+  const Ctx c = resolve_context(a);
   // readfirstlane tells the compiler that the wavefront index (and everything derived from
   // it: KV head, query-code address) is uniform, so those loads become scalar
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int64_t nblk = key_blocks(a.n);
+  const int64_t nblk = key_blocks(c.n);
   const int unit = blockIdx.y;
   const int64_t blk0 = a.blk_begin + ((int64_t)blockIdx.x * 4 + wave) * BPW;
   if (blk0 >= nblk) return;
   const int G = a.Hq / a.Hkv;
   const int64_t head0 = (int64_t)(unit / a.Hkv) * a.Hq + (int64_t)(unit % a.Hkv) * G;
-  scan_blocks<KT, WDT, LT, BPW, true>(a, unit, blk0, lane, 0, G, [&](int h, int64_t blk, uint64_t m) {
+  scan_blocks<KT, WDT, LT, BPW, true>(a, c, unit, blk0, lane, 0, G, [&](int h, int64_t blk, uint64_t m) {
     if (lane == 0) a.masks[(head0 + h) * nblk + blk] = m;
   });
 }
@@ -64,13 +64,13 @@ template <bool FP32> constexpr int kGatherIters = FP32 ? 4 : 8;
 template <bool FP32>
 __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
   __shared__ uint16_t lists[8][kRangeBlocks * kBlockKeys];
-  resolve_context(a);
+  const Ctx c = resolve_context(a);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int unit = blockIdx.y, range = blockIdx.x;
   const int b = unit / a.Hkv, g = unit % a.Hkv;
   const int G = a.Hq / a.Hkv;
   const int64_t bh = (int64_t)b * a.Hq + (int64_t)g * G + wave;
-  const int64_t nblk = key_blocks(a.n);
+  const int64_t nblk = key_blocks(c.n);
   const int64_t blk0 = (int64_t)range * kRangeBlocks;
   uint16_t* list = lists[wave];
   HeadVectors<FP32> hv;
@@ -85,15 +85,15 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
     // ---- expand the scan's ballots into an index list (wavefront prefix sum) ----
     uint64_t m = 0;
     if (lane < kRangeBlocks && blk0 + lane < nblk) m = a.masks[bh * nblk + blk0 + lane];
-    const int c = __popcll(m);
-    int incl = c;
+    const int pc = __popcll(m);
+    int incl = pc;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
       const int v = __shfl_up(incl, o);
       if (lane >= o) incl += v;
     }
     total = __shfl(incl, 63);
-    int pos = incl - c;
+    int pos = incl - pc;
     while (m) {
       const int bit = __ffsll((unsigned long long)m) - 1;
       list[pos++] = (uint16_t)(lane * kBlockKeys + bit);
@@ -103,16 +103,16 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
     __builtin_amdgcn_wave_barrier();
   } else {
     static_first = (int64_t)(range - a.nscan) * kStaticPerRange;
-    const int64_t left = a.n_static - static_first;
+    const int64_t left = c.n_static - static_first;
     total = (int)(left < kStaticPerRange ? left : kStaticPerRange);
   }
   float* pp = a.partial + (bh * a.nranges + range) * kPartialStride;
   if (!is_static) {
     gather_estimate_wave<FP32, kGatherIters<FP32>>(a, unit, bh, total, total, hv,
-                               [&](int c) { return blk0 * kBlockKeys + (int64_t)list[c]; }, pp);
+                               [&](int cc) { return blk0 * kBlockKeys + (int64_t)list[cc]; }, pp);
   } else {
     gather_estimate_wave<FP32, kGatherIters<FP32>>(a, unit, bh, total, 0, hv,
-                               [&](int c) { return static_key(a, static_first + c); }, pp);
+                               [&](int cc) { return static_key(a, c, static_first + cc); }, pp);
   }
 }
 
@@ -140,14 +140,13 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
   constexpr int kIt = FP32 ? (kFusedIters + 1) / 2 : kFusedIters;   // the same registers per batch
   __shared__ uint64_t smask[8][kFusedBlocks];
   __shared__ uint16_t lists[4][kFusedBlocks * kBlockKeys];
-  resolve_context(a);
-  const int64_t n_now = a.n, n_static_now = a.n_static;    // (the gather re-reads its arguments: these two it keeps)
+  const Ctx c = resolve_context(a);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int unit = blockIdx.y, run = blockIdx.x;
   const int nruns = gridDim.x;                             // = f_nranges
   const int G = a.Hq / a.Hkv;
   const int64_t head0 = (int64_t)(unit / a.Hkv) * a.Hq + (int64_t)(unit % a.Hkv) * G;
-  const int64_t nblk = key_blocks(a.n);
+  const int64_t nblk = key_blocks(c.n);
   const int wave_blocks = a.f_wave_blocks;                 // 1 .. kFusedWaveBlocks key blocks per wavefront
   const int run_blocks = 4 * wave_blocks;
   const int64_t blk0 = (int64_t)run * run_blocks;
@@ -155,7 +154,7 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
   for (int j = 0; j < wave_blocks; ++j) {
     const int bi = wave * wave_blocks + j;
     if (blk0 + bi < nblk) {
-      scan_blocks<KT, WDT, LT, 1, DBG>(a, unit, blk0 + bi, lane, 0, G, [&](int h, int64_t, uint64_t m) {
+      scan_blocks<KT, WDT, LT, 1, DBG>(a, c, unit, blk0 + bi, lane, 0, G, [&](int h, int64_t, uint64_t m) {
         if (lane == 0) smask[h][bi] = m;
       });
     } else if (lane < G) {
@@ -177,8 +176,8 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
     request_head_vectors<FP32>(ga, unit, head0 + h, hv);
     // ---- the ballots of head h as an index list (wavefront prefix sum) ----
     uint64_t m = lane < run_blocks ? smask[h][lane] : 0;
-    const int c = __popcll(m);
-    int incl = c;
+    const int pc = __popcll(m);
+    int incl = pc;
     static_assert(kFusedBlocks <= 32, "the ballots of a run are summed over 32 lanes");
 #pragma unroll
     for (int o = 1; o < 32; o <<= 1) {
@@ -186,7 +185,7 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
       if (lane >= o) incl += v;
     }
     const int total = __shfl(incl, 31);
-    int pos = incl - c;
+    int pos = incl - pc;
     while (m) {
       const int bit = __ffsll((unsigned long long)m) - 1;
       list[pos++] = (uint16_t)(lane * kBlockKeys + bit);
@@ -195,12 +194,11 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
     __builtin_amdgcn_wave_barrier();
     // static keys run, run + nruns, ... ride along behind the sampled ones
-    const int nst = static_share_of(n_static_now, run, nruns);
+    const int nst = static_share(c, run, nruns);
     gather_estimate_wave<FP32, kIt>(ga, unit, head0 + h, total + nst, total, hv,
                                     [&](int cc) {
                                       return cc < total ? blk0 * kBlockKeys + (int64_t)list[cc]
-                                                        : static_key_of(n_now, n_static_now, ga.n_sink, ga.n_local,
-                                                                        run + (int64_t)(cc - total) * nruns);
+                                                        : static_key(ga, c, run + (int64_t)(cc - total) * nruns);
                                     },
                                     ga.partial + ((head0 + h) * ga.f_nranges + run) * kPartialStride);
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
@@ -302,11 +300,11 @@ static hipError_t launch_scan(const AttnArgs& a, hipStream_t s, hipEvent_t start
 }
 
 // a wavefront merges 16 partials per pass: enough wavefronts for one pass where that fits
-static hipError_t launch_merge(const AttnArgs& a, int64_t heads, hipStream_t s, hipEvent_t stop) {
+static hipError_t launch_merge(const AttnArgs& a, int64_t heads, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
   const dim3 grid((unsigned)heads);
-  if (a.nranges <= 64) launch_timed(merge_partials_kernel<4>, grid, dim3(256), s, nullptr, stop, a);
-  else if (a.nranges <= 128) launch_timed(merge_partials_kernel<8>, grid, dim3(512), s, nullptr, stop, a);
-  else launch_timed(merge_partials_kernel<16>, grid, dim3(1024), s, nullptr, stop, a);
+  if (a.nranges <= 64) launch_timed(merge_partials_kernel<4>, grid, dim3(256), s, start, stop, a);
+  else if (a.nranges <= 128) launch_timed(merge_partials_kernel<8>, grid, dim3(512), s, start, stop, a);
+  else launch_timed(merge_partials_kernel<16>, grid, dim3(1024), s, start, stop, a);
   return hipGetLastError();
 }
 
@@ -363,7 +361,7 @@ hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, 
       if ((e = launch_lookup_gather(b, *tables, nslices, app_runs, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr)) != hipSuccess)
         return e;
       if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
-      return launch_merge(b, heads, s, ev ? ev[3] : nullptr);
+      return launch_merge(b, heads, s, ev ? ev[4] : nullptr, ev ? ev[3] : nullptr);
     }
     if (lookup) {
       e = launch_table_lookup(a, *tables, s, ev ? ev[0] : nullptr, ev && !scan ? ev[1] : nullptr);
@@ -379,14 +377,14 @@ hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, 
     if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
     AttnArgs b = a;
     b.nranges = a.f_nranges;
-    if ((e = launch_merge(b, heads, s, ev ? ev[3] : nullptr)) != hipSuccess) return e;
+    if ((e = launch_merge(b, heads, s, ev ? ev[4] : nullptr, ev ? ev[3] : nullptr)) != hipSuccess) return e;
     return hipGetLastError();
   }
   const dim3 grid((unsigned)a.nranges, (unsigned)(a.B * a.Hkv)), block(64 * (a.Hq / a.Hkv));
   if (a.is_fp32) launch_timed(gather_estimate_kernel<true>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);
   else launch_timed(gather_estimate_kernel<false>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  return launch_merge(a, heads, s, ev ? ev[3] : nullptr);
+  return launch_merge(a, heads, s, ev ? ev[4] : nullptr, ev ? ev[3] : nullptr);
 }
 
 }  // namespace mp

@@ -85,6 +85,23 @@ class Session:
     def hash_query(self):
         mp.magicpig_hash_query(self.params, self.q, self.W, self.q_codes, self.ws)
 
+    def prepare(self):
+        """Prepared projector (once per model) and, if there is a centering vector, its thresholds."""
+        self.prepared = mp.alloc_prepared_projector(self.params)
+        mp.magicpig_prepare_projector(self.params, self.W, self.prepared)
+        self.centering = None
+        if self.mu is not None:
+            self.centering = mp.alloc_centering(self.params)
+            mp.magicpig_prepare_centering(self.params, self.mu, self.prepared, self.centering)
+
+    def hash_query_prepared(self, q_codes=None):
+        mp.magicpig_hash_query_prepared(self.params, self.q, self.prepared, self.q_codes if q_codes is None else q_codes)
+
+    def hash_keys_prepared(self, first, count, key_codes=None, q_codes=None):
+        """Keys [first, first + count) (and the queries, if q_codes is given) through the prepared form."""
+        mp.magicpig_hash_decode_step_prepared(self.params, self.q, self.Kc, self.mu, self.centering, self.prepared,
+                                              first, count, self.key_codes if key_codes is None else key_codes, q_codes)
+
     def key_table_codes(self) -> np.ndarray:
         """[B, Hkv, n_cap, L] canonical codes read back from the packed buffer."""
         torch.cuda.synchronize()

@@ -78,6 +78,26 @@ def run_case(oracle, w: wl.Workload, seed=0, alpha=0.8, use_mu=True, n_cap=None,
             print(f"   key codes: every key of {len({(b, h // w.group) for b, h in pairs})} (batch, KV head) units, and "
                   f"{checked} random keys ({checked / (w.batch * w.n_kv_heads * n):.2%}) over all "
                   f"{w.batch * w.n_kv_heads} units", flush=True)
+    if check_codes and n > 0:
+        # the same hashing from the prepared projector (matrix cores for bf16): queries, and the
+        # newest keys coded into buffers of their own by both forms, which must then be equal
+        s.prepare()
+        qc = torch.full_like(s.q_codes, -1)
+        s.hash_query_prepared(qc)
+        nq = w.batch * w.n_q_heads * s.NQ
+        assert torch.equal(qc[:nq], s.q_codes[:nq])
+        cnt = min(n, max(1, 128 // (w.batch * w.n_kv_heads)))
+        if w.batch * w.n_kv_heads <= 128:
+            a, b_ = torch.full_like(s.key_codes, 0x5a5a5a5a), torch.full_like(s.key_codes, 0x5a5a5a5a)
+            mp.magicpig_hash_keys(s.params, s.Kc, s.mu, s.W, n - cnt, cnt, a, s.ws)
+            qc.fill_(-1)
+            s.hash_keys_prepared(n - cnt, cnt, key_codes=b_, q_codes=qc)
+            assert torch.equal(a, b_), "keys coded from the prepared projector differ"
+            assert torch.equal(qc[:nq], s.q_codes[:nq])
+            # ... and those are the codes the prefill wrote for these keys
+            full = s.key_codes.clone()
+            s.hash_keys_prepared(n - cnt, cnt)
+            assert torch.equal(full, s.key_codes)
     res = s.attend()
     worst = 0.0
     for b, h in pairs:
@@ -367,18 +387,84 @@ def test_hash_bits_follow_the_exact_sum(oracle, nrows):
             s.hash_keys()
             ref = oracle.hash_keys(rows[0, 0], W, None if mu is None else mu[0, 0], K, L)
             np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
+            # the prepared form on the same rows, taken as keys (64 at a time) and as queries
+            s.prepare()
+            s.key_codes.fill_(0x5a5a5a5a)
+            for first in range(0, nrows, 64):
+                s.hash_keys_prepared(first, 64)
+            np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
+            sq = Session(K=K, L=L, dtype=dtype, Kc=rows, Vc=rows, q=rows[:, 0, :5][:, :, :], W=W, n_ctx=nrows)
+            sq.prepare()
+            sq.hash_query_prepared()
+            np.testing.assert_array_equal(sq.query_table_codes()[0], oracle.hash_query(rows[0, 0, :5], W, K, L))
     # centering that matters only in exact arithmetic
     mu = np.zeros((1, 1, 128), np.float32)
     mu[0, 0, 0] = big
     mu[0, 0, 1] = tiny
     rows2 = np.zeros((1, 1, nrows, 128), np.float32)
     rows2[0, 0, :, 0] = big
-    s = Session(K=K, L=L, dtype="fp32", Kc=rows2, Vc=rows2, q=rows2[:, :, 0], W=W, n_ctx=nrows)
-    s.set_mu(mu)
-    s.hash_keys()
     ref = oracle.hash_keys(rows2[0, 0], W, mu[0, 0], K, L)
-    np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
     assert ref[0, 0] == 0          # x - mu = -2^-40 < 0 in both planes of table 0
+    for dtype in ("fp32", "bf16"):
+        s = Session(K=K, L=L, dtype=dtype, Kc=rows2, Vc=rows2, q=rows2[:, :, 0], W=W, n_ctx=nrows)
+        s.set_mu(mu)
+        s.hash_keys()
+        np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
+        s.prepare()
+        s.key_codes.fill_(0x5a5a5a5a)
+        for first in range(0, nrows, 64):
+            s.hash_keys_prepared(first, 64)
+        np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
+
+
+@pytest.mark.parametrize("K,L", [(10, 150), (9, 120), (7, 65), (16, 40), (1, 1), (5, 512), (11, 300), (6, 64)])
+def test_hashing_from_the_prepared_projector(oracle, K, L):
+    # the few-vectors matrix-core kernel: 70 query vectors (a full group of 64 and a ragged one),
+    # keys appended in batches that end inside and across 32-key groups, with and without centering;
+    # an all-zero vector (every projection exactly zero: each one is re-evaluated exactly) and vectors
+    # that are multiples of projector columns (the magnitude bound is tight there)
+    w = wl.Workload("prep", 2, 35, 5, 300, K, L, "bf16", (8,))
+    data = wl.generate(w)
+    Kc, q, W = data["K"].copy(), data["q"].copy(), data["W"]
+    q[0, 3] = 0.0
+    q[1, 7] = wl.store(3.0 * W[:, (K * L) // 2], "bf16")
+    q[1, 8] = wl.store(-0.5 * W[:, 0], "bf16")
+    Kc[0, 1, 290] = 0.0
+    Kc[1, 4, 299] = wl.store(2.0 * W[:, K * L - 1], "bf16")
+    mu = oracle_mu(oracle, Kc, 250)
+    mu[1, 4] = Kc[1, 4, 299]                                       # a key equal to its centering vector: projections exactly 0
+    for use_mu in (True, False):
+        s = Session(K=K, L=L, dtype="bf16", Kc=Kc, Vc=data["V"], q=q, W=W)
+        s.set_mu(mu if use_mu else None)
+        s.prepare()
+        s.key_codes.fill_(0x5a5a5a5a)
+        s.q_codes.fill_(0x5a5a5a5a)
+        first = 0
+        for cnt in (12, 1, 7, 3, 12, 12, 5, 12, 12, 12, 12, 12):      # 10 units x 12 keys = 120 vectors at most
+            s.hash_keys_prepared(first, cnt, q_codes=s.q_codes if first == 0 else None)
+            first += cnt
+        while first < 300:
+            cnt = min(12, 300 - first)
+            s.hash_keys_prepared(first, cnt)
+            first += cnt
+        for b in range(2):
+            np.testing.assert_array_equal(s.query_table_codes()[b], oracle.hash_query(q[b], W, K, L))
+            for g in range(5):
+                ref = oracle.hash_keys(Kc[b, g], W, mu[b, g] if use_mu else None, K, L)
+                np.testing.assert_array_equal(s.key_table_codes_unit(b, g), ref)
+    # float32: the prepared form is a copy of the projector behind the same calls
+    w32 = wl.Workload("prep32", 1, 6, 2, 200, min(K, 8), min(L, 75), "fp32", (8,))
+    d32 = wl.generate(w32)
+    mu32 = oracle_mu(oracle, d32["K"], 200)
+    s = Session(K=w32.K, L=w32.L, dtype="fp32", Kc=d32["K"], Vc=d32["V"], q=d32["q"], W=d32["W"])
+    s.set_mu(mu32)
+    s.prepare()
+    for first in range(0, 200, 50):
+        s.hash_keys_prepared(first, 50, q_codes=s.q_codes)
+    np.testing.assert_array_equal(s.query_table_codes()[0], oracle.hash_query(d32["q"][0], d32["W"], w32.K, w32.L))
+    for g in range(2):
+        np.testing.assert_array_equal(s.key_table_codes_unit(0, g),
+                                      oracle.hash_keys(d32["K"][0, g], d32["W"], mu32[0, g], w32.K, w32.L))
 
 
 def test_overflow_of_the_recheck_list_falls_back_to_the_float64_kernel(oracle):
