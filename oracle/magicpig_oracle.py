@@ -13,8 +13,11 @@ probability"); expected budget for orthogonal vectors (App. E, Eq. "budget"); ex
 softmax attention recovered when every key is sampled with u = 1 (Sec. 2.1 definition,
 checked against torch's scaled_dot_product_attention); Monte-Carlo inclusion frequency
 and unbiasedness of numerator/denominator over random projectors (Eq. "importance
-sampling unnormalized"); brute-force collision counting; invariants.  No function here
-is "parity unpinned".
+sampling unnormalized"); brute-force collision counting; invariants; the two comparison
+estimators of Sec. 2.1 and Sec. 3.2 (TopK attention, oracle sampling estimation) against
+the values the paper prints for its zoo example (App. "TopK vs. Sampling"), the closed
+forms of its two theorems on oracle sampling, and brute force.  No function here is
+"parity unpinned".
 
 Notation follows the paper: K sign bits per table, L tables, p_i per-hyperplane
 agreement probability, u_i inclusion probability, S the sample, T the static
@@ -42,6 +45,67 @@ def exact_attention(q, K, V):
     z = K @ q / math.sqrt(q.shape[0])
     w = np.exp(z - z.max())
     return (w / w.sum()) @ V
+
+
+def attention_weights(q, K):
+    """w = softmax(q K^T / sqrt(d)): the attention (score) distribution of Sec. 2.1."""
+    q = np.asarray(q, np.float64)
+    K = np.asarray(K, np.float64)
+    z = K @ q / math.sqrt(q.shape[0])
+    e = np.exp(z - z.max())
+    return e / e.sum()
+
+
+# --------------------------------------------------------------------------------------
+# Sec. 2.1 / 3.1: TopK attention (the upper bound of search-based sparse attention)
+# --------------------------------------------------------------------------------------
+def topk_attention(q, K, V, m):
+    """The m keys with the largest attention scores, renormalised among themselves:
+    sum_{i in top} w_i v_i / sum_{i in top} w_i  (Sec. 2.1: Pi selects r_1..r_m, D = 1/sum w_{r_i}).
+    Ties are broken towards the lower index.  Returns (out, sorted indices of the selection)."""
+    V = np.asarray(V, np.float64)
+    n = V.shape[0]
+    m = int(min(max(m, 0), n))
+    if m == 0:
+        return np.zeros(V.shape[1], np.float64), np.zeros(0, np.int64)
+    w = attention_weights(q, K)
+    order = np.lexsort((np.arange(n), -w))          # descending score, then ascending index
+    top = np.sort(order[:m])
+    return (w[top] / w[top].sum()) @ V[top], top
+
+
+# --------------------------------------------------------------------------------------
+# Sec. 3.2: oracle sampling estimation
+# --------------------------------------------------------------------------------------
+def oracle_sampling_estimate(q, K, V, uniforms):
+    """Definition "Oracle Sampling Estimation": B = len(uniforms) indices are drawn independently
+    from the attention distribution w and the output is estimated as (1/B) sum_j v_{i_j}.  The
+    randomness is passed in: `uniforms` are B numbers in [0, 1), turned into indices by
+    inverting the cumulative distribution of w.  Returns (estimate, drawn indices); the
+    computation cost of the estimate is the number of unique indices (Sec. 3.2)."""
+    V = np.asarray(V, np.float64)
+    u = np.asarray(uniforms, np.float64).reshape(-1)
+    if u.size == 0:
+        return np.zeros(V.shape[1], np.float64), np.zeros(0, np.int64)
+    w = attention_weights(q, K)
+    cdf = np.cumsum(w)
+    idx = np.minimum(np.searchsorted(cdf, u * cdf[-1], side="right"), w.size - 1)
+    return V[idx].mean(axis=0), idx.astype(np.int64)
+
+
+def oracle_sampling_trace_of_covariance(q, K, V, budget):
+    """Theorem "Oracle sampling estimation is unbiased ...", proof: Tr Cov = (E|v|^2 - |o|^2) / B."""
+    V = np.asarray(V, np.float64)
+    w = attention_weights(q, K)
+    o = w @ V
+    return float((w @ (V * V).sum(axis=1) - o @ o) / budget)
+
+
+def relative_error(estimate, exact):
+    """|estimate - exact| / |exact| (Euclidean norms): the estimation error of the paper's figures."""
+    estimate = np.asarray(estimate, np.float64)
+    exact = np.asarray(exact, np.float64)
+    return float(np.linalg.norm(estimate - exact) / max(np.linalg.norm(exact), 1e-300))
 
 
 # --------------------------------------------------------------------------------------

@@ -87,6 +87,101 @@ def test_decode_step_centers_with_the_mean_of_all_keys(oracle):
     np.testing.assert_array_equal(r["key_codes"][0, 0], oracle.hash_keys(Kc[0, 0], W, hand, 3, 4))
 
 
+# ---- TopK attention (Sec. 2.1) and oracle sampling estimation (Sec. 3.2) -----------------
+def zoo():
+    """The zoo example of App. "TopK vs. Sampling" as an attention problem: 73 keys whose attention
+    scores are the probabilities of the kinds (head dimension 1, logit = log probability), values =
+    daily food."""
+    w = np.array([0.1, 0.1, 0.1] + [0.01] * 70)
+    food = np.array([50.0, 20.0, 10.0] + [1.0] * 70)
+    return np.ones(1), np.log(w)[:, None], food[:, None], w
+
+
+def test_zoo_example_true_average_and_topk(oracle):
+    g = golden()
+    q, K, V, w = zoo()
+    np.testing.assert_allclose(oracle.attention_weights(q, K), w, rtol=1e-12)
+    assert abs(oracle.exact_attention(q, K, V)[0] - g["zoo_true_average"]) < 1e-12
+    t10, sel10 = oracle.topk_attention(q, K, V, 10)
+    t20, sel20 = oracle.topk_attention(q, K, V, 20)
+    assert abs(t10[0] - 807.0 / 37.0) < 1e-12 and round(t10[0]) == g["zoo_topk_10"]
+    assert abs(t20[0] - 817.0 / 47.0) < 1e-12 and round(t20[0]) == g["zoo_topk_20"]
+    assert sel10.tolist() == list(range(10)) and sel20.size == 20      # ties: the lower indices
+    # the whole context is exact attention; nothing selected is the zero vector
+    assert abs(oracle.topk_attention(q, K, V, 73)[0][0] - g["zoo_true_average"]) < 1e-12
+    assert oracle.topk_attention(q, K, V, 0)[0][0] == 0.0
+
+
+def test_zoo_example_sampling_is_unbiased_with_the_printed_spread(oracle):
+    g = golden()
+    q, K, V, w = zoo()
+    rng = np.random.default_rng(2024)
+    trials = 200_000
+    for budget, key in ((10, "zoo_sampling_std_10"), (20, "zoo_sampling_std_20")):
+        est = np.array([oracle.oracle_sampling_estimate(q, K, V, rng.random(budget))[0][0] for _ in range(trials)])
+        std = est.std()
+        assert abs(est.mean() - g["zoo_true_average"]) < 4 * std / math.sqrt(trials)     # unbiased
+        assert abs(std - g[key]) < 0.07                        # 4.7 / 3.4 as printed (two digits) + Monte-Carlo noise
+        assert round(math.sqrt(oracle.oracle_sampling_trace_of_covariance(q, K, V, budget)), 1) == g[key]
+        # Theorem on oracle sampling, proof: Tr Cov = (E|v|^2 - |o|^2) / B = 225.01 / B here
+        assert abs(oracle.oracle_sampling_trace_of_covariance(q, K, V, budget) - 225.01 / budget) < 1e-9
+        assert abs(std ** 2 - 225.01 / budget) < 0.02 * 225.01 / budget
+
+
+def test_topk_against_a_sorted_brute_force(oracle):
+    rng = np.random.default_rng(5)
+    n, d = 57, 6
+    q, K, V = f32(rng, d), f32(rng, n, d), f32(rng, n, d)
+    z = [(sum(float(a) * float(b) for a, b in zip(K[i], q)) / math.sqrt(d), i) for i in range(n)]
+    for m in (1, 2, 13, 56, 57, 80):
+        best = sorted(z, key=lambda t: (-t[0], t[1]))[:min(m, n)]
+        mx = max(t[0] for t in best)
+        den = sum(math.exp(t[0] - mx) for t in best)
+        want = [sum(math.exp(t[0] - mx) / den * float(V[t[1], j]) for t in best) for j in range(d)]
+        got, sel = oracle.topk_attention(q, K, V, m)
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-14)
+        assert sel.tolist() == sorted(t[1] for t in best)
+    np.testing.assert_allclose(oracle.topk_attention(q, K, V, n)[0], oracle.exact_attention(q, K, V), rtol=1e-12)
+    # the selection keeps the largest scores: every kept score >= every dropped one
+    w = oracle.attention_weights(q, K)
+    _, sel = oracle.topk_attention(q, K, V, 20)
+    assert w[sel].min() >= np.delete(w, sel).max()
+
+
+def test_oracle_sampling_draws_from_the_attention_distribution(oracle):
+    # three keys with scores 0.2, 0.3, 0.5: the uniforms select by the cumulative distribution
+    q = np.ones(1)
+    K = np.log(np.array([0.2, 0.3, 0.5]))[:, None]
+    V = np.array([[1.0, 0.0], [0.0, 1.0], [4.0, 4.0]])
+    est, idx = oracle.oracle_sampling_estimate(q, K, V, [0.0, 0.19, 0.21, 0.49, 0.51, 0.999])
+    assert idx.tolist() == [0, 0, 1, 1, 2, 2]
+    np.testing.assert_allclose(est, [(1 + 1 + 4 + 4) / 6.0, (1 + 1 + 4 + 4) / 6.0])
+    assert oracle.oracle_sampling_estimate(q, K, V, [])[0].tolist() == [0.0, 0.0]
+    # unbiased in every coordinate; Tr Cov = (E|v|^2 - |o|^2) / B, falling as 1 / B; the number of
+    # unique draws has mean n - sum (1 - w_i)^B <= 1 + B (1 - max w)  (both theorems of Sec. 3.2)
+    rng = np.random.default_rng(9)
+    n, d = 40, 3
+    qq, KK, VV = f32(rng, d), 2.0 * f32(rng, n, d), f32(rng, n, d)
+    w = oracle.attention_weights(qq, KK)
+    o = oracle.exact_attention(qq, KK, VV)
+    trials, last = 40_000, None
+    for budget in (4, 16, 64):
+        runs = [oracle.oracle_sampling_estimate(qq, KK, VV, rng.random(budget)) for _ in range(trials)]
+        est = np.array([r[0] for r in runs])
+        tr = est.var(axis=0).sum()
+        want = oracle.oracle_sampling_trace_of_covariance(qq, KK, VV, budget)
+        assert abs(want - (float(w @ (VV.astype(np.float64) ** 2).sum(axis=1)) - float(o @ o)) / budget) < 1e-12
+        assert np.all(np.abs(est.mean(axis=0) - o) < 4 * est.std(axis=0) / math.sqrt(trials))
+        assert abs(tr - want) < 0.05 * want
+        assert last is None or tr < last
+        last = tr
+        uniq = np.mean([np.unique(r[1]).size for r in runs])
+        expect = n - ((1.0 - w) ** budget).sum()
+        assert abs(uniq - expect) < 0.02 * expect
+        assert expect <= 1 + budget * (1 - w.max()) + 1e-12
+    assert oracle.relative_error([3.0, 4.0], [0.0, 0.0 + 5.0]) == pytest.approx(math.sqrt(9 + 1) / 5)
+
+
 # ---- P1: per-hyperplane agreement probability, Sec. 2.2 -------------------------------
 @pytest.mark.parametrize("deg", [30, 60, 90, 120, 150])
 def test_agreement_probability_matches_empirical_hyperplanes(oracle, deg):
