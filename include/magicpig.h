@@ -223,7 +223,7 @@ MAGICPIG_API int magicpig_sampled_attention_noalloc(const magicpig_params* param
  * For every (batch, KV head) and table the keys [0, n_ctx) are grouped by their K-bit code:
  * a decode step then reads only the L buckets selected by the query's codes instead of every
  * key's code, and obtains the same counts on the keys it touches and the same sample S.
- * Supported for K <= 12, L <= 255, batch * n_q_heads <= 65535 (otherwise the size is 0 and the
+ * Supported for K <= 12, batch * n_q_heads <= 65535 (otherwise the size is 0 and the
  * calls return MAGICPIG_UNSUPPORTED).  The buffer holds, each part 256-byte aligned: a header of
  * 256 bytes (word 0: number of 16384-key windows when the buckets are ordered by window, else
  * 0); [batch*n_kv_heads][L][2^K + 1] uint32 bucket offsets; [batch*n_kv_heads][L][n_cap] uint32

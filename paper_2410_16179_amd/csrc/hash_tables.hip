@@ -28,8 +28,9 @@
 
 namespace mp {
 
-constexpr int kLookupRunBlocks = 512;                 // 64-key blocks per lookup workgroup
-constexpr int kLookupRunKeys = kLookupRunBlocks * kBlockKeys;
+// 64-key blocks per workgroup of the counting lookup: 32 KB of hit counters, one byte per key up
+// to 255 tables, two bytes beyond (a key can collide in every table)
+template <int BITS> constexpr int kLookupRunBlocks = 512 * 8 / BITS;
 
 // tables handled by one build workgroup: as many histograms of 2^K counters as fit 64 KB of LDS
 __host__ __device__ inline int ht_tables_per_pass(int K) {
@@ -204,8 +205,12 @@ __global__ __launch_bounds__(256) void ht_place_kernel(TableArgs a) {
   }
 }
 
+template <int BITS>
 __global__ __launch_bounds__(1024) void table_lookup_kernel(AttnArgs a, TableArgs tb) {
-  __shared__ uint32_t counters[kLookupRunKeys / 4];   // one byte per key of the run
+  constexpr int kLookupRunKeys = kLookupRunBlocks<BITS> * kBlockKeys;
+  constexpr int kPerWord = 32 / BITS;                  // counters per 32-bit LDS word
+  constexpr uint32_t kCntMask = (1u << BITS) - 1u;
+  __shared__ uint32_t counters[kLookupRunKeys / kPerWord];
   __shared__ uint32_t bstart[512], blen[512];
   const Ctx cx = resolve_context(a);
   const int tid = threadIdx.x;
@@ -220,7 +225,7 @@ __global__ __launch_bounds__(1024) void table_lookup_kernel(AttnArgs a, TableArg
   const int64_t key0 = (int64_t)run * kLookupRunKeys;
 
   __shared__ uint32_t qs[256];
-  for (int i = tid; i < kLookupRunKeys / 4; i += 1024) counters[i] = 0u;
+  for (int i = tid; i < kLookupRunKeys / kPerWord; i += 1024) counters[i] = 0u;
   if (tid < a.NQ) qs[tid] = a.qcodes[bh * a.NQ + tid];   // one round trip for the query's words
   __syncthreads();
   // bucket of every table: the query's K-bit code of table t selects offsets[t][code..code+1]
@@ -254,7 +259,7 @@ __global__ __launch_bounds__(1024) void table_lookup_kernel(AttnArgs a, TableArg
   // a key outside this run (or the "no entry" marker) wraps to a value >= kLookupRunKeys
   auto count_key = [&](uint32_t key) {
     const uint32_t rel = key - ukey0;
-    if (rel < (uint32_t)kLookupRunKeys) atomicAdd(&counters[rel >> 2], 1u << (8 * (rel & 3)));
+    if (rel < (uint32_t)kLookupRunKeys) atomicAdd(&counters[rel / kPerWord], 1u << (BITS * (rel % kPerWord)));
   };
 #pragma unroll
   for (int k = 0; k < kMaxB; ++k) {
@@ -270,33 +275,27 @@ __global__ __launch_bounds__(1024) void table_lookup_kernel(AttnArgs a, TableArg
   }
   __syncthreads();
 
-  // ballots of the blocks the tables cover: thread = 32 consecutive keys (half a block)
+  // ballots of the blocks the tables cover: a thread takes 32 consecutive keys (half a block)
   const int64_t nblk = key_blocks(cx.n);
-  const int64_t kfirst = key0 + (int64_t)tid * 32;
-  if (kfirst < key_blocks(tb.n) * kBlockKeys) {
+  for (int part = tid; part < kLookupRunKeys / 32; part += 1024) {
+    const int64_t kfirst = key0 + (int64_t)part * 32;
+    if (kfirst >= key_blocks(tb.n) * kBlockKeys) break;
     // positions of this thread's keys that are real and outside the static set
     const int64_t lo = (a.n_sink > kfirst ? a.n_sink : kfirst) - kfirst;
     const int64_t hi_key = cx.n - a.n_local < cx.n ? cx.n - a.n_local : cx.n;
     const int64_t hi = (hi_key < kfirst + 32 ? hi_key : kfirst + 32) - kfirst;
     uint32_t elig = 0;
     if (hi > lo) elig = (hi - lo >= 32 ? 0xffffffffu : ((1u << (hi - lo)) - 1u)) << lo;
+    auto count_of = [&](int j) { return (int)((counters[(part * 32 + j) / kPerWord] >> (BITS * (j % kPerWord))) & kCntMask); };
     uint32_t bits = 0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const uint32_t cw = counters[tid * 8 + j];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int cnt = (cw >> (8 * q)) & 0xff;
-        bits |= (uint32_t)(a.tau <= 0 || cnt >= a.tau) << (j * 4 + q);
-      }
-    }
+    for (int j = 0; j < 32; ++j) bits |= (uint32_t)(a.tau <= 0 || count_of(j) >= a.tau) << j;
     bits &= elig;
     reinterpret_cast<uint32_t*>(a.masks)[(bh * nblk) * 2 + kfirst / 32] = bits;
     if (a.dbg_counts || a.dbg_cand) {                 // debug outputs only
       for (int j = 0; j < 32; ++j) {
         const int64_t i = kfirst + j;
-        const int cnt = (counters[tid * 8 + (j >> 2)] >> (8 * (j & 3))) & 0xff;
-        if (a.dbg_counts && i < cx.n) a.dbg_counts[bh * a.dbg_stride + i] = (uint16_t)cnt;
+        if (a.dbg_counts && i < cx.n) a.dbg_counts[bh * a.dbg_stride + i] = (uint16_t)count_of(j);
         if (a.dbg_cand && ((bits >> j) & 1u)) {
           const int pos = atomicAdd(&a.dbg_ncand[bh], 1);
           if (pos < a.dbg_cand_cap) a.dbg_cand[bh * a.dbg_cand_cap + pos] = (int32_t)i;
@@ -645,6 +644,8 @@ hipError_t launch_lookup_gather(const AttnArgs& a0, const TableArgs& t, int nsli
   else if (a.K == 9 && a.L == 120) launch_lookup_gather_for<9, 4, 24>(a, t, grid, s, start, stop);
   else if (a.K == 10 && a.L == 170) launch_lookup_gather_for<10, 6, 10>(a, t, grid, s, start, stop);
   else if (a.K == 8 && a.L == 75) launch_lookup_gather_for<8, 3, 11>(a, t, grid, s, start, stop);
+  else if (a.K == 10 && a.L == 220) launch_lookup_gather_for<10, 7, 28>(a, t, grid, s, start, stop);
+  else if (a.K == 11 && a.L == 300) launch_lookup_gather_for<11, 10, 12>(a, t, grid, s, start, stop);
   else launch_lookup_gather_for<0, 0, 0>(a, t, grid, s, start, stop);
   return hipGetLastError();
 }
@@ -659,9 +660,13 @@ hipError_t launch_table_lookup(const AttnArgs& a, const TableArgs& t, hipStream_
     else hipLaunchKernelGGL(table_lookup_bitmap_kernel, grid, dim3(1024), bitmap_bytes, s, a, t);
     return hipGetLastError();
   }
-  const dim3 grid((unsigned)((nblk + kLookupRunBlocks - 1) / kLookupRunBlocks), (unsigned)((int64_t)a.B * a.Hq));
-  if (start || stop) hipExtLaunchKernelGGL(table_lookup_kernel, grid, dim3(1024), 0, s, start, stop, 0, a, t);
-  else hipLaunchKernelGGL(table_lookup_kernel, grid, dim3(1024), 0, s, a, t);
+  auto go = [&](auto kernel, int run_blocks) {
+    const dim3 grid((unsigned)((nblk + run_blocks - 1) / run_blocks), (unsigned)((int64_t)a.B * a.Hq));
+    if (start || stop) hipExtLaunchKernelGGL(kernel, grid, dim3(1024), 0, s, start, stop, 0, a, t);
+    else hipLaunchKernelGGL(kernel, grid, dim3(1024), 0, s, a, t);
+  };
+  if (a.L <= 255) go(table_lookup_kernel<8>, kLookupRunBlocks<8>);
+  else go(table_lookup_kernel<16>, kLookupRunBlocks<16>);
   return hipGetLastError();
 }
 

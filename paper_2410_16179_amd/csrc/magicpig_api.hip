@@ -147,8 +147,8 @@ AttnWs ws_attention_layout(const magicpig_params* p) {
 size_t ws_attention(const magicpig_params* p) { return ws_attention_layout(p).total; }
 
 bool tables_supported(const magicpig_params* p) {
-  // bucket offsets are 2^K + 1 words per table; hit counters are bytes; one grid row per head
-  return p->K <= 12 && p->L <= 255 && (int64_t)p->batch * p->n_q_heads <= 65535;
+  // bucket offsets are 2^K + 1 words per table (the build keeps whole histograms in LDS); one grid row per head
+  return p->K <= 12 && (int64_t)p->batch * p->n_q_heads <= 65535;
 }
 
 // workspace of the two-pass table build: the code of every key in every table

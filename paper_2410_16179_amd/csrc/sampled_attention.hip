@@ -292,7 +292,7 @@ static hipError_t launch_scan(const AttnArgs& a, hipStream_t s, hipEvent_t start
                  grid_t, block, s, start, stop, a);                                                 \
     return hipGetLastError();                                                                       \
   }
-  MP_TUNED(10, 150) MP_TUNED(9, 120) MP_TUNED(10, 170) MP_TUNED(8, 75)
+  MP_TUNED(10, 150) MP_TUNED(9, 120) MP_TUNED(10, 170) MP_TUNED(8, 75) MP_TUNED(10, 220) MP_TUNED(11, 300)
 #undef MP_TUNED
   const dim3 grid((unsigned)((nscanned + 3) / 4), (unsigned)(a.B * a.Hkv));
   launch_timed(collision_scan_kernel<0, 0, 0, 1>, grid, block, s, start, stop, a);
@@ -327,6 +327,8 @@ static hipError_t launch_scan_gather(const AttnArgs& a, hipStream_t s, hipEvent_
   else if (a.K == 9 && a.L == 120) launch_scan_gather_for<9, 4, 24>(a, grid, s, start, stop);
   else if (a.K == 10 && a.L == 170) launch_scan_gather_for<10, 6, 10>(a, grid, s, start, stop);
   else if (a.K == 8 && a.L == 75) launch_scan_gather_for<8, 3, 11>(a, grid, s, start, stop);
+  else if (a.K == 10 && a.L == 220) launch_scan_gather_for<10, 7, 28>(a, grid, s, start, stop);   // App. E (K, L) study
+  else if (a.K == 11 && a.L == 300) launch_scan_gather_for<11, 10, 12>(a, grid, s, start, stop);
   else launch_scan_gather_for<0, 0, 0>(a, grid, s, start, stop);
   return hipGetLastError();
 }

@@ -56,6 +56,9 @@ CONFIGS = {
     "C4": Workload("C4", 16, 32, 8, 65536, 9, 120, "bf16", (8, 512)),
     "C5": Workload("C5", 8, 64, 8, 131072, 10, 170, "bf16", (32,)),
 }
+# The benchmark shape (C3) with the larger table sets of the paper's (K, L) study (App. E).
+CONFIGS["C3_K10_L220"] = Workload("C3_K10_L220", 1, 32, 8, 98304, 10, 220, "bf16", (32,))
+CONFIGS["C3_K11_L300"] = Workload("C3_K11_L300", 1, 32, 8, 98304, 11, 300, "bf16", (32,))
 
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:

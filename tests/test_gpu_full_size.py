@@ -74,6 +74,20 @@ def test_c5_whole_batch_at_full_context(oracle):
           f"worst output error {worst:.2e}", flush=True)
 
 
+@pytest.mark.parametrize("name", ["C3_K10_L220", "C3_K11_L300"])
+def test_larger_tables_of_the_hyperparameter_study_at_long_context(oracle, name):
+    # (10,220) and (11,300) of App. E at 65536 keys: their own scan instantiations (69 and 104 code
+    # words per key) and, for 300 tables, the table path beyond 255 tables (16-bit hit counters in
+    # the counting lookup); every key code of two KV heads, four query heads
+    w = wl.scaled(wl.CONFIGS[name], n_ctx=65536)
+    heads = [(0, 5), (0, 6), (0, 30), (0, 31)]
+    ref, res, worst = run_case(oracle, w, heads=heads, oracle_codes_too=False, indexed=(61440,))
+    frac = np.mean([ref["S"][0][h].size for _, h in heads]) / w.n_ctx
+    print(f"   {name}: sampled fraction {frac:.4f} (App. E budget for orthogonal vectors: {oracle.expected_budget(w.K, w.L):.4f}), "
+          f"worst output error {worst:.2e}", flush=True)
+    assert 0.5 * oracle.expected_budget(w.K, w.L) < frac < 4 * oracle.expected_budget(w.K, w.L)
+
+
 def test_c3_ragged_context_in_a_larger_cache(oracle):
     # the benchmark shape with a context that ends inside a code block and inside a run of
     # blocks (the last workgroup of a KV head scans fewer blocks than the others and a part of its
