@@ -100,12 +100,19 @@ __global__ __launch_bounds__(256) void prep_threshold_kernel(HashMfmaArgs a) {
   float c = -INFINITY;                                 // pad rows: never >= 0, never flagged
   if (real) {
     const int j = t * a.K + x % a.K;
-    double th = 0.0;
+    double th = 0.0, mg = 0.0;
     if (mu) {
       const uint16_t* wt = reinterpret_cast<const uint16_t*>(a.wt) + (int64_t)j * kHeadDim;
-      for (int d = 0; d < kHeadDim; ++d) th += (double)mu[d] * (double)__uint_as_float((uint32_t)wt[d] << 16);
+      for (int d = 0; d < kHeadDim; ++d) {
+        const double pm = (double)mu[d] * (double)__uint_as_float((uint32_t)wt[d] << 16);   // exact
+        th += pm;
+        mg += fabs(pm);
+      }
     }
     c = 0.0f - (float)th;                              // +0 when the threshold is zero
+    // for the exact re-evaluation: the same sum in float64 and a float32 upper bound of its magnitude sum
+    a.thr64[(int64_t)unit * a.K * a.L + j] = th;
+    a.magmu[(int64_t)unit * a.K * a.L + j] = (float)mg * 1.000001f;
   }
   const int eta = (rho >> 2) & 1, r = 4 * (rho >> 3) + (rho & 3);
   a.thr[(((int64_t)unit * a.ntiles + T) * 2 + eta) * 16 + r] = c;
@@ -136,37 +143,46 @@ __device__ inline void recheck_pairs(const HashMfmaArgs& a, long long* limb, uin
     const int64_t k = (int64_t)((e >> 16) & 0xffffffffull);
     const int ub = (int)unit / a.n_kv_heads, uh = (int)unit % a.n_kv_heads;
     const int64_t xoff = (int64_t)ub * a.stride_b + (int64_t)uh * a.stride_h + k * a.stride_n;
-    float kv[kPieces][8], wv[kPieces][8], mv[kPieces][8];
+    // Products of two bf16 values are exact in float32; they are added in float64 (at most 128
+    // roundings of 2^-53 of the magnitude sum) and the centering term mu.W_j comes ready-made in
+    // float64 from the threshold kernel, with the same kind of error on its own magnitude sum:
+    // |s - exact| < 2^-45 (sum|k w| + sum|mu w|).  The magnitude sums are float32 upper bounds.
+    uint4 kraw[kPieces], wraw[kPieces];
 #pragma unroll
     for (int p = 0; p < kPieces; ++p) {
       const int d0 = (p * LPP + sl) * 8;
-      load8<false>(Kc, xoff + d0, kv[p]);
-      load8<false>(WT, (int64_t)j * kHeadDim + d0, wv[p]);
-      if (a.mu) load8<true>(a.mu + unit * kHeadDim, d0, mv[p]);
+      kraw[p] = *reinterpret_cast<const uint4*>(Kc + xoff + d0);
+      wraw[p] = *reinterpret_cast<const uint4*>(WT + (int64_t)j * kHeadDim + d0);
     }
-    double s = 0.0, mag = 0.0;
+    double s = 0.0;
+    float magf = 0.f;
 #pragma unroll
     for (int p = 0; p < kPieces; ++p) {
+      const uint32_t ku[4] = {kraw[p].x, kraw[p].y, kraw[p].z, kraw[p].w};
+      const uint32_t wu[4] = {wraw[p].x, wraw[p].y, wraw[p].z, wraw[p].w};
 #pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const double w = (double)wv[p][t];
-        const double pr = (double)kv[p][t] * w;
-        s += pr;
-        mag += fabs(pr);
-        if (a.mu) {
-          const double pm = (double)mv[p][t] * w;
-          s -= pm;
-          mag += fabs(pm);
-        }
+      for (int t = 0; t < 4; ++t) {
+        const float p0 = __uint_as_float(ku[t] << 16) * __uint_as_float(wu[t] << 16);                 // exact
+        const float p1 = __uint_as_float(ku[t] & 0xffff0000u) * __uint_as_float(wu[t] & 0xffff0000u);   // exact
+        s += (double)p0;
+        s += (double)p1;
+        magf += fabsf(p0);
+        magf += fabsf(p1);
       }
     }
 #pragma unroll
     for (int o = LPP / 2; o > 0; o >>= 1) {
       s += __shfl_xor(s, o);
-      mag += __shfl_xor(mag, o);
+      magf += __shfl_xor(magf, o);
+    }
+    double mag = (double)(magf * 1.0001f);
+    if (a.mu) {
+      s -= a.thr64[unit * (a.K * a.L) + j];
+      mag += (double)a.magmu[unit * (a.K * a.L) + j];
     }
     bool bit = s >= 0.0;
-    const bool unsure = on && sl == 0 && mag > 0.0 && fabs(s) <= kF64Slack * mag;
+    // (1e-42: float32 products below 2^-126 are rounded to multiples of 2^-149; 128 of them)
+    const bool unsure = on && sl == 0 && mag > 0.0 && fabs(s) <= kF64Slack * mag + 1e-42;
     uint64_t pending = __ballot(unsure);
     while (pending) {
       const int src = __ffsll((unsigned long long)pending) - 1;

@@ -83,8 +83,9 @@ size_t ws_mean(const magicpig_params* p) {
 }
 
 // key-hashing workspace (bf16, matrix cores):
-// [A fragments | W transposed | thresholds | |mu| | column norms | scalars | flagged-element list]
-struct HashWs { size_t afrag_off, wt_off, thr_off, munorm_off, rownorm_off, scalar_off, list_off, total; int ntiles; uint64_t list_cap; };
+// [A fragments | W transposed | thresholds | thresholds in float64 | their magnitude sums | |mu| |
+//  column norms | scalars | flagged-element list]
+struct HashWs { size_t afrag_off, wt_off, thr_off, thr64_off, magmu_off, munorm_off, rownorm_off, scalar_off, list_off, total; int ntiles; uint64_t list_cap; };
 HashWs ws_hash_layout(const magicpig_params* p) {
   HashWs w{};
   const int NQ = mp::plane_words(p->K, p->L);
@@ -94,7 +95,9 @@ HashWs ws_hash_layout(const magicpig_params* p) {
   w.afrag_off = 0;
   w.wt_off = align256(nquads * 4 * 8 * 64 * 16);
   w.thr_off = w.wt_off + align256((size_t)p->K * p->L * mp::kHeadDim * 2);
-  w.munorm_off = w.thr_off + align256(units * w.ntiles * 32 * sizeof(float));
+  w.thr64_off = w.thr_off + align256(units * w.ntiles * 32 * sizeof(float));
+  w.magmu_off = w.thr64_off + align256(units * (size_t)p->K * p->L * sizeof(double));
+  w.munorm_off = w.magmu_off + align256(units * (size_t)p->K * p->L * sizeof(float));
   w.rownorm_off = w.munorm_off + align256(units * sizeof(float));
   w.scalar_off = w.rownorm_off + align256((size_t)w.ntiles * 32 * sizeof(float));
   w.list_off = w.scalar_off + 256;
@@ -416,6 +419,8 @@ int magicpig_hash_keys(const magicpig_params* p, const void* K_cache, const floa
     m.stride_b = p->k_stride_b; m.stride_h = p->k_stride_h; m.stride_n = p->k_stride_n;
     m.afrag = wsb + wl.afrag_off; m.wt = wsb + wl.wt_off;
     m.thr = reinterpret_cast<float*>(wsb + wl.thr_off);
+    m.thr64 = reinterpret_cast<double*>(wsb + wl.thr64_off);
+    m.magmu = reinterpret_cast<float*>(wsb + wl.magmu_off);
     m.munorm = reinterpret_cast<float*>(wsb + wl.munorm_off);
     m.rownorm = reinterpret_cast<float*>(wsb + wl.rownorm_off);
     m.wmax_bits = reinterpret_cast<unsigned*>(wsb + wl.scalar_off);

@@ -99,6 +99,8 @@ struct HashMfmaArgs {
   void* afrag;                 // projector in MFMA A-fragment order, bf16
   void* wt;                    // projector transposed [K*L][128], bf16
   float* thr;                  // [units][ntiles][2][16] initial accumulators
+  double* thr64;               // [units][K*L] mu.W_j in float64 (exact products, 128 roundings of 2^-53)
+  float* magmu;                // [units][K*L] an upper bound of sum_d |mu_d W_dj|
   float* munorm;               // [units]
   float* rownorm;              // [ntiles*32] norm of the projector column behind each tile row
   unsigned* wmax_bits;         // max column norm of W (float bits), kept for the statistics
