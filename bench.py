@@ -39,13 +39,14 @@ METRIC = "LSH-sampled decode attn: query-heads/s at 96k ctx"
 
 def build_workload(w, data, copies: int):
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
-    Kd = torch.from_numpy(data["K"]).to(tdt).cuda()
-    Vd = torch.from_numpy(data["V"]).to(tdt).cuda()
+    kvt = torch.float8_e4m3fn if w.kv == "fp8" else tdt     # (the generator already rounded the values to the type)
+    Kd = torch.from_numpy(data["K"]).to(kvt).cuda()
+    Vd = torch.from_numpy(data["V"]).to(kvt).cuda()
     qd = torch.from_numpy(data["q"]).to(tdt).cuda()
     Wd = torch.from_numpy(data["W"]).to(tdt).cuda()
     params = mp.make_params(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, K=w.K,
                             L=w.L, n_ctx=w.n_ctx, dtype=w.dtype, min_hits=w.min_hits,
-                            n_sink=w.n_sink, n_local=w.n_local)
+                            n_sink=w.n_sink, n_local=w.n_local, kv_dtype=w.kv)
     sets = []
     for c in range(copies):
         sets.append({
@@ -368,7 +369,7 @@ def main():
         n_dev = torch.zeros(1, dtype=torch.int64, device="cuda")
         live = mp.make_params(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, K=w.K, L=w.L,
                               n_ctx=w.n_ctx, dtype=w.dtype, min_hits=w.min_hits, n_sink=w.n_sink,
-                              n_local=w.n_local, n_ctx_dev=n_dev)
+                              n_local=w.n_local, n_ctx_dev=n_dev, kv_dtype=w.kv)
 
         def token(form):
             n_dev.add_(1)
@@ -404,7 +405,7 @@ def main():
         if tables_info is not None:
             p_idx = mp.make_params(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, K=w.K, L=w.L,
                                    n_ctx=n_idx, n_cap=w.n_ctx, dtype=w.dtype, min_hits=w.min_hits,
-                                   n_sink=w.n_sink, n_local=w.n_local)
+                                   n_sink=w.n_sink, n_local=w.n_local, kv_dtype=w.kv)
             for s_ in sets:
                 mp.magicpig_build_tables(p_idx, s_["codes"], s_["tables"], bws)
             loop_info["tables_ms_per_token"] = time_tokens("tables")
@@ -420,7 +421,8 @@ def main():
 
     n_static = min(w.n_ctx, w.n_sink + w.n_local)
     scan_bytes = w.batch * w.n_kv_heads * max(w.n_ctx - n_static, 0) * w.K * w.L / 8.0
-    gather_bytes = float((n_sampled + n_static).sum()) * 2 * 128 * (2 if w.dtype == "bf16" else 4)
+    kv_elem_bytes = 1 if w.kv == "fp8" else (2 if w.dtype == "bf16" else 4)
+    gather_bytes = float((n_sampled + n_static).sum()) * 2 * 128 * kv_elem_bytes
     out_bytes = heads * 128 * 4
     alg_bytes = scan_bytes + gather_bytes + out_bytes
     # the dominant kernel streams the codes of the eligible keys and gathers the K and V rows
@@ -437,7 +439,8 @@ def main():
         "metric": METRIC, "value": value, "unit": "query-heads/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "dtype": ("bf16" if w.dtype == "bf16" else "f32") + (" (K / V cache: fp8 e4m3)" if w.kv == "fp8" else ""),
+        "data": "synthetic",
         "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads} query / {w.n_kv_heads} KV heads, "
                                f"head_dim 128, context {w.n_ctx}, K={w.K} L={w.L}, min_hits {w.min_hits}, "
                                f"{w.n_sink} sink + {w.n_local} local, {args.copies} rotating cache copies",

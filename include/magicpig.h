@@ -27,7 +27,8 @@
  *  - Tensors: q [batch, n_q_heads, 128]; K/V cache [batch, n_kv_heads, n, 128] addressed
  *    through element strides (innermost dimension contiguous); W [128, K*L] row-major,
  *    column t*K + b being hyperplane b of table t; mu [batch, n_kv_heads, 128] float32.
- *    q, K, V, W share the element type `dtype` (bf16 or float32).
+ *    q, K, V, W share the element type `dtype` (bf16 or float32), unless kv_dtype gives the
+ *    caches a storage type of their own.
  *  - Grouped-query attention: query head h uses KV head h / (n_q_heads / n_kv_heads).
  */
 #ifndef MAGICPIG_H
@@ -44,6 +45,11 @@ extern "C" {
 #define MAGICPIG_API __attribute__((visibility("default")))
 
 enum { MAGICPIG_BF16 = 0, MAGICPIG_FP32 = 1 };
+/* storage type of the K / V cache (magicpig_params.kv_dtype) */
+enum { MAGICPIG_KV_SAME = 0,        /* the caches hold `dtype` elements                          */
+       MAGICPIG_KV_FP8_E4M3 = 1 };  /* the caches hold OCP e4m3 bytes (quantised K / V, the
+                                       paper's App. "Limitations and future work"); needs dtype
+                                       BF16 for q and W                                          */
 
 enum {
   MAGICPIG_OK = 0,
@@ -79,6 +85,10 @@ typedef struct magicpig_params {
                          loop; n_ctx is then the largest value the word may hold (grids and
                          workspace are sized for it; larger values are clamped to it).  The other
                          calls ignore it. */
+  int32_t kv_dtype;   /* MAGICPIG_KV_SAME | MAGICPIG_KV_FP8_E4M3.  An e4m3 cache element stands for
+                         the value its byte decodes to (no scale): every result - hash codes, sample,
+                         probabilities, output - is defined on those values exactly as for the other
+                         types (each e4m3 value is also a bf16 value).  Strides stay in elements. */
 } magicpig_params;
 
 /* ---- packed code layout (part of the contract: the caller stores codes between calls) ----

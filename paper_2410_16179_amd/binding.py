@@ -18,6 +18,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("MAGICPIG_LIB") or os.path.join(_PKG, "libmagicpig.so")
 
 MAGICPIG_BF16, MAGICPIG_FP32 = 0, 1
+MAGICPIG_KV_SAME, MAGICPIG_KV_FP8_E4M3 = 0, 1
 
 
 class MagicpigError(RuntimeError):
@@ -34,6 +35,7 @@ class magicpig_params(ctypes.Structure):
         ("k_stride_b", ctypes.c_int64), ("k_stride_h", ctypes.c_int64), ("k_stride_n", ctypes.c_int64),
         ("v_stride_b", ctypes.c_int64), ("v_stride_h", ctypes.c_int64), ("v_stride_n", ctypes.c_int64),
         ("n_ctx_dev", ctypes.c_void_p),
+        ("kv_dtype", ctypes.c_int32),
     ]
 
 
@@ -124,9 +126,11 @@ def _stream() -> int:
 
 def make_params(*, batch, n_q_heads, n_kv_heads, K, L, n_ctx, dtype, n_cap=None, min_hits=2,
                 n_sink=4, n_local=64, head_dim=128, k_strides=None, v_strides=None,
-                n_ctx_dev=None) -> magicpig_params:
+                n_ctx_dev=None, kv_dtype=0) -> magicpig_params:
     """Parameter block; strides default to a contiguous [batch, n_kv_heads, n_cap, 128] cache.
-    n_ctx_dev: an int64 device tensor holding the live context length, or None."""
+    n_ctx_dev: an int64 device tensor holding the live context length, or None.
+    kv_dtype: 0 (caches hold `dtype`), 1 or "fp8" (caches hold OCP e4m3 bytes)."""
+    kv_dtype = {"fp8": MAGICPIG_KV_FP8_E4M3, "": 0, None: 0}.get(kv_dtype, kv_dtype)
     n_cap = n_ctx if n_cap is None else n_cap
     dense = (n_kv_heads * n_cap * head_dim, n_cap * head_dim, head_dim)
     ks = dense if k_strides is None else tuple(k_strides)
@@ -135,7 +139,7 @@ def make_params(*, batch, n_q_heads, n_kv_heads, K, L, n_ctx, dtype, n_cap=None,
             torch.float32: MAGICPIG_FP32}.get(dtype, dtype)
     return magicpig_params(batch, n_q_heads, n_kv_heads, head_dim, K, L, min_hits, n_sink, n_local,
                            code, n_ctx, n_cap, ks[0], ks[1], ks[2], vs[0], vs[1], vs[2],
-                           None if n_ctx_dev is None else n_ctx_dev.data_ptr())
+                           None if n_ctx_dev is None else n_ctx_dev.data_ptr(), kv_dtype)
 
 
 def magicpig_code_words_per_key(params) -> int:

@@ -290,10 +290,12 @@ __device__ inline void request_head_vectors(const AttnArgs& a, int unit, int64_t
 // row; the inclusion probability and the logit q.k/sqrt(d) - log u are evaluated once per key
 // (the first n_sampled keys only: the keys behind them, static ones, enter with u = 1); an
 // online max/sum softmax accumulates the weighted V rows.
-template <bool FP32, int kIters, class KeyOf>
+// ET: element type of the K / V caches (kBF16, kFP32, or kFP8 with bf16 queries).
+template <int ET, int kIters, class KeyOf>
 __device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t bh, int total, int n_sampled,
-                                            const HeadVectors<FP32>& hv, KeyOf key_of, float* pp) {
+                                            const HeadVectors<ET == kFP32>& hv, KeyOf key_of, float* pp) {
   static_assert(kIters >= 1 && kIters <= 16, "one lane of a quarter wavefront per row of a batch");
+  constexpr bool FP32 = ET == kFP32;
   const int lane = threadIdx.x & 63;
   const int b = unit / a.Hkv, g = unit % a.Hkv;
   const int qd = lane >> 4, sl = lane & 15;
@@ -320,15 +322,15 @@ __device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t
       if (it < rounds) {
         const uint32_t idx = (uint32_t)key_of(ok[it] ? cc : base);
         if (ok[it]) {
-          frag_load<FP32>(a.Kc, kbase + (int64_t)((uint64_t)idx * ksn), kf[it]);
-          frag_load<FP32>(a.Vc, vbase + (int64_t)((uint64_t)idx * vsn), vf[it]);
+          frag_load<ET>(a.Kc, kbase + (int64_t)((uint64_t)idx * ksn), kf[it]);
+          frag_load<ET>(a.Vc, vbase + (int64_t)((uint64_t)idx * vsn), vf[it]);
         } else {
-          frag_zero<FP32>(kf[it]);
-          frag_zero<FP32>(vf[it]);
+          frag_zero<ET>(kf[it]);
+          frag_zero<ET>(vf[it]);
         }
       } else {
-        frag_zero<FP32>(kf[it]);
-        frag_zero<FP32>(vf[it]);
+        frag_zero<ET>(kf[it]);
+        frag_zero<ET>(vf[it]);
       }
     }
     // (first use of the query and the centering vector: after the rows have been requested)
@@ -347,9 +349,9 @@ __device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t
     for (int it = 0; it < kIters; ++it) {
       if (it >= rounds) break;
       float kv[8];
-      frag_to_float<FP32>(kf[it], kv);
+      frag_to_float<ET>(kf[it], kv);
       float dq = 0.f, nn = 0.f;
-      if constexpr (FP32) {
+      if constexpr (ET != kBF16) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) dq += qf[e] * kv[e];
       } else {
@@ -393,7 +395,7 @@ __device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t
       if (it >= rounds) break;
       const float wv = __shfl(wgt, (lane & 48) | it);
       float vv[8];
-      frag_to_float<FP32>(vf[it], vv);
+      frag_to_float<ET>(vf[it], vv);
 #pragma unroll
       for (int e = 0; e < 8; ++e) o[e] += wv * vv[e];
     }

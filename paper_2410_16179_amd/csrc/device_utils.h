@@ -6,16 +6,52 @@
 
 namespace mp {
 
-// Eight consecutive elements of a 128-element row, as stored (bf16: 16 bytes, float32: 32).
+// Element types of the tensors.  The helpers below take one as template argument; a `bool FP32`
+// converts to kBF16 / kFP32.  kFP8: OCP e4m3 bytes (value = the decoded byte, no scale), a storage
+// type of the K / V cache only; every e4m3 value is a bf16 value.
+enum : int { kBF16 = 0, kFP32 = 1, kFP8 = 2 };
+
+typedef float mp_f32x2 __attribute__((ext_vector_type(2)));
+// eight e4m3 bytes -> eight floats (v_cvt_pk_f32_fp8: two per instruction)
+__device__ inline void fp8x8_to_float(uint32_t lo, uint32_t hi, float (&v)[8]) {
+  const mp_f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)lo, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)lo, true);
+  const mp_f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8((int)hi, false), d = __builtin_amdgcn_cvt_pk_f32_fp8((int)hi, true);
+  v[0] = a.x; v[1] = a.y; v[2] = b.x; v[3] = b.y; v[4] = c.x; v[5] = c.y; v[6] = d.x; v[7] = d.y;
+}
+// eight e4m3 bytes -> the same eight values as bf16 (exact: e4m3 has 3 mantissa bits), packed
+__device__ inline uint4 fp8x8_to_bf16x8(uint32_t lo, uint32_t hi) {
+  float v[8];
+  fp8x8_to_float(lo, hi, v);
+  uint4 r;
+  r.x = (__float_as_uint(v[0]) >> 16) | (__float_as_uint(v[1]) & 0xffff0000u);
+  r.y = (__float_as_uint(v[2]) >> 16) | (__float_as_uint(v[3]) & 0xffff0000u);
+  r.z = (__float_as_uint(v[4]) >> 16) | (__float_as_uint(v[5]) & 0xffff0000u);
+  r.w = (__float_as_uint(v[6]) >> 16) | (__float_as_uint(v[7]) & 0xffff0000u);
+  return r;
+}
+__device__ inline float fp8_to_float(uint8_t b) {
+  const mp_f32x2 v = __builtin_amdgcn_cvt_pk_f32_fp8((int)(uint32_t)b, false);
+  return v.x;
+}
+// bytes per element
+__host__ __device__ inline int elem_bytes(int et) { return et == kFP32 ? 4 : (et == kFP8 ? 1 : 2); }
+
+// Eight consecutive elements of a 128-element row, as stored (e4m3: 8 bytes in a.x, a.y; bf16: 16
+// bytes; float32: 32).
 struct Frag {
   uint4 a, b;
 };
 
 // The rows of a decode step are read once: non-temporal loads.
-template <bool FP32>
+template <int ET>
 __device__ inline void frag_load(const void* base, int64_t elem, Frag& f) {
   typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-  if constexpr (FP32) {
+  if constexpr (ET == kFP8) {
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 a = __builtin_nontemporal_load(
+        reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(base) + elem));
+    f.a.x = a.x; f.a.y = a.y;
+  } else if constexpr (ET == kFP32) {
     const u32x4* p = reinterpret_cast<const u32x4*>(reinterpret_cast<const float*>(base) + elem);
     const u32x4 a = __builtin_nontemporal_load(p), b = __builtin_nontemporal_load(p + 1);
     f.a = make_uint4(a.x, a.y, a.z, a.w);
@@ -27,15 +63,17 @@ __device__ inline void frag_load(const void* base, int64_t elem, Frag& f) {
   }
 }
 
-template <bool FP32>
+template <int ET>
 __device__ inline void frag_zero(Frag& f) {
   f.a = make_uint4(0, 0, 0, 0);
-  if constexpr (FP32) f.b = make_uint4(0, 0, 0, 0);
+  if constexpr (ET == kFP32) f.b = make_uint4(0, 0, 0, 0);
 }
 
-template <bool FP32>
+template <int ET>
 __device__ inline void frag_to_float(const Frag& f, float (&v)[8]) {
-  if constexpr (FP32) {
+  if constexpr (ET == kFP8) {
+    fp8x8_to_float(f.a.x, f.a.y, v);
+  } else if constexpr (ET == kFP32) {
     v[0] = __uint_as_float(f.a.x); v[1] = __uint_as_float(f.a.y);
     v[2] = __uint_as_float(f.a.z); v[3] = __uint_as_float(f.a.w);
     v[4] = __uint_as_float(f.b.x); v[5] = __uint_as_float(f.b.y);
@@ -51,9 +89,12 @@ __device__ inline void frag_to_float(const Frag& f, float (&v)[8]) {
 }
 
 // Eight consecutive elements starting at element index `elem`, converted to float32.
-template <bool FP32>
+template <int ET>
 __device__ inline void load8(const void* base, int64_t elem, float (&v)[8]) {
-  if constexpr (FP32) {
+  if constexpr (ET == kFP8) {
+    const uint2 r = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint8_t*>(base) + elem);
+    fp8x8_to_float(r.x, r.y, v);
+  } else if constexpr (ET == kFP32) {
     const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + elem);
     const float4 a = p[0], b = p[1];
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;

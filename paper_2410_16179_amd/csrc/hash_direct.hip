@@ -21,6 +21,21 @@ __device__ inline double load_elem(const void* p, int64_t idx) {
   const uint32_t b = reinterpret_cast<const uint16_t*>(p)[idx];
   return (double)__uint_as_float(b << 16);
 }
+// element idx of the vectors X of a call: as above, or an e4m3 byte of a quantised K cache
+template <bool FP32>
+__device__ inline double load_x_elem(const HashDirectArgs& a, int64_t idx) {
+  if constexpr (!FP32) {
+    if (a.x_fp8) return (double)fp8_to_float(reinterpret_cast<const uint8_t*>(a.X)[idx]);
+  }
+  return load_elem<FP32>(a.X, idx);
+}
+template <bool FP32>
+__device__ inline void load_x8(const HashDirectArgs& a, int64_t idx, float (&v)[8]) {
+  if constexpr (!FP32) {
+    if (a.x_fp8) { load8<kFP8>(a.X, idx, v); return; }
+  }
+  load8<FP32>(a.X, idx, v);
+}
 
 // One wavefront codes two vectors at a time: lanes 0..31 take tables 32w..32w+31 of the
 // first, lanes 32..63 of the second; a ballot turns the 64 sign tests into two code words.
@@ -72,7 +87,7 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
 #pragma unroll
       for (int i = 0; i < kHeadDim; i += 8) {
         float v[8];
-        load8<FP32>(a.X, xbase + i, v);
+        load_x8<FP32>(a, xbase + i, v);
 #pragma unroll
         for (int e = 0; e < 8; ++e) xf[i + e] = v[e];
       }
@@ -103,7 +118,7 @@ __global__ __launch_bounds__(256) void hash_direct_kernel(HashDirectArgs a) {
       const float* smu = a.mu ? a.mu + su * kHeadDim : nullptr;
       const bool r = exact_sign_nonneg_wave(
           limbs[wave],
-          [&](int d) { return load_elem<FP32>(a.X, xb + d); },
+          [&](int d) { return load_x_elem<FP32>(a, xb + d); },
           [&](int d) { return load_elem<FP32>(a.W, (int64_t)d * ncol + sj); },
           [&](int d) { return smu ? (double)smu[d] : 0.0; }, smu != nullptr);
       if (lane == src) bit = r;
@@ -243,6 +258,10 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
         v = make_float4(-m.x, -m.y, -m.z, -m.w);
       } else if constexpr (FP32) {
         v = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.X) + xb[rr] + i4 * 4);
+      } else if (a.x_fp8) {                              // rows of an e4m3 K cache
+        const uint32_t r = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(a.X) + xb[rr] + i4 * 4);
+        const mp_f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)r, false), hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)r, true);
+        v = make_float4(lo.x, lo.y, hi.x, hi.y);
       } else {
         const uint2 r = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a.X) + xb[rr] + i4 * 4);
         v = make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u),
@@ -396,7 +415,7 @@ __global__ __launch_bounds__(512) void hash_rows_kernel(HashDirectArgs a0, HashD
       const int64_t xbase = xb[rr];
       const bool r = exact_sign_nonneg_wave(
           limbs[wave],
-          [&](int d) { return load_elem<FP32>(a.X, xbase + d); },
+          [&](int d) { return load_x_elem<FP32>(a, xbase + d); },
           [&](int d) { return load_elem<FP32>(a.W, (int64_t)d * ncol + sj); },
           [&](int d) { return smu ? (double)smu[d] : 0.0; }, smu != nullptr);
       if (lane == src) bit = r;

@@ -154,12 +154,26 @@ __global__ __launch_bounds__(512) void hash_few_mfma_kernel(HashFewArgs a) {
             (unit % a.n_kv_heads) * a.stride_h + key * a.stride_n;
     rp[1] = rp[0];
   }
+  const bool key8 = is_key && a.kv_fp8;                    // the key rows are e4m3 bytes (wave-uniform)
   const bool two = !is_key && grp * 64 + 32 < a.n_q;       // a second tile of vectors (wave-uniform)
+  if (key8) {
+    // (same element offset, one byte per element; widened to the same values in bf16)
+    const uint8_t* row8 = reinterpret_cast<const uint8_t*>(a.Kc) + (rp[0] - reinterpret_cast<const uint16_t*>(a.Kc)) + hh * 8;
+    uint2 r8[8];
 #pragma unroll
-  for (int s = 0; s < 8; ++s) {
-    B[0][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(rp[0] + s * 16 + hh * 8));
-    if (two) B[1][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(rp[1] + s * 16 + hh * 8));
-    else B[1][s] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+    for (int s = 0; s < 8; ++s) r8[s] = *reinterpret_cast<const uint2*>(row8 + s * 16);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      B[0][s] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(r8[s].x, r8[s].y));
+      B[1][s] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+    }
+  } else {
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      B[0][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(rp[0] + s * 16 + hh * 8));
+      if (two) B[1][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(rp[1] + s * 16 + hh * 8));
+      else B[1][s] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+    }
   }
   const bool centered = is_key && a.mu != nullptr;
   f32x16 acc[2][2];

@@ -151,7 +151,12 @@ __device__ inline void recheck_pairs(const HashMfmaArgs& a, long long* limb, uin
 #pragma unroll
     for (int p = 0; p < kPieces; ++p) {
       const int d0 = (p * LPP + sl) * 8;
-      kraw[p] = *reinterpret_cast<const uint4*>(Kc + xoff + d0);
+      if (a.kv_fp8) {                                    // e4m3 bytes, widened to the same values in bf16
+        const uint2 r8 = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint8_t*>(a.Kc) + xoff + d0);
+        kraw[p] = fp8x8_to_bf16x8(r8.x, r8.y);
+      } else {
+        kraw[p] = *reinterpret_cast<const uint4*>(Kc + xoff + d0);
+      }
       wraw[p] = *reinterpret_cast<const uint4*>(WT + (int64_t)j * kHeadDim + d0);
     }
     double s = 0.0;
@@ -192,7 +197,10 @@ __device__ inline void recheck_pairs(const HashMfmaArgs& a, long long* limb, uin
       const float* smu = a.mu ? a.mu + su * kHeadDim : nullptr;
       const bool r = exact_sign_nonneg_wave(
           limb,
-          [&](int d) { return (double)__uint_as_float((uint32_t)Kc[sx + d] << 16); },
+          [&](int d) {
+            return a.kv_fp8 ? (double)fp8_to_float(reinterpret_cast<const uint8_t*>(a.Kc)[sx + d])
+                            : (double)__uint_as_float((uint32_t)Kc[sx + d] << 16);
+          },
           [&](int d) { return (double)__uint_as_float((uint32_t)WT[(int64_t)sj * kHeadDim + d] << 16); },
           [&](int d) { return smu ? (double)smu[d] : 0.0; }, smu != nullptr);
       if (lane == src) bit = r;
@@ -256,9 +264,18 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
     key[bt] = cb * kBlockKeys + bt * 32 + kap;
     key_ok[bt] = wave_on && key[bt] >= first && key[bt] < last;
     const int64_t krow = key_ok[bt] ? key[bt] : first;  // any valid row for masked lanes
+    if (a.kv_fp8) {                                      // e4m3 bytes, widened to the same values in bf16
+      const uint8_t* row8 = reinterpret_cast<const uint8_t*>(a.Kc) + ubase + krow * a.stride_n + hh * 8;
+      uint2 r8[8];
 #pragma unroll
-    for (int s = 0; s < 8; ++s)
-      B[bt][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(Kc + ubase + krow * a.stride_n + s * 16 + hh * 8));
+      for (int s = 0; s < 8; ++s) r8[s] = *reinterpret_cast<const uint2*>(row8 + s * 16);
+#pragma unroll
+      for (int s = 0; s < 8; ++s) B[bt][s] = __builtin_bit_cast(bf16x8, fp8x8_to_bf16x8(r8[s].x, r8[s].y));
+    } else {
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+        B[bt][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(Kc + ubase + krow * a.stride_n + s * 16 + hh * 8));
+    }
   }
   // largest column norm of the projector (requested together with the keys)
   __shared__ float sWmax[4];

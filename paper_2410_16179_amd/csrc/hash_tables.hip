@@ -426,8 +426,9 @@ hipError_t launch_build_tables(const TableArgs& t, hipStream_t s) {
 // 16 code blocks per slice, are found by the collision scan in the workgroups of slice 0, 1,
 // ... and join the gather batches there.
 // KT, WDT, LT: the collision scan's compile-time K, ceil(L/32) and tables of the last group (0: any).
-template <int KT, int WDT, int LT, bool FP32>
+template <int KT, int WDT, int LT, int ET>
 __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableArgs tb) {
+  constexpr bool FP32 = ET == kFP32;
   constexpr int kSliceWords = kLgSliceBlocks * 2;       // 32-key words of a slice
   constexpr int kWaveWords = kLgWaveBlocks * 2;
   __shared__ uint32_t seen[kSliceWords], twice[kSliceWords];
@@ -615,7 +616,7 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
   // static keys slot, slot + slots, ... ride along behind the sampled ones
   const int slots = a.lg_nslices * 16, slot = slice * 16 + wave;
   const int nst = static_share(cx, slot, slots);
-  gather_estimate_wave<FP32, (FP32 ? 4 : 8)>(a, unit, bh, n_sampled + nst, n_sampled, hv,
+  gather_estimate_wave<ET, (FP32 ? 4 : 8)>(a, unit, bh, n_sampled + nst, n_sampled, hv,
                                             [&](int cc) {
                                               if (cc >= n_sampled) return static_key(a, cx, slot + (int64_t)(cc - n_sampled) * slots);
                                               return (cc < in_slice ? wave_key0 : app_blk * kBlockKeys) + (int64_t)list[cc];
@@ -625,13 +626,13 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
 
 template <int KT, int WDT, int LT>
 static void launch_lookup_gather_for(const AttnArgs& a, const TableArgs& t, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
-  if (a.is_fp32) {
-    if (start || stop) hipExtLaunchKernelGGL((lookup_gather_kernel<KT, WDT, LT, true>), grid, dim3(1024), 0, s, start, stop, 0, a, t);
-    else hipLaunchKernelGGL((lookup_gather_kernel<KT, WDT, LT, true>), grid, dim3(1024), 0, s, a, t);
-  } else {
-    if (start || stop) hipExtLaunchKernelGGL((lookup_gather_kernel<KT, WDT, LT, false>), grid, dim3(1024), 0, s, start, stop, 0, a, t);
-    else hipLaunchKernelGGL((lookup_gather_kernel<KT, WDT, LT, false>), grid, dim3(1024), 0, s, a, t);
-  }
+  auto go = [&](auto kernel) {
+    if (start || stop) hipExtLaunchKernelGGL(kernel, grid, dim3(1024), 0, s, start, stop, 0, a, t);
+    else hipLaunchKernelGGL(kernel, grid, dim3(1024), 0, s, a, t);
+  };
+  if (a.is_fp32) go(lookup_gather_kernel<KT, WDT, LT, kFP32>);
+  else if (a.kv_fp8) go(lookup_gather_kernel<KT, WDT, LT, kFP8>);
+  else go(lookup_gather_kernel<KT, WDT, LT, kBF16>);
 }
 
 hipError_t launch_lookup_gather(const AttnArgs& a0, const TableArgs& t, int nslices, int appended_runs, hipStream_t s, hipEvent_t start, hipEvent_t stop) {

@@ -7,7 +7,7 @@
 
 namespace mp {
 
-template <bool FP32>
+template <int ET>
 __global__ __launch_bounds__(256) void key_mean_partial_kernel(MeanArgs a) {
   __shared__ double red[16][kHeadDim];
   const int unit = blockIdx.y, chunk = blockIdx.x;
@@ -19,7 +19,7 @@ __global__ __launch_bounds__(256) void key_mean_partial_kernel(MeanArgs a) {
 #pragma unroll 4
   for (int64_t i = r0 + rl; i < r1; i += 16) {
     float v[8];
-    load8<FP32>(a.Kc, base + i * a.stride_n + cg * 8, v);
+    load8<ET>(a.Kc, base + i * a.stride_n + cg * 8, v);
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] += v[e];
   }
@@ -56,8 +56,9 @@ hipError_t launch_key_mean(const MeanArgs& a, hipStream_t s) {
   if (a.units <= 0) return hipSuccess;
   if (a.nchunk > 0) {
     dim3 grid((unsigned)a.nchunk, (unsigned)a.units);
-    if (a.is_fp32) hipLaunchKernelGGL(key_mean_partial_kernel<true>, grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(key_mean_partial_kernel<false>, grid, dim3(256), 0, s, a);
+    if (a.is_fp32) hipLaunchKernelGGL(key_mean_partial_kernel<kFP32>, grid, dim3(256), 0, s, a);
+    else if (a.kv_fp8) hipLaunchKernelGGL(key_mean_partial_kernel<kFP8>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(key_mean_partial_kernel<kBF16>, grid, dim3(256), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

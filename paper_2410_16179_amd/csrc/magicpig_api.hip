@@ -55,6 +55,8 @@ int check_params(const magicpig_params* p) {
   if (p->head_dim != mp::kHeadDim) return MAGICPIG_UNSUPPORTED;
   if (p->K < 1 || p->K > 16 || p->L < 1 || p->L > 512) return MAGICPIG_UNSUPPORTED;
   if (p->dtype != MAGICPIG_BF16 && p->dtype != MAGICPIG_FP32) return MAGICPIG_UNSUPPORTED;
+  if (p->kv_dtype != MAGICPIG_KV_SAME && p->kv_dtype != MAGICPIG_KV_FP8_E4M3) return MAGICPIG_UNSUPPORTED;
+  if (p->kv_dtype == MAGICPIG_KV_FP8_E4M3 && p->dtype != MAGICPIG_BF16) return MAGICPIG_UNSUPPORTED;
   const int G = p->n_q_heads / p->n_kv_heads;
   if (G > 8) return MAGICPIG_UNSUPPORTED;                 // a workgroup keeps the ballots of at most eight heads
   if (p->n_cap > (int64_t)1 << 31) return MAGICPIG_UNSUPPORTED;
@@ -228,6 +230,7 @@ mp::HashDirectArgs key_rows(const magicpig_params* p, const void* K_cache, const
   mp::HashDirectArgs a{};
   a.X = K_cache; a.W = W; a.mu = mu; a.codes = key_codes;
   a.is_fp32 = p->dtype == MAGICPIG_FP32;
+  a.x_fp8 = p->kv_dtype == MAGICPIG_KV_FP8_E4M3;
   a.K = p->K; a.L = p->L; a.NW = mp::code_words(p->K, p->L); a.NQ = mp::plane_words(p->K, p->L);
   a.query_layout = 0;
   a.n_keys = n_keys > 0 ? n_keys : 1; a.first_key = first_key;
@@ -305,6 +308,7 @@ int run_attention_impl(const magicpig_params* p, const void* q, const void* K_ca
   a.dbg_counts = dbg_counts; a.dbg_cand = dbg_cand; a.dbg_ncand = dbg_ncand; a.dbg_cand_cap = dbg_cand_cap;
   a.dbg_stride = p->n_ctx; a.n_dev = p->n_ctx_dev;
   a.is_fp32 = p->dtype == MAGICPIG_FP32;
+  a.kv_fp8 = p->kv_dtype == MAGICPIG_KV_FP8_E4M3;
   a.B = p->batch; a.Hq = p->n_q_heads; a.Hkv = p->n_kv_heads; a.K = p->K; a.L = p->L;
   a.Wd = mp::table_words(p->L); a.NW = mp::code_words(p->K, p->L); a.NQ = mp::plane_words(p->K, p->L);
   a.tau = p->min_hits; a.n_sink = p->n_sink; a.n_local = p->n_local;
@@ -386,6 +390,7 @@ int magicpig_key_mean(const magicpig_params* p, const void* K_cache, float* mu_o
   mp::MeanArgs a{};
   a.Kc = K_cache; a.mu = mu_out; a.partial = reinterpret_cast<double*>(workspace);
   a.is_fp32 = p->dtype == MAGICPIG_FP32;
+  a.kv_fp8 = p->kv_dtype == MAGICPIG_KV_FP8_E4M3;
   a.n_kv_heads = p->n_kv_heads; a.units = p->batch * p->n_kv_heads; a.n = p->n_ctx;
   a.rows_per_chunk = kMeanRowsPerChunk;
   a.nchunk = (int)((p->n_ctx + kMeanRowsPerChunk - 1) / kMeanRowsPerChunk);
@@ -415,6 +420,7 @@ int magicpig_hash_keys(const magicpig_params* p, const void* K_cache, const floa
     m.Kc = K_cache; m.W = W; m.mu = mu; m.codes = key_codes;
     m.K = p->K; m.L = p->L; m.NW = a.NW; m.NQ = a.NQ; m.ntiles = wl.ntiles;
     m.units = p->batch * p->n_kv_heads; m.n_kv_heads = p->n_kv_heads;
+    m.kv_fp8 = p->kv_dtype == MAGICPIG_KV_FP8_E4M3;
     m.n_keys = n_keys; m.first_key = first_key; m.n_cap = p->n_cap; m.blocks_cap = a.blocks_cap;
     m.stride_b = p->k_stride_b; m.stride_h = p->k_stride_h; m.stride_n = p->k_stride_n;
     m.afrag = wsb + wl.afrag_off; m.wt = wsb + wl.wt_off;
@@ -550,6 +556,7 @@ int magicpig_hash_decode_step_prepared(const magicpig_params* p, const void* q, 
   }
   a.q = q; a.qcodes = q_codes; a.n_q = with_q ? p->batch * p->n_q_heads : 0;
   a.Kc = K_cache; a.kcodes = key_codes;
+  a.kv_fp8 = p->kv_dtype == MAGICPIG_KV_FP8_E4M3;
   a.n_krows = with_k ? (int)((int64_t)p->batch * p->n_kv_heads * n_keys) : 0;
   a.n_keys = n_keys > 0 ? n_keys : 1; a.first_key = first_key; a.n_cap = p->n_cap;
   a.blocks_cap = mp::key_blocks(p->n_cap); a.n_dev = p->n_ctx_dev;

@@ -73,6 +73,7 @@ struct HashDirectArgs {
   const float* mu;      // per (b,g) [128] or nullptr
   uint32_t* codes;
   int is_fp32;          // element type of X and W
+  int x_fp8;            // the vectors X are rows of an e4m3 K cache (W is bf16)
   int K, L, NW, NQ;     // NW: words per key code, NQ: plane words (= words per query code)
   int query_layout;     // 1: codes[row][NQ] plane words, pad bits 1;  0: blocked key layout, pad bits 0
   // key addressing: row r in [0, units*n_keys): unit = r / n_keys, i = first_key + r % n_keys
@@ -93,6 +94,7 @@ struct HashDirectArgs {
 struct HashMfmaArgs {
   const void* Kc; const void* W; const float* mu; uint32_t* codes;
   int K, L, NW, NQ, ntiles, units, n_kv_heads;
+  int kv_fp8;                  // the K cache holds e4m3 bytes
   int64_t n_keys, first_key, n_cap, blocks_cap;
   int64_t stride_b, stride_h, stride_n;
   // workspace pieces
@@ -160,6 +162,7 @@ struct HashFewArgs {
   const void* q; uint32_t* qcodes; int n_q;                     // query vectors [n_q][128], codes [n_q][NQ]
   const void* Kc; const float* mu; uint32_t* kcodes;            // key vectors: key first_key + r % n_keys of unit r / n_keys
   int n_krows;                                                  // units * n_keys (0: no keys)
+  int kv_fp8;                                                   // the K cache holds e4m3 bytes
   int64_t n_keys, first_key, n_cap, blocks_cap;
   const int64_t* n_dev;                                         // see HashDirectArgs::n_dev
   int n_kv_heads;
@@ -170,7 +173,7 @@ struct HashFewArgs {
 
 struct MeanArgs {
   const void* Kc; float* mu; double* partial;
-  int is_fp32; int n_kv_heads; int units; int64_t n; int nchunk; int64_t rows_per_chunk;
+  int is_fp32; int kv_fp8; int n_kv_heads; int units; int64_t n; int nchunk; int64_t rows_per_chunk;
   int64_t stride_b, stride_h, stride_n;
 };
 
@@ -184,7 +187,8 @@ struct AttnArgs {
   uint64_t* masks;        // [B*Hq][key blocks] ballots of sampled + static keys
   uint16_t* dbg_counts; int32_t* dbg_cand; int32_t* dbg_ncand; int64_t dbg_cand_cap;
   int64_t dbg_stride;     // keys per head in dbg_counts (the launch-time context length)
-  int is_fp32;
+  int is_fp32;            // q, K, V are float32 (else q is bf16)
+  int kv_fp8;             // K and V caches hold e4m3 bytes (q is bf16)
   int B, Hq, Hkv, K, L, Wd, NW, NQ, tau, n_sink, n_local;
   int64_t n, blocks_cap;
   // if not null: the context length in device memory, read by the kernels when they run (a decode

@@ -57,12 +57,13 @@ __global__ __launch_bounds__(256) void collision_scan_kernel(AttnArgs a) {
 }
 
 // rows per quarter wavefront and batch of the stand-alone gather: 32 K and 32 V rows in flight
-template <bool FP32> constexpr int kGatherIters = FP32 ? 4 : 8;
+template <int ET> constexpr int kGatherIters = ET == kFP32 ? 4 : 8;
 
 // One wavefront = one (query head, run of kRangeBlocks key blocks).  blockDim = 64 * G:
 // the G wavefronts of a workgroup serve the G heads of one KV head on the same run.
-template <bool FP32>
+template <int ET>
 __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
+  constexpr bool FP32 = ET == kFP32;
   __shared__ uint16_t lists[8][kRangeBlocks * kBlockKeys];
   const Ctx c = resolve_context(a);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -108,10 +109,10 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
   }
   float* pp = a.partial + (bh * a.nranges + range) * kPartialStride;
   if (!is_static) {
-    gather_estimate_wave<FP32, kGatherIters<FP32>>(a, unit, bh, total, total, hv,
+    gather_estimate_wave<ET, kGatherIters<ET>>(a, unit, bh, total, total, hv,
                                [&](int cc) { return blk0 * kBlockKeys + (int64_t)list[cc]; }, pp);
   } else {
-    gather_estimate_wave<FP32, kGatherIters<FP32>>(a, unit, bh, total, 0, hv,
+    gather_estimate_wave<ET, kGatherIters<ET>>(a, unit, bh, total, 0, hv,
                                [&](int cc) { return static_key(a, c, static_first + cc); }, pp);
   }
 }
@@ -135,8 +136,10 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
 // they cost neither workgroups nor batches nor partials of their own.
 // One partial per (head, run).
 // DBG: with the debug outputs (counts, candidate lists).
-template <int KT, int WDT, int LT, bool FP32, bool DBG>
+// ET: element type of the caches (kBF16, kFP32, or kFP8 with bf16 queries).
+template <int KT, int WDT, int LT, int ET, bool DBG>
 __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
+  constexpr bool FP32 = ET == kFP32;
   constexpr int kIt = FP32 ? (kFusedIters + 1) / 2 : kFusedIters;   // the same registers per batch
   __shared__ uint64_t smask[8][kFusedBlocks];
   __shared__ uint16_t lists[4][kFusedBlocks * kBlockKeys];
@@ -195,7 +198,7 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
     __builtin_amdgcn_wave_barrier();
     // static keys run, run + nruns, ... ride along behind the sampled ones
     const int nst = static_share(c, run, nruns);
-    gather_estimate_wave<FP32, kIt>(ga, unit, head0 + h, total + nst, total, hv,
+    gather_estimate_wave<ET, kIt>(ga, unit, head0 + h, total + nst, total, hv,
                                     [&](int cc) {
                                       return cc < total ? blk0 * kBlockKeys + (int64_t)list[cc]
                                                         : static_key(ga, c, run + (int64_t)(cc - total) * nruns);
@@ -313,11 +316,14 @@ static void launch_scan_gather_for(const AttnArgs& a, dim3 grid, hipStream_t s, 
   const dim3 block(256);
   const bool dbg = a.dbg_counts || a.dbg_cand;
   if (a.is_fp32) {
-    if (dbg) launch_timed(scan_gather_kernel<KT, WDT, LT, true, true>, grid, block, s, start, stop, a);
-    else launch_timed(scan_gather_kernel<KT, WDT, LT, true, false>, grid, block, s, start, stop, a);
+    if (dbg) launch_timed(scan_gather_kernel<KT, WDT, LT, kFP32, true>, grid, block, s, start, stop, a);
+    else launch_timed(scan_gather_kernel<KT, WDT, LT, kFP32, false>, grid, block, s, start, stop, a);
+  } else if (a.kv_fp8) {
+    if (dbg) launch_timed(scan_gather_kernel<KT, WDT, LT, kFP8, true>, grid, block, s, start, stop, a);
+    else launch_timed(scan_gather_kernel<KT, WDT, LT, kFP8, false>, grid, block, s, start, stop, a);
   } else {
-    if (dbg) launch_timed(scan_gather_kernel<KT, WDT, LT, false, true>, grid, block, s, start, stop, a);
-    else launch_timed(scan_gather_kernel<KT, WDT, LT, false, false>, grid, block, s, start, stop, a);
+    if (dbg) launch_timed(scan_gather_kernel<KT, WDT, LT, kBF16, true>, grid, block, s, start, stop, a);
+    else launch_timed(scan_gather_kernel<KT, WDT, LT, kBF16, false>, grid, block, s, start, stop, a);
   }
 }
 
@@ -383,8 +389,9 @@ hipError_t launch_sampled_attention(const AttnArgs& a, const TableArgs* tables, 
     return hipGetLastError();
   }
   const dim3 grid((unsigned)a.nranges, (unsigned)(a.B * a.Hkv)), block(64 * (a.Hq / a.Hkv));
-  if (a.is_fp32) launch_timed(gather_estimate_kernel<true>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);
-  else launch_timed(gather_estimate_kernel<false>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);
+  if (a.is_fp32) launch_timed(gather_estimate_kernel<kFP32>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);
+  else if (a.kv_fp8) launch_timed(gather_estimate_kernel<kFP8>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);
+  else launch_timed(gather_estimate_kernel<kBF16>, grid, block, s, nullptr, ev ? ev[2] : nullptr, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   return launch_merge(a, heads, s, ev ? ev[4] : nullptr, ev ? ev[3] : nullptr);
 }

@@ -37,6 +37,7 @@ class Workload:
     min_hits: int = 2
     n_sink: int = 4
     n_local: int = 64
+    kv: str = ""      # storage type of the K / V cache when it differs from dtype: "fp8" (OCP e4m3)
 
     @property
     def group(self) -> int:
@@ -59,6 +60,8 @@ CONFIGS = {
 # The benchmark shape (C3) with the larger table sets of the paper's (K, L) study (App. E).
 CONFIGS["C3_K10_L220"] = Workload("C3_K10_L220", 1, 32, 8, 98304, 10, 220, "bf16", (32,))
 CONFIGS["C3_K11_L300"] = Workload("C3_K11_L300", 1, 32, 8, 98304, 11, 300, "bf16", (32,))
+# The benchmark shape with a quantised (e4m3) K / V cache (App. "Limitations and future work").
+CONFIGS["C3_fp8kv"] = Workload("C3_fp8kv", 1, 32, 8, 98304, 10, 150, "bf16", (32,), kv="fp8")
 
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
@@ -70,8 +73,21 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
     return rounded.view(np.float32)
 
 
+def round_to_e4m3(x: np.ndarray) -> np.ndarray:
+    """float32 -> nearest OCP e4m3 value (4 exponent bits, bias 7; 3 mantissa bits; subnormals in
+    steps of 2^-9; largest value 448, larger magnitudes are clamped to it; ties to even), as float32."""
+    x = np.clip(np.ascontiguousarray(x, dtype=np.float32), -448.0, 448.0)
+    mag = np.abs(x).astype(np.float64)
+    e = np.floor(np.log2(np.maximum(mag, 2.0 ** -20)))
+    step = 2.0 ** (np.maximum(e, -6.0) - 3.0)               # spacing of the values around |x|
+    y = np.minimum(np.rint(mag / step) * step, 448.0)
+    return (np.sign(x) * y).astype(np.float32)
+
+
 def store(x: np.ndarray, dtype: str) -> np.ndarray:
     x = np.ascontiguousarray(x, dtype=np.float32)
+    if dtype == "fp8":
+        return round_to_e4m3(x)
     return round_to_bf16(x) if dtype == "bf16" else x
 
 
@@ -94,7 +110,7 @@ def keys_values(wl: Workload, b: int, g: int, seed: int = 0):
     K = r.standard_normal((wl.n_ctx, wl.head_dim), dtype=np.float32)
     K += m
     V = r.standard_normal((wl.n_ctx, wl.head_dim), dtype=np.float32)
-    return store(K, wl.dtype), store(V, wl.dtype)
+    return store(K, wl.kv or wl.dtype), store(V, wl.kv or wl.dtype)
 
 
 def query(wl: Workload, b: int, h: int, K_g: np.ndarray, seed: int = 0,

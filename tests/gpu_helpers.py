@@ -16,6 +16,10 @@ def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
         t16 = t.to(torch.bfloat16)
         assert torch.equal(t16.to(torch.float32), t), "inputs must be bf16-representable"
         t = t16
+    elif dtype == "fp8":
+        t8 = t.to(torch.float8_e4m3fn)
+        assert torch.equal(t8.to(torch.float32), t), "inputs must be e4m3-representable"
+        t = t8
     return t.cuda()
 
 
@@ -39,7 +43,7 @@ class Session:
     """Device buffers of one problem instance."""
 
     def __init__(self, *, K, L, dtype, Kc, Vc, q, W, n_ctx=None, min_hits=2, n_sink=4, n_local=64,
-                 layout="dense", n_ctx_dev=None):
+                 layout="dense", n_ctx_dev=None, kv=""):
         """layout "dense": K and V caches [B, Hkv, n_cap, 128]; "token_major": both caches stored
         [B, n_cap, Hkv, row] with the heads of a token next to each other, K rows of 128 elements
         and V rows padded to 160, handed to the library through its stride arguments."""
@@ -49,12 +53,13 @@ class Session:
         self.n = n_cap if n_ctx is None else n_ctx
         self.dtype = dtype
         self._pkw = dict(batch=B, n_q_heads=self.Hq, n_kv_heads=Hkv, K=K, L=L, n_cap=n_cap, dtype=dtype,
-                         min_hits=min_hits, n_sink=n_sink, n_local=n_local, n_ctx_dev=n_ctx_dev)
-        self.Kc, self.Vc, self.q, self.W = (to_dev(x, dtype) for x in (Kc, Vc, q, W))
+                         min_hits=min_hits, n_sink=n_sink, n_local=n_local, n_ctx_dev=n_ctx_dev, kv_dtype=kv)
+        self.Kc, self.Vc = (to_dev(x, kv or dtype) for x in (Kc, Vc))     # kv = "fp8": caches of e4m3 bytes
+        self.q, self.W = (to_dev(x, dtype) for x in (q, W))
         if layout == "token_major":
             vrow = 160
             kt = self.Kc.permute(0, 2, 1, 3).contiguous()                       # [B, n_cap, Hkv, 128]
-            vt = torch.full((B, n_cap, Hkv, vrow), float("nan"), dtype=self.Vc.dtype, device="cuda")
+            vt = torch.full((B, n_cap, Hkv, vrow), float("nan"), dtype=torch.bfloat16, device="cuda").to(self.Vc.dtype)
             vt[..., :d] = self.Vc.permute(0, 2, 1, 3)
             self.Kc, self.Vc = kt, vt
             self._pkw["k_strides"] = (n_cap * Hkv * d, d, Hkv * d)
@@ -114,7 +119,7 @@ class Session:
         unit's part of the packed buffer."""
         torch.cuda.synchronize()
         one = mp.make_params(**{**self._pkw, "batch": 1, "n_kv_heads": 1, "n_q_heads": 1,
-                                "k_strides": None, "v_strides": None, "n_ctx_dev": None}, n_ctx=self.n)
+                                "k_strides": None, "v_strides": None, "n_ctx_dev": None, "kv_dtype": 0}, n_ctx=self.n)
         idx = mp.key_code_gather_index(one)[0, 0]                       # [n_cap, NW] inside the unit
         per_unit = (self.n_cap + 63) // 64 * 64 * self.NW
         u = b * self.Hkv + g

@@ -39,14 +39,14 @@ def run_case(oracle, w: wl.Workload, seed=0, alpha=0.8, use_mu=True, n_cap=None,
             for h in range(w.n_q_heads):
                 q[b, h] = wl.query(w, b, h, Kc[b, h // w.group], seed, alpha, center=mu[b, h // w.group])
     if n_cap is not None and n_cap > n:          # cache with spare capacity behind the context
-        pad = wl.store(np.random.default_rng(5).standard_normal((w.batch, w.n_kv_heads, n_cap - n, 128)), w.dtype)
+        pad = wl.store(np.random.default_rng(5).standard_normal((w.batch, w.n_kv_heads, n_cap - n, 128)), w.kv or w.dtype)
         Kc = np.concatenate([Kc, pad], axis=2)
         Vc = np.concatenate([Vc, pad], axis=2)
     ref = oracle.decode_step(q, Kc[:, :, :n], Vc[:, :, :n], W, w.K, w.L,
                              mu=mu if use_mu else np.zeros((w.batch, w.n_kv_heads, 128), np.float32),
                              min_hits=w.min_hits, n_sink=w.n_sink, n_local=w.n_local, heads=heads)
     s = Session(K=w.K, L=w.L, dtype=w.dtype, Kc=Kc, Vc=Vc, q=q, W=W, n_ctx=n,
-                min_hits=w.min_hits, n_sink=w.n_sink, n_local=w.n_local, layout=layout)
+                min_hits=w.min_hits, n_sink=w.n_sink, n_local=w.n_local, layout=layout, kv=w.kv)
     s.set_mu(mu)
     if check_key_mean:
         assert np.abs(s.key_mean() - oracle_mu(oracle, Kc, n)).max() <= 1e-5 * np.abs(Kc).max()
@@ -213,6 +213,28 @@ def test_token_major_cache_with_padded_value_rows(oracle):
         for g in range(2):
             ref = oracle.hash_keys(data["K"][b, g], data["W"], mu[b, g], w.K, w.L)
             np.testing.assert_array_equal(s.key_table_codes()[b, g], ref)
+
+
+def test_quantised_kv_cache(oracle):
+    # K and V caches of OCP e4m3 bytes (q and W bf16): every kernel that reads the caches decodes
+    # them; codes, counts, samples and outputs are those of the decoded values, which is what the
+    # oracle is given.  Llama-8B and 70B shapes, a ragged context, the token-major layout with
+    # padded V rows, a cache with spare capacity, keys appended behind tables, other thresholds.
+    run_case(oracle, wl.scaled(wl.CONFIGS["C2"], n_ctx=5003, kv="fp8"), check_key_mean=True, indexed=(2048,))
+    run_case(oracle, wl.scaled(wl.CONFIGS["C5"], batch=2, n_ctx=2500, kv="fp8"), oracle_codes_too=False)
+    run_case(oracle, wl.scaled(wl.CONFIGS["C2"], batch=2, n_ctx=1777, n_q_heads=8, n_kv_heads=2, kv="fp8"),
+             layout="token_major", check_key_mean=True, oracle_codes_too=False, indexed=(1024,))
+    run_case(oracle, wl.scaled(wl.CONFIGS["C4"], batch=1, n_ctx=1000, n_q_heads=8, n_kv_heads=2, kv="fp8", min_hits=3),
+             n_cap=1500, oracle_codes_too=False)
+    # generic (K, L) and all-zero keys (every projection re-evaluated; the list overflows: float64 fallback)
+    w = wl.Workload("gen8", 1, 4, 2, 700, 7, 65, "bf16", (8,), kv="fp8")
+    run_case(oracle, w, oracle_codes_too=False)
+    data = wl.generate(w)
+    Kz = np.zeros_like(data["K"])
+    s = Session(K=w.K, L=w.L, dtype="bf16", Kc=Kz, Vc=data["V"], q=data["q"], W=data["W"], kv="fp8")
+    s.hash_keys()
+    assert mp.hash_keys_stats(s.params, s.ws)["overflowed"]
+    np.testing.assert_array_equal(s.key_table_codes()[0, 0], oracle.hash_keys(Kz[0, 0], data["W"], None, w.K, w.L))
 
 
 @pytest.mark.parametrize("Hq,Hkv", [(24, 8), (6, 1), (5, 1), (7, 1)])

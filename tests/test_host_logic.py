@@ -40,8 +40,9 @@ def test_library_exports_nothing_but_the_declared_symbols():
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(mp.magicpig_params) == 10 * 4 + 8 * 8 + 8
+    assert ctypes.sizeof(mp.magicpig_params) == 10 * 4 + 8 * 8 + 8 + 8       # (kv_dtype and padding)
     assert mp.magicpig_params.n_ctx_dev.offset == 10 * 4 + 8 * 8
+    assert mp.magicpig_params.kv_dtype.offset == 10 * 4 + 8 * 8 + 8
 
 
 def test_sizes_and_paper_projector_size():
@@ -141,6 +142,8 @@ def test_argument_validation_without_a_gpu():
     assert hash_query(params(K=17)) == -2
     assert hash_query(params(L=513)) == -2
     assert hash_query(params(dtype=7)) == -2
+    assert hash_query(params(kv_dtype=5)) == -2
+    assert hash_query(params(dtype="fp32", kv_dtype="fp8")) == -2   # e4m3 caches go with bf16 queries and projector
     assert hash_query(params(n_q_heads=6, n_kv_heads=4)) == -1
     assert hash_query(params(n_q_heads=24, n_kv_heads=8, batch=0)) == 0   # group size 3 is fine (batch 0: nothing to launch)
     assert hash_query(params(n_q_heads=72, n_kv_heads=8)) == -2      # group size 9
