@@ -102,12 +102,17 @@ def cpu_baseline(w, data, seed):
         ctx = mpc.get_context("fork")
         global _CPU_JOB
         _CPU_JOB = (sub, mu, codes, w)
-        t0 = time.time()
         with ctx.Pool(nproc) as pool:
-            pool.map(_cpu_heads, chunks)
-        par_s = time.time() - t0
+            pool.map(_cpu_heads, [[] for _ in range(nproc)])     # workers started and warm (not timed)
+            reps = 5
+            t0 = time.time()
+            for _ in range(reps):
+                pool.map(_cpu_heads, chunks)
+            par_s = (time.time() - t0) / reps
         all_cores = {"value": len(heads) / par_s, "unit": "query-heads/s", "cores": nproc,
-                     "host_cores_available": ncores, "seconds": par_s}
+                     "host_cores_available": ncores, "seconds": par_s,
+                     "sample": f"the same decode step, its {len(heads)} heads dealt over {nproc} worker processes "
+                               f"(started beforehand), mean of {reps} passes"}
     except Exception as exc:  # noqa: BLE001
         all_cores = {"error": str(exc), "host_cores_available": ncores}
     return {
@@ -128,6 +133,8 @@ def _cpu_heads(heads):
     from oracle import magicpig_oracle as oracle
     from threadpoolctl import threadpool_limits
     sub, mu, codes, w = _CPU_JOB
+    if not heads:
+        return 0
     with threadpool_limits(limits=1):
         oracle.decode_step(sub["q"], sub["K"], sub["V"], sub["W"], w.K, w.L, mu=mu, min_hits=w.min_hits,
                            n_sink=w.n_sink, n_local=w.n_local, key_codes=codes, heads=heads)

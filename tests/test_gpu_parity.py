@@ -489,6 +489,40 @@ def test_hashing_from_the_prepared_projector(oracle, K, L):
                                       oracle.hash_keys(d32["K"][0, g], d32["W"], mu32[0, g], w32.K, w32.L))
 
 
+def test_matrix_core_key_hashing_on_adversarial_rows(oracle):
+    # rows chosen against the error bound of the matrix-core path: multiples of projector columns
+    # (Cauchy-Schwarz is tight: |k.W_j| = |k||W_j|), sums and differences of two columns, rows with
+    # huge cancelling terms next to small ones, and keys equal to the centering vector up to one
+    # element; with a large common mean, so that most of every projection cancels against mu.W_j
+    K, L, n = 10, 150, 1024
+    w = wl.Workload("adv", 1, 4, 1, n, K, L, "bf16", (8,))
+    W = wl.projector(w, 3)
+    rng = np.random.default_rng(17)
+    rows = np.zeros((n, 128), np.float64)
+    cols = rng.integers(0, K * L, size=(n, 2))
+    c = np.exp2(rng.integers(-6, 7, size=n)).astype(np.float64)
+    kind = np.arange(n) % 4
+    rows[kind == 0] = (c[:, None] * W[:, cols[:, 0]].T)[kind == 0]
+    rows[kind == 1] = (W[:, cols[:, 0]].T - W[:, cols[:, 1]].T)[kind == 1]
+    big = np.zeros((n, 128)); big[:, 0] = 2.0 ** 30; big[:, 1] = -2.0 ** 30; big[:, 2:] = rng.standard_normal((n, 126)) * 2.0 ** -8
+    rows[kind == 2] = big[kind == 2]
+    mean = 6.0 * rng.standard_normal(128)
+    rows[kind == 3] = mean + 2.0 ** -7 * rng.standard_normal((n, 128))[kind == 3]
+    Kc = wl.store(rows, "bf16")[None, None]
+    mu = wl.store(mean, "bf16").astype(np.float32)[None, None]
+    Kc[0, 0, 3::64] = mu[0, 0]                                       # exactly the centering vector: every projection is 0
+    for use_mu in (True, False):
+        s = Session(K=K, L=L, dtype="bf16", Kc=Kc, Vc=Kc, q=Kc[:, :, :4].reshape(1, 4, 128), W=W)
+        s.set_mu(mu if use_mu else None)
+        s.hash_keys()
+        st = mp.hash_keys_stats(s.params, s.ws)
+        print(f"   adversarial rows, centering {use_mu}: {st}", flush=True)
+        ref = oracle.hash_keys(Kc[0, 0], W, mu[0, 0] if use_mu else None, K, L)
+        np.testing.assert_array_equal(s.key_table_codes()[0, 0], ref)
+        s.hash_query()
+        np.testing.assert_array_equal(s.query_table_codes()[0], oracle.hash_query(Kc[0, 0, :4], W, K, L))
+
+
 def test_overflow_of_the_recheck_list_falls_back_to_the_float64_kernel(oracle):
     # all-zero keys: every matrix-core result is exactly zero, every projection is flagged,
     # the list overflows and the direct kernel must produce the codes (all ones: 0 >= 0)

@@ -209,6 +209,18 @@ def test_argument_validation_without_a_gpu():
     assert lib.magicpig_status_string(0) == b"ok"
 
 
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    # the boundary is a C ABI: a C99 program includes the header (pedantic, warnings are errors),
+    # links against the shared library and calls it without a GPU
+    import subprocess
+    exe = str(tmp_path / "use_from_c")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "c_abi", "use_from_c.c"), "-o", exe, mp.LIB_PATH,
+                    "-Wl,-rpath," + os.path.dirname(mp.LIB_PATH)], check=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout.split()
+    assert out[0] == "47" and int(out[1]) == mp.magicpig_workspace_bytes(params()) and "unsupported" in " ".join(out[2:])
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(mp, "_lib", None)
     monkeypatch.setattr(mp, "LIB_PATH", "/nonexistent/libmagicpig.so")
