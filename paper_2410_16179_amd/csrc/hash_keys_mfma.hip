@@ -51,6 +51,7 @@ __global__ __launch_bounds__(256) void prep_projector_kernel(HashMfmaArgs a) {
     *a.list_count = 0u;
     *a.overflow = 0;
     *a.flagged_total = 0u;
+    *a.wmax_bits = 0u;                                   // largest column norm: raised by the threshold kernel
   }
   const int row = gid >> 4, piece = gid & 15;        // row = T*32 + rho
   if (row >= a.ntiles * 32) return;
@@ -92,6 +93,8 @@ __global__ __launch_bounds__(256) void prep_threshold_kernel(HashMfmaArgs a) {
     a.munorm[unit] = (float)sqrt(ss) * 1.000001f;
   }
   if (row >= a.ntiles * 32) return;
+  // the largest column norm of the projector, once per call (non-negative floats order like integers)
+  if (unit == 0) atomicMax(a.wmax_bits, __float_as_uint(a.rownorm[row]));
   const int T = row >> 5, rho = row & 31;
   int x, beta;
   tile_row_to_bit(T, rho, &x, &beta);
@@ -218,20 +221,24 @@ __device__ inline void recheck_pairs(const HashMfmaArgs& a, long long* limb, uin
   }
 }
 
-// One quad of fragments (4 tiles x 8 k-steps x 64 lanes x 16 bytes = 32 KB), global -> LDS
+// One pair of tiles (2 tiles x 8 k-steps x 64 lanes x 16 bytes = 16 KB of fragments), global -> LDS
 // without passing through registers: lane l of a wavefront supplies the address of its 16
 // bytes, the hardware writes them to (wave-uniform LDS base) + 16 l.  The caller waits for
 // the vector-memory counter before the barrier that publishes the stage.
-__device__ inline void stage_quad(const uint4* gquad, uint4* stage, int tid, int wave) {
+__device__ inline void stage_pair(const uint4* gpair, uint4* stage, int tid, int wave) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+  for (int i = 0; i < 4; ++i)
     __builtin_amdgcn_global_load_lds(
-        (const __attribute__((address_space(1))) void*)(gquad + i * 256 + tid),
+        (const __attribute__((address_space(1))) void*)(gpair + i * 256 + tid),
         (__attribute__((address_space(3))) void*)(stage + i * 256 + wave * 64), 16, 0, 0);
 }
 
-__global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) {
-  __shared__ uint4 sA0[4 * 8 * 64], sA1[4 * 8 * 64];   // two stages of one word quad: 4 tiles x 8 k-steps
+// Three workgroups per compute unit: 152 registers, 46 KB of LDS (two 16 KB stages, the list).
+// With stages of four tiles (80 KB, two workgroups per compute unit) the kernel was 10 % slower:
+// a workgroup goes through its phases (load and norm the keys, sweep, queue, re-evaluate) one
+// after the other, and a third resident workgroup fills more of the gaps.
+__global__ __launch_bounds__(256, 3) void hash_keys_mfma_kernel(HashMfmaArgs a) {
+  __shared__ uint4 sA0[2 * 8 * 64], sA1[2 * 8 * 64];     // two stages of a tile pair: 2 tiles x 8 k-steps each
   __shared__ float sThr[2][4 * 2 * 16];
   __shared__ unsigned long long sList[kListCapLocal];
   __shared__ unsigned sCount;
@@ -249,7 +256,7 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
   const int nquads = a.ntiles / 4;                       // the fragment array holds whole quads
   const uint4* gA = reinterpret_cast<const uint4*>(a.afrag);
   const float* gThr = a.thr + (int64_t)unit * a.ntiles * 32;
-  stage_quad(gA, sA0, tid, wave);
+  stage_pair(gA, sA0, tid, wave);
   if (tid < 128) sThr[0][tid] = gThr[tid];
 
   // ---- B operand: my 64 keys, resident in registers for the whole kernel ----
@@ -277,18 +284,15 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
         B[bt][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(Kc + ubase + krow * a.stride_n + s * 16 + hh * 8));
     }
   }
-  // largest column norm of the projector (requested together with the keys)
-  __shared__ float sWmax[4];
-  {
-    float wm = 0.f;
-    for (int i = tid; i < a.ntiles * 32; i += 256) wm = fmaxf(wm, a.rownorm[i]);
-    wm = wave_max(wm);
-    if (lane == 0) sWmax[wave] = wm;
-  }
+  // largest column norm of the projector (from the threshold kernel; requested together with the keys)
+  const float wmax = __uint_as_float(*a.wmax_bits);
   const float munorm = a.munorm[unit];
   float knorm[2];
 #pragma unroll
   for (int bt = 0; bt < 2; ++bt) {
+    // |k|^2 by v_dot2_f32_bf16 (two exact products per instruction, float32 accumulation: the
+    // relative error of the norm, below 1e-5, is inside the margin of kGamma)
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
     float ss = 0.f;
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
@@ -296,20 +300,18 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
       const uint32_t u[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float lo = __uint_as_float(u[i] << 16), hi = __uint_as_float(u[i] & 0xffff0000u);
-        ss += lo * lo + hi * hi;
+        const bf16x2 v2 = __builtin_bit_cast(bf16x2, u[i]);
+        ss = __builtin_amdgcn_fdot2_f32_bf16(v2, v2, ss, false);
       }
     }
     ss += __shfl_xor(ss, 32);                            // the other half of the row
-    knorm[bt] = sqrtf(ss) * 1.000001f;
+    knorm[bt] = sqrtf(ss) * 1.00002f;
   }
 
   const int NW = a.NW;
   uint32_t* blk_codes = a.codes + ((int64_t)unit * a.blocks_cap + cb) * (kBlockKeys * (int64_t)NW);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  const float wmax = fmaxf(fmaxf(sWmax[0], sWmax[1]), fmaxf(sWmax[2], sWmax[3]));
-  if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *a.wmax_bits = __float_as_uint(wmax);   // statistics
   // flagged iff |acc| < bnd, bnd being just above the rigorous bound (so "<=" is covered)
 #pragma unroll
   for (int bt = 0; bt < 2; ++bt)
@@ -362,24 +364,33 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
     }
     if (x0 + 4 >= NQ && tail.nbits > 0) emit(tail_x, (uint32_t)tail.acc);   // last quad: the rest
   };
-  // One quad: 4 MFMA tiles (2 pairs = 4 code words) against the 64 keys of this wavefront.
-  auto do_quad = [&](int q, const uint4* sCur, uint4* sNext) {
+  // One quad: 4 MFMA tiles (2 pairs = 4 code words) against the 64 keys of this wavefront.  The
+  // fragments travel in stages of a pair: pair 2q sits in sA0 when the quad starts (published by
+  // the last barrier), pair 2q + 1 goes to sA1 while the first pair is multiplied, and the first
+  // pair of the next quad goes to sA0 while the second is.
+  auto do_quad = [&](int q) {
     const int cur = q & 1;
     const bool more = q + 1 < nquads;
     float stt = -INFINITY;
     if (q > 0) store_quad(q - 1);
-    if (more) {                                          // next quad travels while this one is used
-      stage_quad(gA + (int64_t)(q + 1) * 2048, sNext, tid, wave);
-      if (tid < 128) stt = gThr[(q + 1) * 128 + tid];
-    }
+    stage_pair(gA + ((int64_t)q * 2 + 1) * 1024, sA1, tid, wave);
+    if (more && tid < 128) stt = gThr[(q + 1) * 128 + tid];
 
-    if (wave_on) {
-      uint32_t wd[2][2];                                 // [pair][key tile] inverted bits, MSB first
-      uint32_t fl[2][2];                                 // same bit positions: |acc| <= bound
+    uint32_t wd[2][2];                                   // [pair][key tile] inverted bits, MSB first
+    uint32_t fl[2][2];                                   // same bit positions: |acc| <= bound
 #pragma unroll
-      for (int pair = 0; pair < 2; ++pair) {
-        wd[pair][0] = 0; wd[pair][1] = 0;
-        fl[pair][0] = 0; fl[pair][1] = 0;
+    for (int pair = 0; pair < 2; ++pair) {
+      wd[pair][0] = 0; wd[pair][1] = 0;
+      fl[pair][0] = 0; fl[pair][1] = 0;
+      if (pair == 1) {
+        // (every wavefront of the workgroup, working or not, passes here) the second pair has
+        // landed in sA1 and everybody is done with sA0: the first pair of the next quad may go there
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (more) stage_pair(gA + ((int64_t)q * 2 + 2) * 1024, sA0, tid, wave);
+      }
+      if (wave_on) {
+        const uint4* sTile = pair ? sA1 : sA0;
 #pragma unroll
         for (int tau = 0; tau < 2; ++tau) {
           const int tile = pair * 2 + tau;
@@ -392,7 +403,7 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
           f32x16 acc0 = c, acc1 = c;
 #pragma unroll
           for (int s = 0; s < 8; ++s) {
-            const bf16x8 af = __builtin_bit_cast(bf16x8, sCur[(tile * 8 + s) * 64 + lane]);
+            const bf16x8 af = __builtin_bit_cast(bf16x8, sTile[(tau * 8 + s) * 64 + lane]);
             acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, B[0][s], acc0, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, B[1][s], acc1, 0, 0, 0);
           }
@@ -410,6 +421,8 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
         wd[pair][0] = ~wd[pair][0];
         wd[pair][1] = ~wd[pair][1];
       }
+    }
+    if (wave_on) {
       // lanes < 32 hold words x0 (pair 0) and x0+2 (pair 1) of keys kap / 32+kap, lanes >= 32
       // hold x0+1 and x0+3: one half-swap per pair leaves lane l with the words of key l
       const auto s0 = __builtin_amdgcn_permlane32_swap(wd[0][0], wd[0][1], false, false);
@@ -451,10 +464,7 @@ __global__ __launch_bounds__(256, 2) void hash_keys_mfma_kernel(HashMfmaArgs a) 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the next stage has landed in LDS
     __syncthreads();
   };
-  for (int q = 0; q < nquads; q += 2) {
-    do_quad(q, sA0, sA1);
-    if (q + 1 < nquads) do_quad(q + 1, sA1, sA0);
-  }
+  for (int q = 0; q < nquads; ++q) do_quad(q);
   store_quad(nquads - 1);
 
   // ---- re-evaluate this workgroup's flagged pairs while its key rows are still in L2 ----
