@@ -70,7 +70,8 @@ typedef struct magicpig_params {
                          uses 2 (Sec. 4.3).  0: every eligible key is sampled with u = 1,
                          which makes the result exact attention. */
   int32_t n_sink;     /* first n_sink and last n_local keys form the static set T, attended */
-  int32_t n_local;    /* exactly and excluded from sampling (Sec. 4.4 "On-device cache")    */
+  int32_t n_local;    /* exactly and excluded from sampling (Sec. 4.4 "On-device cache");
+                         each 0 .. 2^30, else MAGICPIG_INVALID_ARG */
   int32_t dtype;      /* MAGICPIG_BF16 | MAGICPIG_FP32: element type of q, K, V, W */
   int64_t n_ctx;      /* keys per sequence seen by the decode step (all sequences alike)    */
   int64_t n_cap;      /* key capacity of the code buffer per (batch, KV head), >= n_ctx     */

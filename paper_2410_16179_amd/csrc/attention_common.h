@@ -58,9 +58,12 @@ __device__ inline float inclusion_probability(float cosv, const AttnArgs& a) {
   float t = __expf((float)L * lg);           // term j = 0
   float head = 0.f;
   if (tau <= kFastTau) {
-    for (int j = 0; j < tau; ++j) {
-      head += t;
-      t *= a.head_ratio[j] * r;
+#pragma unroll
+    for (int j = 0; j < kFastTau; ++j) {                   // (constant indices: the ratios are scalar operands)
+      if (j < tau) {
+        head += t;
+        t *= a.head_ratio[j] * r;
+      }
     }
     float s = 1.f;
 #pragma unroll
@@ -256,7 +259,8 @@ __device__ inline int64_t static_key(const AttnArgs& a, const Ctx& c, int64_t j)
 // s, s + slots, s + 2 slots, ... (at long contexts at most one each), which ride along in the
 // batch of its sampled keys instead of costing batches of their own.
 __device__ inline int static_share_of(int64_t n_static, int slot, int slots) {
-  return slot < n_static ? (int)((n_static - slot + slots - 1) / slots) : 0;
+  // (n_static <= n_sink + n_local, two 32-bit counts: a 32-bit division)
+  return slot < n_static ? (int)(((uint32_t)n_static - (uint32_t)slot + (uint32_t)slots - 1u) / (uint32_t)slots) : 0;
 }
 __device__ inline int static_share(const Ctx& c, int slot, int slots) {
   return static_share_of(c.n_static, slot, slots);
@@ -393,7 +397,7 @@ __device__ inline void gather_estimate_wave(const AttnArgs& a, int unit, int64_t
 #pragma unroll
     for (int it = 0; it < kIters; ++it) {
       if (it >= rounds) break;
-      const float wv = __shfl(wgt, (lane & 48) | it);
+      const float wv = row_bcast16(wgt, it);               // the weight of this quarter wavefront's row
       float vv[8];
       frag_to_float<ET>(vf[it], vv);
 #pragma unroll

@@ -123,6 +123,22 @@ __device__ inline float row_sum16(float v) {
   return v;
 }
 
+// Lane n (0 .. 15) of every row of 16 lanes, in all lanes of that row.
+template <int N>
+__device__ inline float dpp_row_bcast(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x150 + N, 0xf, 0xf, false));
+}
+__device__ inline float row_bcast16(float v, int n) {      // n: a constant after unrolling
+  switch (n) {
+    case 0: return dpp_row_bcast<0>(v);   case 1: return dpp_row_bcast<1>(v);   case 2: return dpp_row_bcast<2>(v);
+    case 3: return dpp_row_bcast<3>(v);   case 4: return dpp_row_bcast<4>(v);   case 5: return dpp_row_bcast<5>(v);
+    case 6: return dpp_row_bcast<6>(v);   case 7: return dpp_row_bcast<7>(v);   case 8: return dpp_row_bcast<8>(v);
+    case 9: return dpp_row_bcast<9>(v);   case 10: return dpp_row_bcast<10>(v); case 11: return dpp_row_bcast<11>(v);
+    case 12: return dpp_row_bcast<12>(v); case 13: return dpp_row_bcast<13>(v); case 14: return dpp_row_bcast<14>(v);
+    default: return dpp_row_bcast<15>(v);
+  }
+}
+
 template <int N>
 __device__ inline float dpp_row_ror_keep(float v) {
   const int r = __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, v), __builtin_bit_cast(int, v), 0x120 + N, 0xf, 0xf, false);

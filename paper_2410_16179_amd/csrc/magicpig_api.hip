@@ -52,6 +52,7 @@ int check_params(const magicpig_params* p) {
   if (p->n_q_heads % p->n_kv_heads != 0) return MAGICPIG_INVALID_ARG;
   if (p->n_ctx < 0 || p->n_cap < p->n_ctx) return MAGICPIG_INVALID_ARG;
   if (p->n_sink < 0 || p->n_local < 0 || p->min_hits < 0) return MAGICPIG_INVALID_ARG;
+  if (p->n_sink > (1 << 30) || p->n_local > (1 << 30)) return MAGICPIG_INVALID_ARG;   // their sum is handled in 32 bits
   if (p->head_dim != mp::kHeadDim) return MAGICPIG_UNSUPPORTED;
   if (p->K < 1 || p->K > 16 || p->L < 1 || p->L > 512) return MAGICPIG_UNSUPPORTED;
   if (p->dtype != MAGICPIG_BF16 && p->dtype != MAGICPIG_FP32) return MAGICPIG_UNSUPPORTED;
@@ -117,7 +118,7 @@ size_t ws_hash_for(const magicpig_params* p, int64_t n_keys) {
 }
 
 // decode workspace: [partials | ballots]
-struct AttnWs { size_t partial_off, masks_off, total; int nranges, nscan, f_nranges, f_wave_blocks; int64_t n_static; };
+struct AttnWs { size_t partial_off, masks_off, total; int nranges, nscan, f_nranges, f_wave_blocks, f_touch; int64_t n_static; };
 AttnWs ws_attention_layout(const magicpig_params* p) {
   AttnWs w{};
   const int64_t nblk = mp::key_blocks(p->n_ctx);
@@ -132,13 +133,15 @@ AttnWs ws_attention_layout(const magicpig_params* p) {
   // start late and end last (measured at 8 KV heads: 100000 keys 48.6 -> 44.8 us per step, 65536
   // keys 36.1 -> 33.7, 32768 keys 27.4 -> 23.9 against runs of 16, 8 or 4 blocks chosen to fill
   // the chip at least once).  When even the longest runs do not fit (large batches) the rounds
-  // are many anyway: 16 blocks.
+  // are many anyway: the longest runs, 24 blocks (fewer partials; batch 16 x 65536 keys: 275 ->
+  // 272.5 us against 16 blocks), and the wavefronts touch the rows of their last block early.
   const int64_t units = (int64_t)p->batch * p->n_kv_heads;
   auto groups = [&](int wb) { return units * ((nblk + 4 * wb - 1) / (4 * wb)); };
   const int64_t fits = mp::kFusedFill + mp::kFusedFill / 64;   // 780: a dozen late workgroups cost less than longer runs
   w.f_wave_blocks = 1;
   while (w.f_wave_blocks < mp::kFusedWaveBlocks && groups(w.f_wave_blocks) > fits) ++w.f_wave_blocks;
-  if (groups(w.f_wave_blocks) > fits) w.f_wave_blocks = 4;
+  w.f_touch = 0;
+  if (groups(w.f_wave_blocks) > fits) { w.f_wave_blocks = mp::kFusedWaveBlocks; w.f_touch = 1; }
   w.f_nranges = (int)((nblk + 4 * w.f_wave_blocks - 1) / (4 * w.f_wave_blocks));
   // lookup + gather in one launch: 16 partials per slice
   const int lg = (int)((nblk + mp::kLgSliceBlocks - 1) / mp::kLgSliceBlocks) * 16;
@@ -304,7 +307,7 @@ int run_attention_impl(const magicpig_params* p, const void* q, const void* K_ca
   a.partial = reinterpret_cast<float*>(wsb + wl.partial_off); a.out = out;
   a.masks = reinterpret_cast<uint64_t*>(wsb + wl.masks_off);
   a.nranges = wl.nranges; a.nscan = wl.nscan; a.n_static = wl.n_static;
-  a.f_nranges = wl.f_nranges; a.f_wave_blocks = wl.f_wave_blocks;
+  a.f_nranges = wl.f_nranges; a.f_wave_blocks = wl.f_wave_blocks; a.f_touch = wl.f_touch;
   a.dbg_counts = dbg_counts; a.dbg_cand = dbg_cand; a.dbg_ncand = dbg_ncand; a.dbg_cand_cap = dbg_cand_cap;
   a.dbg_stride = p->n_ctx; a.n_dev = p->n_ctx_dev;
   a.is_fp32 = p->dtype == MAGICPIG_FP32;

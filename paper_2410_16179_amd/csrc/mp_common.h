@@ -203,6 +203,7 @@ struct AttnArgs {
   // scan and gather in one launch: one workgroup, and one partial per head, for every run of
   // 4 * f_wave_blocks key blocks (f_wave_blocks: key blocks per wavefront, 1 .. kFusedWaveBlocks)
   int f_nranges, f_wave_blocks;
+  int f_touch;               // 1: its workgroups come in several rounds (wavefronts touch the rows of the keys of their last block)
   // lookup + gather in one launch: slices of the indexed range; the first lg_app_runs of them
   // also take a run of 16 appended key blocks each
   int lg_nslices, lg_app_runs;

@@ -17,10 +17,11 @@
 //   static set with count >= min_hits are reported as one 64-bit ballot per (head, block).
 //   No LDS, no barrier, about 60 VGPRs.
 // gather and estimate (gather_estimate_wave)
-//   One wavefront per (query head, run of key blocks): the ballots are expanded into an
-//   index list in LDS by a wavefront prefix sum (the static sink and local-window keys ride
+//   One wavefront per (query head, run of key blocks): the sampled keys are an index list in
+//   LDS (gather_estimate_kernel expands the ballots by a wavefront prefix sum; scan_gather_kernel
+//   appends to the list while it compares); the static sink and local-window keys ride
 //   along in these batches, or, in gather_estimate_kernel, are taken 32 each by wavefronts of
-//   their own); rows are gathered four at a time (a quarter wavefront holds one 128-element row)
+//   their own; rows are gathered four at a time (a quarter wavefront holds one 128-element row)
 //   with up to 32 K rows and 32 V rows in flight; q.k, q.(k-mu), |k-mu|^2 are reduced over
 //   the 16 lanes of a row, the inclusion probability u_i and the logit q.k/sqrt(d) - log u_i
 //   are evaluated once per candidate, and an online max/sum softmax accumulates the weighted
@@ -119,8 +120,9 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
 
 // Scan and gather in one launch (the whole context is scanned, no hash tables): a workgroup of
 // four wavefronts compares a run of up to kFusedBlocks = 24 consecutive code blocks with the G
-// heads' codes (scan_blocks, f_wave_blocks blocks per wavefront one after the other), leaves the
-// ballots in LDS, and wavefront h then gathers and weighs the keys that head h samples from the
+// heads' codes (scan_blocks, f_wave_blocks blocks per wavefront one after the other), appends
+// the keys each head samples to that head's list in LDS as it goes, and wavefront h then gathers
+// and weighs the keys that head h samples from the
 // run (16 blocks: about 17 at a sampling rate of 1.6 %, one batch of the 32-row gather).  As
 // separate launches the gather follows the scan with two dependent round trips of its own
 // (ballots, then rows) on an idle memory system; here the rows of one workgroup travel while
@@ -128,8 +130,11 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
 // (measured at 32 heads x 98304 keys: 33 us against 25.6 + 13.7 us).  The host picks the run
 // length, 4 to 24 blocks: the shortest whose workgroups are all resident at once (16 blocks at
 // that shape).  Shorter runs measured the same kernel time there but cost more partials and
-// gather batches; the 143 registers of this form (three wavefronts per SIMD) measured faster
-// than the same kernel held to 128.
+// gather batches.  What remains exposed there, after the last block of codes has arrived
+// (time stamps): 0.7 us until the four wavefronts meet, 0.6 us candidate positions and row
+// addresses, 1.6 us for the rows, 1.3 us estimator, 0.7 us weighted V rows and the partial;
+// until then the kernel moves its bytes at the rate of a plain read of the same codes.
+// OCC: workgroups per compute unit the kernel is compiled for (see launch_scan_gather_as).
 // The grid is one workgroup per run (at 8 KV heads x 98304 keys: 768, exactly what is resident
 // at once; workgroups that start late end last).  The keys of the static set T are dealt over
 // the runs of their KV head (key j to run j mod runs) and join the gather batches there, so
@@ -137,12 +142,16 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
 // One partial per (head, run).
 // DBG: with the debug outputs (counts, candidate lists).
 // ET: element type of the caches (kBF16, kFP32, or kFP8 with bf16 queries).
-template <int KT, int WDT, int LT, int ET, bool DBG>
-__global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
+template <int KT, int WDT, int LT, int ET, bool DBG, int OCC>
+__global__ __launch_bounds__(256, OCC) void scan_gather_kernel(AttnArgs a) {
   constexpr bool FP32 = ET == kFP32;
   constexpr int kIt = FP32 ? (kFusedIters + 1) / 2 : kFusedIters;   // the same registers per batch
-  __shared__ uint64_t smask[8][kFusedBlocks];
-  __shared__ uint16_t lists[4][kFusedBlocks * kBlockKeys];
+  constexpr int kSeg = kFusedWaveBlocks * kBlockKeys;      // most keys one wavefront can report for a head
+  // seg[h][w]: the keys of the run that head h samples among the blocks of wavefront w, in key
+  // order (position in the run, 11 bits); seg_n[h][w]: how many.  Written while the blocks are
+  // compared, so that nothing but the row gather is left to do after the last block.
+  __shared__ uint16_t seg[8][4][kSeg];
+  __shared__ int seg_n[8][4];
   const Ctx c = resolve_context(a);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int unit = blockIdx.y, run = blockIdx.x;
@@ -153,18 +162,24 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
   const int wave_blocks = a.f_wave_blocks;                 // 1 .. kFusedWaveBlocks key blocks per wavefront
   const int run_blocks = 4 * wave_blocks;
   const int64_t blk0 = (int64_t)run * run_blocks;
+  int found = 0;                                           // lane h: keys of head h found so far by this wavefront
+  uint64_t last_found = 0;                                 // keys of the wavefront's last block that some head samples
 #pragma unroll 1
   for (int j = 0; j < wave_blocks; ++j) {
     const int bi = wave * wave_blocks + j;
     if (blk0 + bi < nblk) {
       scan_blocks<KT, WDT, LT, 1, DBG>(a, c, unit, blk0 + bi, lane, 0, G, [&](int h, int64_t, uint64_t m) {
-        if (lane == 0) smask[h][bi] = m;
+        if (m) {                                           // (wave-uniform)
+          const int at = __builtin_amdgcn_readlane(found, h);
+          const int below = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
+          if ((m >> lane) & 1) seg[h][wave][at + below] = (uint16_t)(bi * kBlockKeys + lane);
+          if (lane == h) found = at + __popcll(m);
+        }
+        if (j == wave_blocks - 1) last_found |= m;
       });
-    } else if (lane < G) {
-      smask[lane][bi] = 0;
     }
   }
-  __syncthreads();
+  if (lane < G) seg_n[lane][wave] = found;
   // The gather reads its arguments from the kernel argument segment again, through a pointer the
   // compiler cannot trace back: otherwise it loads them all at the start of the kernel and keeps
   // them in scalar registers across the scan, whose query words then no longer fit (50 spills,
@@ -173,40 +188,66 @@ __global__ __launch_bounds__(256, 3) void scan_gather_kernel(AttnArgs a) {
   const_args_ptr kp = (const_args_ptr)__builtin_amdgcn_kernarg_segment_ptr();
   asm volatile("" : "+s"(kp));
   const AttnArgs& ga = *(const AttnArgs*)kp;
-  uint16_t* list = lists[wave];
+  // ... and all of them here, in one batch of scalar loads that is back before the barrier opens
+  // (requested where they are used they cost four dependent round trips at the end of the kernel)
+  asm volatile("" ::"s"(ga.q), "s"(ga.Kc), "s"(ga.Vc), "s"(ga.mu), "s"(ga.partial), "s"(ga.Hq), "s"(ga.Hkv), "s"(ga.K), "s"(ga.L),
+               "s"(ga.tau), "s"(ga.n_sink), "s"(ga.n_local), "s"(ga.ks_b), "s"(ga.ks_h), "s"(ga.ks_n), "s"(ga.vs_b), "s"(ga.vs_h),
+               "s"(ga.vs_n), "s"(ga.f_nranges), "s"(ga.f_touch), "s"(ga.scale));
+  asm volatile("" ::"s"(ga.head_ratio[0]), "s"(ga.head_ratio[1]), "s"(ga.head_ratio[2]), "s"(ga.head_ratio[3]), "s"(ga.tail_ratio[0]),
+               "s"(ga.tail_ratio[1]), "s"(ga.tail_ratio[2]), "s"(ga.tail_ratio[3]), "s"(ga.tail_ratio[4]), "s"(ga.tail_ratio[5]),
+               "s"(ga.tail_ratio[6]), "s"(ga.tail_ratio[7]), "s"(ga.tail_ratio[8]), "s"(ga.tail_ratio[9]), "s"(ga.tail_ratio[10]),
+               "s"(ga.tail_ratio[11]), "s"(ga.tail_ratio[12]), "s"(ga.tail_ratio[13]), "s"(ga.tail_ratio[14]), "s"(ga.tail_ratio[15]));
+  static_assert(kFastTau == 4 && kTailTerms == 16, "the list above names every ratio");
+  // When the workgroups of a launch come in several rounds the memory system is busy whenever one
+  // of them reaches its gather, and its rows then take as long as a block of codes.  The rows of
+  // the keys found in the last block are requested last of all (block compared, barrier, candidate
+  // positions, only then the request): a wavefront touches one word of each of their cache lines
+  // here already, so that the gather finds them in, or on their way to, the L2 (measured at batch
+  // 16 x 65536 keys: 284 -> 276 us; with all workgroups resident at once it costs half a
+  // microsecond instead, and touching the rows of every block costs 10 %).  The touches are
+  // loads with a destination, consumed at the end of the kernel; the barrier does not wait for them.
+  constexpr int kLines = ET == kFP32 ? 4 : (ET == kFP8 ? 1 : 2);            // 128-byte lines per row
+  uint32_t touched[2 * kLines];
+#pragma unroll
+  for (int l = 0; l < 2 * kLines; ++l) touched[l] = 0;
+  if (ga.f_touch && ((last_found >> lane) & 1)) {
+    const int64_t key = (blk0 + wave * wave_blocks + wave_blocks - 1) * kBlockKeys + lane;
+    const int b = unit / ga.Hkv, g = unit % ga.Hkv;
+    const char* kr = (const char*)ga.Kc + ((int64_t)b * ga.ks_b + (int64_t)g * ga.ks_h + key * ga.ks_n) * (kLines * 128 / kHeadDim);
+    const char* vr = (const char*)ga.Vc + ((int64_t)b * ga.vs_b + (int64_t)g * ga.vs_h + key * ga.vs_n) * (kLines * 128 / kHeadDim);
+#pragma unroll
+    for (int l = 0; l < kLines; ++l) {
+      touched[2 * l] = *reinterpret_cast<const uint32_t*>(kr + 128 * l);
+      touched[2 * l + 1] = *reinterpret_cast<const uint32_t*>(vr + 128 * l);
+    }
+  }
+  // (the barrier orders the LDS writes above: it waits for them, not for loads in flight)
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
   for (int h = wave; h < G; h += 4) {
     HeadVectors<FP32> hv;
     request_head_vectors<FP32>(ga, unit, head0 + h, hv);
-    // ---- the ballots of head h as an index list (wavefront prefix sum) ----
-    uint64_t m = lane < run_blocks ? smask[h][lane] : 0;
-    const int pc = __popcll(m);
-    int incl = pc;
-    static_assert(kFusedBlocks <= 32, "the ballots of a run are summed over 32 lanes");
-#pragma unroll
-    for (int o = 1; o < 32; o <<= 1) {
-      const int v = __shfl_up(incl, o);
-      if (lane >= o) incl += v;
-    }
-    const int total = __shfl(incl, 31);
-    int pos = incl - pc;
-    while (m) {
-      const int bit = __ffsll((unsigned long long)m) - 1;
-      list[pos++] = (uint16_t)(lane * kBlockKeys + bit);
-      m &= m - 1;
-    }
-    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-    __builtin_amdgcn_wave_barrier();
+    // the four wavefronts' keys of head h, one after the other: candidate cc is entry cc - s_w of
+    // the last wavefront w whose first candidate s_w is not beyond cc
+    const int s1 = __builtin_amdgcn_readfirstlane(seg_n[h][0]);
+    const int s2 = s1 + __builtin_amdgcn_readfirstlane(seg_n[h][1]);
+    const int s3 = s2 + __builtin_amdgcn_readfirstlane(seg_n[h][2]);
+    const int total = s3 + __builtin_amdgcn_readfirstlane(seg_n[h][3]);
+    const uint16_t* segh = &seg[h][0][0];
     // static keys run, run + nruns, ... ride along behind the sampled ones
     const int nst = static_share(c, run, nruns);
     gather_estimate_wave<ET, kIt>(ga, unit, head0 + h, total + nst, total, hv,
                                     [&](int cc) {
-                                      return cc < total ? blk0 * kBlockKeys + (int64_t)list[cc]
-                                                        : static_key(ga, c, run + (int64_t)(cc - total) * nruns);
+                                      if (cc >= total) return static_key(ga, c, run + (int64_t)(cc - total) * nruns);
+                                      const int w = (cc >= s1) + (cc >= s2) + (cc >= s3);
+                                      const int first = w == 0 ? 0 : (w == 1 ? s1 : (w == 2 ? s2 : s3));
+                                      return blk0 * kBlockKeys + (int64_t)segh[w * kSeg + cc - first];
                                     },
                                     ga.partial + ((head0 + h) * ga.f_nranges + run) * kPartialStride);
-    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-    __builtin_amdgcn_wave_barrier();
   }
+#pragma unroll
+  for (int l = 0; l < 2 * kLines; ++l) asm volatile("" ::"v"(touched[l]));
 }
 
 // Merges the (max, sum, output) partials of one query head (NWAVES wavefronts: wavefront w takes
@@ -311,19 +352,30 @@ static hipError_t launch_merge(const AttnArgs& a, int64_t heads, hipStream_t s, 
   return hipGetLastError();
 }
 
+// Workgroups per compute unit the kernel is compiled for: three (up to 168 registers) when the
+// whole grid is resident at once - there the fourth could not be used, and the looser register
+// allocation measured 0.4 us faster at 32 heads x 98304 keys - and four (128 registers) when the
+// workgroups come in several rounds (batch 16 x 65536 keys: 283 against 285 us, and 275 with the
+// early touches, which only pay at that occupancy).
+template <int KT, int WDT, int LT, int ET, bool DBG>
+static void launch_scan_gather_as(const AttnArgs& a, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
+  const dim3 block(256);
+  if (a.f_touch) launch_timed(scan_gather_kernel<KT, WDT, LT, ET, DBG, 4>, grid, block, s, start, stop, a);
+  else launch_timed(scan_gather_kernel<KT, WDT, LT, ET, DBG, 3>, grid, block, s, start, stop, a);
+}
+
 template <int KT, int WDT, int LT>
 static void launch_scan_gather_for(const AttnArgs& a, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop) {
-  const dim3 block(256);
   const bool dbg = a.dbg_counts || a.dbg_cand;
   if (a.is_fp32) {
-    if (dbg) launch_timed(scan_gather_kernel<KT, WDT, LT, kFP32, true>, grid, block, s, start, stop, a);
-    else launch_timed(scan_gather_kernel<KT, WDT, LT, kFP32, false>, grid, block, s, start, stop, a);
+    if (dbg) launch_scan_gather_as<KT, WDT, LT, kFP32, true>(a, grid, s, start, stop);
+    else launch_scan_gather_as<KT, WDT, LT, kFP32, false>(a, grid, s, start, stop);
   } else if (a.kv_fp8) {
-    if (dbg) launch_timed(scan_gather_kernel<KT, WDT, LT, kFP8, true>, grid, block, s, start, stop, a);
-    else launch_timed(scan_gather_kernel<KT, WDT, LT, kFP8, false>, grid, block, s, start, stop, a);
+    if (dbg) launch_scan_gather_as<KT, WDT, LT, kFP8, true>(a, grid, s, start, stop);
+    else launch_scan_gather_as<KT, WDT, LT, kFP8, false>(a, grid, s, start, stop);
   } else {
-    if (dbg) launch_timed(scan_gather_kernel<KT, WDT, LT, kBF16, true>, grid, block, s, start, stop, a);
-    else launch_timed(scan_gather_kernel<KT, WDT, LT, kBF16, false>, grid, block, s, start, stop, a);
+    if (dbg) launch_scan_gather_as<KT, WDT, LT, kBF16, true>(a, grid, s, start, stop);
+    else launch_scan_gather_as<KT, WDT, LT, kBF16, false>(a, grid, s, start, stop);
   }
 }
 
