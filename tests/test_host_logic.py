@@ -149,6 +149,8 @@ def test_argument_validation_without_a_gpu():
     assert hash_query(params(n_q_heads=72, n_kv_heads=8)) == -2      # group size 9
     assert hash_query(params(batch=4097, n_q_heads=32, n_kv_heads=8)) == -2   # more query vectors than one launch takes
     assert hash_query(params(n_ctx=100, n_cap=50)) == -1
+    assert hash_query(params(n_local=(1 << 30) + 1)) == -1           # static-set sizes beyond 2^30
+    assert hash_query(params(n_sink=-1)) == -1
     assert hash_query(params(), W=None) == -1
     assert hash_query(params(), q=ctypes.c_void_p(wsp + 2)) == -1     # misaligned
     p = params()
