@@ -123,6 +123,21 @@ __device__ inline float row_sum16(float v) {
   return v;
 }
 
+// Inclusive prefix sums over the lanes of every row of 16 lanes (row shifts, zeros shifted in), and
+// over lanes 0 .. 31 and 32 .. 63 (the total of an even row joins the row behind it).
+__device__ inline int row_prefix_sum16(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);
+  return v;
+}
+__device__ inline int half_prefix_sum32(int v) {
+  v = row_prefix_sum16(v);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // lane 15 of rows 0 and 2 to rows 1 and 3
+  return v;
+}
+
 // Lane n (0 .. 15) of every row of 16 lanes, in all lanes of that row.
 template <int N>
 __device__ inline float dpp_row_bcast(float v) {

@@ -522,13 +522,12 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
       const uint32_t rel = e[j] - key_lo;
       if (2 * j < nbk && rel < kSliceKeys && ((before[j] >> (rel & 31)) & 1u)) atomicOr(&twice[rel >> 5], 1u << (rel & 31));
     }
-#pragma unroll 1
-    for (int k = 0; k < nbk; ++k) {
-      const uint32_t len = __shfl(my_len, k);
-      if (len > 32) {
-        const uint32_t* p = idxs + (int64_t)(wave + 16 * k) * tb.n_cap + __shfl(my_start, k);
-        for (uint32_t j = 32 + lane; j < len; j += 64) mark(p[j]);
-      }
+    // (rare: the wavefront knows at once whether any of its pieces is that long)
+    for (uint64_t f = __ballot(my_len > 32); f; f &= f - 1) {
+      const int k = __ffsll((unsigned long long)f) - 1;
+      const uint32_t len = __builtin_amdgcn_readlane(my_len, k);
+      const uint32_t* p = idxs + (int64_t)(wave + 16 * k) * tb.n_cap + __builtin_amdgcn_readlane(my_start, k);
+      for (uint32_t j = 32 + lane; j < len; j += 64) mark(p[j]);
     }
   } else {
     // Buckets in no particular order: up to 128 entries of each bucket are requested before any
@@ -564,13 +563,11 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
         }
       }
     }
-#pragma unroll 1
-    for (int k = 0; k < nbk; ++k) {
-      const uint32_t len = __shfl(my_len, k);
-      if (len > 128) {
-        const uint32_t* p = idxs + (int64_t)(wave + 16 * k) * tb.n_cap + __shfl(my_start, k);
-        for (uint32_t j = 128 + lane; j < len; j += 64) mark(p[j]);
-      }
+    for (uint64_t f = __ballot(my_len > 128); f; f &= f - 1) {
+      const int k = __ffsll((unsigned long long)f) - 1;
+      const uint32_t len = __builtin_amdgcn_readlane(my_len, k);
+      const uint32_t* p = idxs + (int64_t)(wave + 16 * k) * tb.n_cap + __builtin_amdgcn_readlane(my_start, k);
+      for (uint32_t j = 128 + lane; j < len; j += 64) mark(p[j]);
     }
   }
   __syncthreads();
@@ -598,13 +595,8 @@ __global__ __launch_bounds__(1024) void lookup_gather_kernel(AttnArgs a, TableAr
     }
   }
   const int c = __popc(bits);
-  int incl = c;
-#pragma unroll
-  for (int o = 1; o < 32; o <<= 1) {
-    const int v = __shfl_up(incl, o);
-    if (lane >= o) incl += v;
-  }
-  const int in_slice = __shfl(incl, 31);                 // kWaveWords <= 32
+  const int incl = half_prefix_sum32(c);                 // kWaveWords <= 32
+  const int in_slice = __builtin_amdgcn_readlane(incl, 31);
   int pos = incl - c;
   for (uint32_t f = bits; f; f &= f - 1) list[pos++] = (uint16_t)(lane * 32 + __ffs(f) - 1);
   // behind them the sampled keys of the wavefront's appended block (lane = key of the block)

@@ -88,13 +88,9 @@ __global__ __launch_bounds__(512) void gather_estimate_kernel(AttnArgs a) {
     uint64_t m = 0;
     if (lane < kRangeBlocks && blk0 + lane < nblk) m = a.masks[bh * nblk + blk0 + lane];
     const int pc = __popcll(m);
-    int incl = pc;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int v = __shfl_up(incl, o);
-      if (lane >= o) incl += v;
-    }
-    total = __shfl(incl, 63);
+    static_assert(kRangeBlocks <= 16, "the ballots of a range are summed over one row of 16 lanes");
+    const int incl = row_prefix_sum16(pc);
+    total = __builtin_amdgcn_readlane(incl, kRangeBlocks - 1);
     int pos = incl - pc;
     while (m) {
       const int bit = __ffsll((unsigned long long)m) - 1;
