@@ -401,11 +401,18 @@ __global__ __launch_bounds__(256, 3) void hash_keys_mfma_kernel(HashMfmaArgs a) 
             c[v4 * 4] = t4.x; c[v4 * 4 + 1] = t4.y; c[v4 * 4 + 2] = t4.z; c[v4 * 4 + 3] = t4.w;
           }
           f32x16 acc0 = c, acc1 = c;
+          // the A fragment of k-step s + 2 is requested from LDS before the MFMAs of step s are
+          // issued (left to itself the compiler emits read, wait, two MFMAs, read, wait, ...)
+          bf16x8 ring[3];
+          ring[0] = __builtin_bit_cast(bf16x8, sTile[(tau * 8) * 64 + lane]);
+          ring[1] = __builtin_bit_cast(bf16x8, sTile[(tau * 8 + 1) * 64 + lane]);
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int s = 0; s < 8; ++s) {
-            const bf16x8 af = __builtin_bit_cast(bf16x8, sTile[(tau * 8 + s) * 64 + lane]);
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, B[0][s], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, B[1][s], acc1, 0, 0, 0);
+            if (s + 2 < 8) ring[(s + 2) % 3] = __builtin_bit_cast(bf16x8, sTile[(tau * 8 + s + 2) * 64 + lane]);
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[s % 3], B[0][s], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[s % 3], B[1][s], acc1, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
           }
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
