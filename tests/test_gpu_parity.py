@@ -237,6 +237,21 @@ def test_quantised_kv_cache(oracle):
     np.testing.assert_array_equal(s.key_table_codes()[0, 0], oracle.hash_keys(Kz[0, 0], data["W"], None, w.K, w.L))
 
 
+@pytest.mark.parametrize("base,changes", [("C4", dict(n_ctx=11003, kv="fp8")), ("C4", dict(n_ctx=11003, dtype="fp32")),
+                                          ("C5", dict(n_ctx=20011))])
+def test_several_rounds_of_workgroups_other_element_types(oracle, base, changes):
+    # Batches whose scan + gather grid does not fit the chip at once at a moderate context: runs of
+    # 24 key blocks, the instantiation for four workgroups per compute unit, the early touches of
+    # the rows of a wavefront's last block - here with e4m3 caches, with float32 inputs, and with
+    # groups of eight query heads; a ragged context; heads of the first, a middle and the last
+    # sequence against the oracle, every head finite.
+    w = wl.scaled(wl.CONFIGS[base], **changes)
+    B, Hq = w.batch, w.n_q_heads
+    heads = [(0, 0), (0, Hq - 1), (B // 2, Hq // 2 + 1), (B - 1, 2), (B - 1, Hq - 1)]
+    ref, res, worst = run_case(oracle, w, heads=heads, oracle_codes_too=False)
+    assert np.isfinite(res["out"]).all() and np.abs(res["out"]).max() < 6.0
+
+
 @pytest.mark.parametrize("Hq,Hkv", [(24, 8), (6, 1), (5, 1), (7, 1)])
 def test_group_sizes_that_are_not_powers_of_two(oracle, Hq, Hkv):
     w = wl.scaled(wl.CONFIGS["C2"], n_ctx=2100, n_q_heads=Hq, n_kv_heads=Hkv)
